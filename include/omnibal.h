@@ -1,0 +1,170 @@
+/*
+ * omnibal.h -- C ABI of the MI355X (gfx950) hot path behind OmniBal-style balanced VLM training:
+ * forward + backward of pre-norm transformer blocks over ONE packed, padding-free,
+ * variable-length mini-batch, plus the host-side balanced grouping that produces the batch.
+ *
+ * What the paper fixes: samples stay whole and a mini-batch carries no padding (Sec. 3 "Data
+ * Imbalance"; Sec. 4.1; Table 3, ISF row: PadRatio 0), the grouping algorithm (Alg. 1) and its
+ * metrics (Eq. 1, Eq. 2).  The block arithmetic is the textbook pre-norm transformer block:
+ *     x1 = x  + Attn(N1(x)) W_o^T (+ b_o)        y = x1 + MLP(N2(x1))
+ * with attention confined to each segment of the packed batch: one ViT image tile (bidirectional)
+ * or one LLM sample (causal), rotary positions restarting at 0 in every segment.
+ *
+ * Conventions for every device entry point
+ *   - All tensor pointers are DEVICE pointers unless the name ends in _host.  The caller owns every
+ *     buffer; the library never allocates or frees device memory, never synchronises, never
+ *     changes the current device.  All work is enqueued on `hip_stream` (a hipStream_t cast to
+ *     void*; NULL = the default stream).
+ *   - Tensors are dense row-major.  Activations [T, H]; weights [out_features, in_features];
+ *     bf16 storage (OB_BF16) with fp32 accumulation; row statistics and log-sum-exp are fp32.
+ *   - Every call validates its arguments on the host first and returns a non-zero ob_status
+ *     WITHOUT launching anything when validation fails.  ob_last_error() gives the text.
+ *   - Feature dimensions (hidden, mlp_dim, head_dim * heads) must be multiples of 64; head_dim
+ *     must be 64 or 128; the token count T is arbitrary (1 .. 2^22).
+ */
+#ifndef OMNIBAL_H
+#define OMNIBAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OB_OK = 0,
+    OB_EINVAL = 1,       /* null pointer, non-positive size, inconsistent head counts ...      */
+    OB_ESEGMENTS = 2,    /* cu_seqlens not starting at 0, not strictly increasing, wrong total  */
+    OB_EUNSUPPORTED = 3, /* head_dim not in {64,128}, dimension not a multiple of 64, fp32 path */
+    OB_EWORKSPACE = 4,   /* workspace / saved buffer smaller than the query functions report    */
+    OB_EHIP = 5          /* a HIP launch failed; text in ob_last_error()                         */
+} ob_status;
+
+typedef enum { OB_BF16 = 0, OB_FP32 = 1 } ob_dtype;
+typedef enum { OB_MASK_SEG_BIDIR = 0, OB_MASK_SEG_CAUSAL = 1 } ob_mask;
+typedef enum { OB_LAYERNORM = 0, OB_RMSNORM = 1 } ob_norm;
+typedef enum { OB_GELU = 0, OB_SWIGLU = 1 } ob_mlp;
+
+/* One block's static description.  has_bias: all four linears carry a bias and (LayerNorm only)
+ * the norms carry beta; otherwise every bias/beta pointer is ignored and may be NULL. */
+typedef struct {
+    int hidden, n_q_heads, n_kv_heads, head_dim, mlp_dim;
+    int norm;          /* ob_norm  */
+    int mlp;           /* ob_mlp   */
+    int mask;          /* ob_mask  */
+    int dtype;         /* ob_dtype */
+    int use_rotary;    /* rotate q,k pairs (i, i+d/2) by pos * base^(-2i/d), pos = t - cu[seg(t)] */
+    float rotary_base;
+    float norm_eps;
+    int has_bias;
+} ob_block_desc;
+
+/* Weights [out, in]: w_qkv [(nq+2nkv)d, H] rows ordered q heads | k heads | v heads;
+ * w_o [H, nq d]; w_up [F, H] (GELU) or [2F, H] = gate rows then up rows (SwiGLU); w_down [H, F].
+ * Norm gains n?_g [H] (bf16), betas n?_b [H]. */
+typedef struct {
+    const void *n1_g, *n1_b, *w_qkv, *b_qkv, *w_o, *b_o, *n2_g, *n2_b, *w_up, *b_up, *w_down, *b_down;
+} ob_block_weights;
+typedef struct {
+    void *n1_g, *n1_b, *w_qkv, *b_qkv, *w_o, *b_o, *n2_g, *n2_b, *w_up, *b_up, *w_down, *b_down;
+} ob_block_grads;
+
+/* Segment layout of one packed mini-batch: cu[0] = 0 < cu[1] < ... < cu[n_seg] = total_tokens.
+ * cu_host is read during validation and launch planning; cu_dev must hold the same n_seg+1
+ * int32 values in device memory.  max_seqlen >= the longest segment. */
+typedef struct {
+    const int32_t *cu_host;
+    const int32_t *cu_dev;
+    int n_seg, total_tokens, max_seqlen;
+} ob_segments;
+
+const char *ob_last_error(void);
+/* 1 when the library was built with its gfx950 kernels (always, for the shipped build). */
+int ob_has_device_code(void);
+
+/* ---- varlen attention (step a4 / b4 of the block) --------------------------------------------
+ * For query head a, KV head a / (nq / nkv):  S_ij = scale * q_i . k_j;  allowed(i, j) <=>
+ * same segment (and j <= i when causal);  o_i = sum_j softmax_j(S_ij) v_j over allowed j;
+ * lse[a, i] = log sum_j exp(S_ij) (natural log), layout [nq, T] fp32.
+ * q, o, d_o, dq: rows of nq*d elements with row strides ldq / ldo (in elements); k, v, dk, dv:
+ * rows of nkv*d elements with row stride ldkv -- so q,k,v may be column slices of one
+ * [T, (nq+2nkv) d] buffer.  Cross-segment score tiles are never computed.
+ * The backward needs ob_varlen_attn_bwd_workspace_bytes() bytes of scratch (holds
+ * Delta_i = sum_d dO_i O_i, [nq, T] fp32).  dk/dv are summed over the nq/nkv query heads of a
+ * group inside one workgroup (no atomics: results are bitwise reproducible). */
+int ob_varlen_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
+                       int ldq, int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d,
+                       float scale, int mask, int dtype, void *hip_stream);
+size_t ob_varlen_attn_bwd_workspace_bytes(int total_tokens, int nq);
+int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const void *o,
+                       const float *lse, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
+                       const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
+                       int dtype, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ---- one transformer block (steps a1..a9 / b9..b1) -------------------------------------------
+ * ob_block_fwd:  y = Block(x); keeps in `saved` (ob_block_saved_bytes) what the backward needs.
+ * ob_block_bwd:  given dy, the same x, weights and `saved`, writes dx and every weight gradient
+ * (bf16, after fp32 accumulation; accumulate_wgrad != 0 adds into the existing gradient buffers
+ * instead of overwriting them).  x/y and dy/dx may not alias each other or `saved`/`ws`. */
+size_t ob_block_saved_bytes(const ob_block_desc *desc, int total_tokens);
+size_t ob_block_workspace_bytes(const ob_block_desc *desc, int total_tokens);
+int ob_block_fwd(const ob_block_desc *desc, const ob_block_weights *w, const void *x, void *y,
+                 void *saved, size_t saved_bytes, const ob_segments *seg, void *ws, size_t ws_bytes,
+                 void *hip_stream);
+int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w, const ob_block_grads *g,
+                 int accumulate_wgrad, const void *x, const void *dy, void *dx, const void *saved,
+                 size_t saved_bytes, const ob_segments *seg, void *ws, size_t ws_bytes,
+                 void *hip_stream);
+
+/* Views into `saved` for tests and profiling: byte offset of a named intermediate
+ * ("h1","qkv","o","lse","x1","h2","up","act","stat1","stat2"); returns (size_t)-1 if unknown. */
+size_t ob_block_saved_offset(const ob_block_desc *desc, int total_tokens, const char *name);
+
+/* ---- building blocks exposed for tests and the bench's per-kernel roofline lines --------------
+ * C[M,N] = op(A) op(B) (+ bias[N]) (+ R[M,N]), bf16 in / fp32 accumulate / bf16 out.
+ *   layout 0 ("NT"): A [M,K], B [N,K]        -- forward  y = a W^T
+ *   layout 1 ("NN"): A [M,K], B [K,N]        -- dgrad    da = dy W
+ *   layout 2 ("TN"): A [K,M], B [K,N]        -- wgrad    dW = dy^T a   (K = tokens)
+ * `R` may equal `C` (in-place accumulate).  N and the feature side of K must be multiples of 64.
+ * ws: ob_gemm_workspace_bytes() bytes of scratch (operand re-layout for NN / TN). */
+size_t ob_gemm_workspace_bytes(int layout, int M, int N, int K);
+int ob_gemm_bf16(int layout, int M, int N, int K, const void *A, const void *B, void *C,
+                 const void *bias, const void *R, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* T x T byte mask (1 = allowed) written by the same segment/causal predicate the attention
+ * kernels use; for bit-exact mask tests, T <= 4096. */
+int ob_debug_materialize_mask(const ob_segments *seg, int mask, uint8_t *mask_dev, void *hip_stream);
+
+/* ---- host side: balanced dynamic mini-batches (Alg. 1, ISF) -----------------------------------
+ * Inputs: per-sample image-tile count n_img[i] = |x_i| and LLM-side token count n_tok[i] = |y_i|.
+ * Sampling stage: walk a random permutation of the not-yet-grouped samples, appending to the
+ * open group until the tile total would exceed Qv or the token total would exceed Qt; the group
+ * still open at the end is a candidate too.  Filtering stage: a candidate is accepted iff its
+ * tile total >= Qv_min or its token total >= Qt_min; accepted samples leave the pool.  Repeated
+ * `iters` times (Sec. 4.1; 10 in App. G).  randperm = Fisher-Yates (i = n-1..1, j uniform in
+ * [0, i] by rejection) over splitmix64 seeded with seed + iteration; the pool is kept in
+ * ascending sample-id order between iterations.
+ * Outputs (host arrays, caller-allocated): group_offsets[n_samples+1], sample_ids[n_samples]
+ * (group g = sample_ids[group_offsets[g] .. group_offsets[g+1])), leftover_ids[n_samples],
+ * groups_per_iter[iters] (may be NULL).  A sample with n_img > Qv or n_tok > Qt -> OB_EINVAL. */
+int ob_pack_isf(const int32_t *n_img, const int32_t *n_tok, int64_t n_samples, int64_t Qv,
+                int64_t Qt, int64_t Qv_min, int64_t Qt_min, int iters, uint64_t seed,
+                int64_t *group_offsets, int64_t *n_groups, int64_t *sample_ids,
+                int64_t *leftover_ids, int64_t *n_leftover, int64_t *groups_per_iter);
+/* Baseline arm (Sec. 5.4, method 1): consecutive runs of B samples of one random permutation. */
+int ob_pack_random(int64_t n_samples, int64_t B, uint64_t seed, int64_t *group_offsets,
+                   int64_t *n_groups, int64_t *sample_ids, int64_t *leftover_ids,
+                   int64_t *n_leftover);
+/* Segment offsets of one packed mini-batch: one segment per sample (LLM) / per tile (ViT). */
+int ob_build_cu_seqlens_llm(const int64_t *group_ids, int64_t n, const int32_t *n_tok,
+                            int32_t *cu_out, int32_t *max_seqlen_out);
+int ob_build_cu_seqlens_vit(int64_t n_tiles, int32_t tile_len, int32_t *cu_out);
+/* Eq. 1 and Eq. 2 (same form): sum_i (max - v_i) / (max * n). */
+double ob_pad_ratio(const int64_t *tokens_per_sample, int64_t n);
+double ob_dist_ratio(const int64_t *tokens_per_minibatch, int64_t n);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMNIBAL_H */

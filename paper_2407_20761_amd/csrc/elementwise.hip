@@ -1,0 +1,424 @@
+// HBM-bound row-wise and elementwise kernels of the block (steps a1, a3, a6, a8 and their
+// backward counterparts b1, b3, b6, b8, bias-gradient column sums, the attention Delta pre-pass).
+// bf16 in / out, fp32 arithmetic, 16-byte loads and stores; one workgroup per token row for the
+// row-wise ones so every byte is read once and written once.
+#include "ob_internal.h"
+
+namespace ob {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+namespace {
+
+constexpr int NORM_THREADS = 256;
+constexpr int MAX_VEC = 4;  // 8-element vectors per thread: H <= 256 * 8 * 4 = 8192
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// sum over the workgroup; every thread gets the result.  `red` holds one float per wave.
+__device__ __forceinline__ float block_sum(float v, float *red) {
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[wave] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int w = 0; w < nw; ++w) t += red[w];
+    return t;
+}
+
+template <bool LAYERNORM>
+__global__ __launch_bounds__(NORM_THREADS) void norm_fwd_kernel(
+    const __bf16 *__restrict__ x, const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ beta,
+    __bf16 *__restrict__ h, float *__restrict__ stats, int T, int H, float eps) {
+    __shared__ float red[NORM_THREADS / 64];
+    const int row = blockIdx.x;
+    const int nvec = H / 8;
+    const __bf16 *xr = x + (size_t)row * H;
+    float v[MAX_VEC][8];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < MAX_VEC; ++i) {
+        const int c = threadIdx.x + i * NORM_THREADS;
+        if (c < nvec) {
+            const bf16x8 t = *(const bf16x8 *)(xr + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v[i][e] = (float)t[e];
+                s += LAYERNORM ? v[i][e] : v[i][e] * v[i][e];
+            }
+        }
+    }
+    s = block_sum(s, red);
+    float mean = 0.f, rstd;
+    if (LAYERNORM) {
+        mean = s / H;
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < MAX_VEC; ++i) {
+            const int c = threadIdx.x + i * NORM_THREADS;
+            if (c < nvec) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float dlt = v[i][e] - mean;
+                    q += dlt * dlt;
+                }
+            }
+        }
+        q = block_sum(q, red);
+        rstd = rsqrtf(q / H + eps);
+    } else {
+        rstd = rsqrtf(s / H + eps);
+    }
+    if (threadIdx.x == 0) {
+        stats[2 * (size_t)row] = mean;
+        stats[2 * (size_t)row + 1] = rstd;
+    }
+#pragma unroll
+    for (int i = 0; i < MAX_VEC; ++i) {
+        const int c = threadIdx.x + i * NORM_THREADS;
+        if (c < nvec) {
+            const bf16x8 g = *(const bf16x8 *)(gamma + c * 8);
+            bf16x8 o;
+            if (LAYERNORM && beta) {
+                const bf16x8 b = *(const bf16x8 *)(beta + c * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    o[e] = (__bf16)((v[i][e] - mean) * rstd * (float)g[e] + (float)b[e]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (__bf16)((v[i][e] - mean) * rstd * (float)g[e]);
+            }
+            *(bf16x8 *)(h + (size_t)row * H + c * 8) = o;
+        }
+    }
+}
+
+// dx = dres + rstd * (dxhat - mean(dxhat) [LayerNorm only] - xhat * mean(dxhat * xhat)),
+// dxhat = dh * gamma.  Each workgroup walks rows blockIdx.x, +gridDim.x, ... and keeps its
+// column sums of dh * xhat (dgamma) and dh (dbeta) in registers; they are written once to
+// partial[blockIdx.x][2][H] and summed by reduce_partials_kernel.
+template <bool LAYERNORM>
+__global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
+    const __bf16 *__restrict__ dh, const __bf16 *__restrict__ x, const float *__restrict__ stats,
+    const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ dres, __bf16 *__restrict__ dx,
+    float *__restrict__ partial, int T, int H) {
+    __shared__ float red[NORM_THREADS / 64];
+    const int nvec = H / 8;
+    float g[MAX_VEC][8], dg[MAX_VEC][8], db[MAX_VEC][8];
+#pragma unroll
+    for (int i = 0; i < MAX_VEC; ++i) {
+        const int c = threadIdx.x + i * NORM_THREADS;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dg[i][e] = db[i][e] = g[i][e] = 0.f;
+        if (c < nvec) {
+            const bf16x8 t = *(const bf16x8 *)(gamma + c * 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) g[i][e] = (float)t[e];
+        }
+    }
+    for (int row = blockIdx.x; row < T; row += gridDim.x) {
+        const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+        float xh[MAX_VEC][8], dxh[MAX_VEC][8];
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < MAX_VEC; ++i) {
+            const int c = threadIdx.x + i * NORM_THREADS;
+            if (c < nvec) {
+                const bf16x8 tx = *(const bf16x8 *)(x + (size_t)row * H + c * 8);
+                const bf16x8 td = *(const bf16x8 *)(dh + (size_t)row * H + c * 8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float d = (float)td[e];
+                    xh[i][e] = ((float)tx[e] - mean) * rstd;
+                    dxh[i][e] = d * g[i][e];
+                    dg[i][e] += d * xh[i][e];
+                    db[i][e] += d;
+                    s1 += dxh[i][e];
+                    s2 += dxh[i][e] * xh[i][e];
+                }
+            }
+        }
+        s2 = block_sum(s2, red) / H;
+        s1 = LAYERNORM ? block_sum(s1, red) / H : 0.f;
+#pragma unroll
+        for (int i = 0; i < MAX_VEC; ++i) {
+            const int c = threadIdx.x + i * NORM_THREADS;
+            if (c < nvec) {
+                const bf16x8 tr = *(const bf16x8 *)(dres + (size_t)row * H + c * 8);
+                bf16x8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    o[e] = (__bf16)((float)tr[e] + rstd * (dxh[i][e] - s1 - xh[i][e] * s2));
+                *(bf16x8 *)(dx + (size_t)row * H + c * 8) = o;
+            }
+        }
+    }
+    float *pg = partial + (size_t)blockIdx.x * 2 * H, *pb = pg + H;
+#pragma unroll
+    for (int i = 0; i < MAX_VEC; ++i) {
+        const int c = threadIdx.x + i * NORM_THREADS;
+        if (c < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pg[c * 8 + e] = dg[i][e];
+                pb[c * 8 + e] = db[i][e];
+            }
+        }
+    }
+}
+
+// out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]; fixed summation order.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial,
+                                                              int n_part, int stride,
+                                                              __bf16 *__restrict__ out, int C,
+                                                              int accumulate) {
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (c >= C) return;
+    float s = 0.f;
+    for (int p = 0; p < n_part; ++p) s += partial[(size_t)p * stride + c];
+    if (accumulate) s += (float)out[c];
+    out[c] = (__bf16)s;
+}
+
+// partial[blockIdx.y][c] = sum over the rows blockIdx.y, +gridDim.y, ... of in[row][c]
+__global__ __launch_bounds__(256) void colsum_kernel(const __bf16 *__restrict__ in, int T, int C,
+                                                     int ld, float *__restrict__ partial) {
+    const int c8 = blockIdx.x * 256 + threadIdx.x;  // 8-column vector index
+    if (c8 * 8 >= C) return;
+    float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int row = blockIdx.y; row < T; row += gridDim.y) {
+        const bf16x8 t = *(const bf16x8 *)(in + (size_t)row * ld + c8 * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] += (float)t[e];
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) partial[(size_t)blockIdx.y * C + c8 * 8 + e] = s[e];
+}
+
+// segment index of token t: the j with cu[j] <= t < cu[j+1]
+__device__ __forceinline__ int find_segment(const int32_t *__restrict__ cu, int n_seg, int t) {
+    int lo = 0, hi = n_seg;  // invariant: cu[lo] <= t < cu[hi]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (cu[mid] <= t) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// In-place rotation of the first n_heads_rot heads of each row of qkv (the q heads then the k
+// heads are contiguous there): pair (i, i + d/2) by sign * pos * base^(-2 i / d).
+// One workgroup per token; thread = (head, 4-wide slice of the half dimension).
+__global__ __launch_bounds__(256) void rotary_kernel(__bf16 *__restrict__ qkv, int ld, int T,
+                                                     int n_heads_rot, int d,
+                                                     const int32_t *__restrict__ cu, int n_seg,
+                                                     float log2_base, float sign) {
+    const int t = blockIdx.x;
+    __shared__ int pos_s;
+    if (threadIdx.x == 0) pos_s = t - cu[find_segment(cu, n_seg, t)];
+    __syncthreads();
+    const float pos = (float)pos_s;
+    const int half = d / 2, per_head = half / 4;
+    for (int w = threadIdx.x; w < n_heads_rot * per_head; w += blockDim.x) {
+        const int head = w / per_head, i0 = (w % per_head) * 4;
+        __bf16 *p = qkv + (size_t)t * ld + head * d + i0;
+        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+        const bf16x4 a = *(const bf16x4 *)p, b = *(const bf16x4 *)(p + half);
+        bf16x4 oa, obb;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float theta = exp2f(-2.0f * (float)(i0 + e) / (float)d * log2_base);
+            float sn, cs;
+            sincosf(pos * theta, &sn, &cs);
+            sn *= sign;
+            const float x1 = (float)a[e], x2 = (float)b[e];
+            oa[e] = (__bf16)(x1 * cs - x2 * sn);
+            obb[e] = (__bf16)(x2 * cs + x1 * sn);
+        }
+        *(bf16x4 *)p = oa;
+        *(bf16x4 *)(p + half) = obb;
+    }
+}
+
+__device__ __forceinline__ float gelu_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_grad_f(float z) {
+    return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.3989422804014327f;
+}
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
+
+// GELU: act[t, f] = gelu(up[t, f]).  SwiGLU: up row = [gate (F) | up (F)], act = silu(gate) * up.
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void act_fwd_kernel(const __bf16 *__restrict__ up,
+                                                      __bf16 *__restrict__ act, long n_vec, int F) {
+    const int fv = F / 8;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += (long)gridDim.x * 256) {
+        const long t = i / fv;
+        const int c = (int)(i % fv) * 8;
+        bf16x8 o;
+        if (SWIGLU) {
+            const bf16x8 g = *(const bf16x8 *)(up + t * 2 * F + c);
+            const bf16x8 u = *(const bf16x8 *)(up + t * 2 * F + F + c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gz = (float)g[e];
+                o[e] = (__bf16)(gz * sigmoid_f(gz) * (float)u[e]);
+            }
+        } else {
+            const bf16x8 u = *(const bf16x8 *)(up + t * F + c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)gelu_f((float)u[e]);
+        }
+        *(bf16x8 *)(act + t * F + c) = o;
+    }
+}
+
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void act_bwd_kernel(const __bf16 *__restrict__ dact,
+                                                      const __bf16 *__restrict__ up,
+                                                      __bf16 *__restrict__ dup, long n_vec, int F) {
+    const int fv = F / 8;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += (long)gridDim.x * 256) {
+        const long t = i / fv;
+        const int c = (int)(i % fv) * 8;
+        const bf16x8 da = *(const bf16x8 *)(dact + t * F + c);
+        if (SWIGLU) {
+            const bf16x8 g = *(const bf16x8 *)(up + t * 2 * F + c);
+            const bf16x8 u = *(const bf16x8 *)(up + t * 2 * F + F + c);
+            bf16x8 og, ou;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float gz = (float)g[e], sg = sigmoid_f(gz), d = (float)da[e];
+                og[e] = (__bf16)(d * (float)u[e] * sg * (1.0f + gz * (1.0f - sg)));
+                ou[e] = (__bf16)(d * gz * sg);
+            }
+            *(bf16x8 *)(dup + t * 2 * F + c) = og;
+            *(bf16x8 *)(dup + t * 2 * F + F + c) = ou;
+        } else {
+            const bf16x8 u = *(const bf16x8 *)(up + t * F + c);
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)((float)da[e] * gelu_grad_f((float)u[e]));
+            *(bf16x8 *)(dup + t * F + c) = o;
+        }
+    }
+}
+
+// delta[head][t] = sum_d dO[t, head, d] * O[t, head, d]; 8 lanes (d = 64) or 16 lanes (d = 128)
+// share one (t, head) row.
+__global__ __launch_bounds__(256) void attn_delta_kernel(const __bf16 *__restrict__ d_o,
+                                                         const __bf16 *__restrict__ o, int ldo,
+                                                         float *__restrict__ delta, int T, int nq,
+                                                         int d) {
+    const int lanes = d / 8;
+    const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+    const long pair = gid / lanes;
+    const int part = (int)(gid % lanes);
+    const bool live = pair < (long)T * nq;
+    float s = 0.f;
+    long t = 0;
+    int head = 0;
+    if (live) {
+        t = pair / nq;
+        head = (int)(pair % nq);
+        const size_t off = (size_t)t * ldo + head * d + part * 8;
+        const bf16x8 a = *(const bf16x8 *)(d_o + off), b = *(const bf16x8 *)(o + off);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)b[e];
+    }
+    for (int off = lanes >> 1; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+    if (live && part == 0) delta[(size_t)head * T + t] = s;
+}
+
+__global__ __launch_bounds__(256) void mask_kernel(const int32_t *__restrict__ cu, int n_seg, int T,
+                                                   int causal, uint8_t *__restrict__ out) {
+    const int i = blockIdx.x;
+    const int seg = find_segment(cu, n_seg, i);
+    const int a = cu[seg], b = causal ? i + 1 : cu[seg + 1];
+    for (int j = threadIdx.x; j < T; j += 256) out[(size_t)i * T + j] = (j >= a && j < b) ? 1 : 0;
+}
+
+}  // namespace
+
+void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *beta, void *h,
+                     float *stats, int T, int H, float eps, hipStream_t s) {
+    if (norm == OB_LAYERNORM)
+        hipLaunchKernelGGL(norm_fwd_kernel<true>, dim3(T), dim3(NORM_THREADS), 0, s, (const __bf16 *)x,
+                           (const __bf16 *)gamma, (const __bf16 *)beta, (__bf16 *)h, stats, T, H, eps);
+    else
+        hipLaunchKernelGGL(norm_fwd_kernel<false>, dim3(T), dim3(NORM_THREADS), 0, s, (const __bf16 *)x,
+                           (const __bf16 *)gamma, (const __bf16 *)nullptr, (__bf16 *)h, stats, T, H, eps);
+}
+
+int norm_bwd_partials(int T) { return T < 1024 ? T : 1024; }
+
+void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
+                     const void *dres, void *dx, float *partial, int T, int H, hipStream_t s) {
+    const int nb = norm_bwd_partials(T);
+    if (norm == OB_LAYERNORM)
+        hipLaunchKernelGGL(norm_bwd_kernel<true>, dim3(nb), dim3(NORM_THREADS), 0, s, (const __bf16 *)dh,
+                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
+                           (__bf16 *)dx, partial, T, H);
+    else
+        hipLaunchKernelGGL(norm_bwd_kernel<false>, dim3(nb), dim3(NORM_THREADS), 0, s, (const __bf16 *)dh,
+                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
+                           (__bf16 *)dx, partial, T, H);
+}
+
+void launch_reduce_partials(const float *partial, int n_part, int stride, void *out, int C,
+                            int accumulate, hipStream_t s) {
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C + 255) / 256), dim3(256), 0, s, partial, n_part,
+                       stride, (__bf16 *)out, C, accumulate);
+}
+
+int colsum_partials(int T) { return T < 256 ? T : 256; }
+
+void launch_colsum(const void *in, int T, int C, int ld, float *partial, hipStream_t s) {
+    dim3 grid((C / 8 + 255) / 256, colsum_partials(T));
+    hipLaunchKernelGGL(colsum_kernel, grid, dim3(256), 0, s, (const __bf16 *)in, T, C, ld, partial);
+}
+
+void launch_rotary(void *qkv, int ld, int T, int n_heads_rot, int d, const int32_t *cu_dev, int n_seg,
+                   float base, float sign, hipStream_t s) {
+    hipLaunchKernelGGL(rotary_kernel, dim3(T), dim3(256), 0, s, (__bf16 *)qkv, ld, T, n_heads_rot, d,
+                       cu_dev, n_seg, log2f(base), sign);
+}
+
+void launch_act_fwd(int mlp, const void *up, void *act, int T, int F, hipStream_t s) {
+    const long n_vec = (long)T * (F / 8);
+    const int blocks = (int)((n_vec + 255) / 256 < 65536 ? (n_vec + 255) / 256 : 65536);
+    if (mlp == OB_SWIGLU)
+        hipLaunchKernelGGL(act_fwd_kernel<true>, dim3(blocks), dim3(256), 0, s, (const __bf16 *)up,
+                           (__bf16 *)act, n_vec, F);
+    else
+        hipLaunchKernelGGL(act_fwd_kernel<false>, dim3(blocks), dim3(256), 0, s, (const __bf16 *)up,
+                           (__bf16 *)act, n_vec, F);
+}
+
+void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T, int F, hipStream_t s) {
+    const long n_vec = (long)T * (F / 8);
+    const int blocks = (int)((n_vec + 255) / 256 < 65536 ? (n_vec + 255) / 256 : 65536);
+    if (mlp == OB_SWIGLU)
+        hipLaunchKernelGGL(act_bwd_kernel<true>, dim3(blocks), dim3(256), 0, s, (const __bf16 *)dact,
+                           (const __bf16 *)up, (__bf16 *)dup, n_vec, F);
+    else
+        hipLaunchKernelGGL(act_bwd_kernel<false>, dim3(blocks), dim3(256), 0, s, (const __bf16 *)dact,
+                           (const __bf16 *)up, (__bf16 *)dup, n_vec, F);
+}
+
+void launch_attn_delta(const void *d_o, const void *o, int ldo, float *delta, int T, int nq, int d,
+                       hipStream_t s) {
+    const long threads = (long)T * nq * (d / 8);
+    hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                       (const __bf16 *)d_o, (const __bf16 *)o, ldo, delta, T, nq, d);
+}
+
+void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out, hipStream_t s) {
+    hipLaunchKernelGGL(mask_kernel, dim3(T), dim3(256), 0, s, cu_dev, n_seg, T,
+                       mask == OB_MASK_SEG_CAUSAL ? 1 : 0, out);
+}
+
+}  // namespace ob

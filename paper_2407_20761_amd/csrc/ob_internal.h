@@ -1,0 +1,59 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/omnibal.h"
+
+namespace ob {
+
+// thread-local error text behind ob_last_error()
+int fail(int status, const char *fmt, ...);
+int check_launch(const char *what);
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- GEMM (gemm.hip) ---------------------------------------------------------------------
+// C[M,N] = A[M,K] B[N,K]^T (+bias[N]) (+R[M,N]); K % 64 == 0, N % 8 == 0, any M.
+void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
+                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s);
+// out[c, r] = in[r, c] for r < rows, 0 for rows <= r < rows_pad; in ld = ld_in, out ld = rows_pad
+void launch_transpose_pad(const void *in, int rows, int cols, int ld_in, void *out, int rows_pad,
+                          hipStream_t s);
+size_t gemm_workspace_bytes(int layout, int M, int N, int K);
+int gemm_any(int layout, int M, int N, int K, const void *A, const void *B, void *C,
+             const void *bias, const void *R, void *ws, size_t ws_bytes, hipStream_t s);
+
+// ---- elementwise (elementwise.hip) -----------------------------------------------------------
+// stats: LayerNorm [T,2] = (mean, rstd); RMSNorm [T,2] = (unused, rstd)
+void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *beta, void *h,
+                     float *stats, int T, int H, float eps, hipStream_t s);
+// dx = dres + norm_bwd(dh); partial [n_part, 2, H] fp32 sums of dgamma / dbeta
+int norm_bwd_partials(int T);
+void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
+                     const void *dres, void *dx, float *partial, int T, int H, hipStream_t s);
+// out[c] (bf16) = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]
+void launch_reduce_partials(const float *partial, int n_part, int stride, void *out, int C,
+                            int accumulate, hipStream_t s);
+int colsum_partials(int T);
+void launch_colsum(const void *in, int T, int C, int ld, float *partial, hipStream_t s);
+void launch_rotary(void *qkv, int ld, int T, int n_heads_rot, int d, const int32_t *cu_dev,
+                   int n_seg, float base, float sign, hipStream_t s);
+void launch_act_fwd(int mlp, const void *up, void *act, int T, int F, hipStream_t s);
+void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T, int F,
+                    hipStream_t s);
+void launch_attn_delta(const void *d_o, const void *o, int ldo, float *delta, int T, int nq, int d,
+                       hipStream_t s);
+void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out, hipStream_t s);
+
+// ---- attention (attention.hip) ---------------------------------------------------------------
+void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int ldq,
+                     int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale,
+                     int mask, hipStream_t s);
+void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse,
+                     const float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
+                     const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
+                     hipStream_t s);
+
+}  // namespace ob

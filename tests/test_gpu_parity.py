@@ -1,0 +1,250 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Tolerance: max|err| / max|ref| <= 2e-2 per tensor for the bf16 path (the benchmark contract's
+bound; bf16 has 8 mantissa bits, every stored intermediate costs up to 2^-9 relative).  Segment
+offsets and masks are compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2407_20761_amd as ob
+import synth_inputs as si
+from conftest import rel_err
+from oracle import block as orc
+from oracle import packer as orc_pack
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+if torch.cuda.is_available():
+    from gpu_util import BlockRun, bytes_buf, run_block, saved_view, to_dev, to_np
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ---- GEMM ------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("layout", [0, 1, 2])
+@pytest.mark.parametrize("M,N,K", [(300, 192, 128), (1, 64, 64), (4100, 8192, 256),
+                                   (1025, 3200, 448), (257, 256, 64)])
+def test_gemm_against_fp64_matmul(layout, M, N, K):
+    if layout == 2 and M % 64:
+        M = (M + 63) // 64 * 64          # the output rows of a weight gradient are a feature dim
+    if layout == 2:
+        K = K + 37                        # the token dimension is ragged
+    _say(f"gemm layout={layout} M={M} N={N} K={K}")
+    rng = np.random.default_rng(M + N + K + layout)
+    A = si.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
+    B = si.round_to_bf16(rng.standard_normal((N, K), dtype=np.float32))
+    bias = si.round_to_bf16(rng.standard_normal((N,), dtype=np.float32))
+    R = si.round_to_bf16(rng.standard_normal((M, N), dtype=np.float32) * 4)
+    ref = A.astype(np.float64) @ B.astype(np.float64).T
+    a_dev = to_dev(A if layout != 2 else A.T.copy())
+    b_dev = to_dev(B if layout == 0 else B.T.copy())
+    ws = bytes_buf(ob.ob_gemm_workspace_bytes(layout, M, N, K))
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ob.ob_gemm_bf16(layout, M, N, K, a_dev, b_dev, c, None, None, ws)
+    assert rel_err(to_np(c), ref) < 5e-3
+    c2 = to_dev(R)
+    ob.ob_gemm_bf16(layout, M, N, K, a_dev, b_dev, c2, to_dev(bias), c2, ws)   # in-place + bias
+    assert rel_err(to_np(c2), ref + bias + R) < 5e-3
+
+
+# ---- attention ------------------------------------------------------------------------------
+
+ATTN_CASES = [
+    # lens, nq, nkv, d, mask
+    ([1, 63, 64, 65, 130, 300], 4, 2, 64, orc.MASK_CAUSAL),
+    ([1, 63, 64, 65, 130, 300], 4, 4, 64, orc.MASK_BIDIR),
+    ([129, 7, 256, 1], 8, 2, 128, orc.MASK_CAUSAL),
+    ([1025, 1025], 3, 3, 128, orc.MASK_BIDIR),
+    ([700], 2, 1, 128, orc.MASK_CAUSAL),
+]
+
+
+@pytest.mark.parametrize("lens,nq,nkv,d,mask", ATTN_CASES)
+def test_varlen_attention_fwd_bwd(lens, nq, nkv, d, mask):
+    _say(f"attention lens={lens} nq={nq} nkv={nkv} d={d} mask={mask}")
+    cu = si.lengths_to_cu(lens)
+    T = int(cu[-1])
+    q, k, v, d_o = si.qkv_tensors(T, nq, nkv, d, seed=len(lens) + d)
+    scale = 1.0 / np.sqrt(d)
+    o_ref, lse_ref = orc.attention_fwd(*(a.astype(np.float64) for a in (q, k, v)), cu, mask, scale)
+    dq_ref, dk_ref, dv_ref = orc.attention_bwd(*(a.astype(np.float64) for a in (d_o, q, k, v)),
+                                               cu, mask, scale)
+    # q, k, v live as column slices of one [T, (nq + 2 nkv) d] buffer, as inside the block
+    Dq = (nq + 2 * nkv) * d
+    qkv = to_dev(np.concatenate([q.reshape(T, -1), k.reshape(T, -1), v.reshape(T, -1)], axis=1))
+    qd, kd, vd = qkv[:, :nq * d], qkv[:, nq * d:(nq + nkv) * d], qkv[:, (nq + nkv) * d:]
+    o = torch.empty((T, nq * d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((nq, T), dtype=torch.float32, device="cuda")
+    seg = ob.Segments(cu)
+    ob.ob_varlen_attn_fwd(qd, kd, vd, o, lse, Dq, Dq, nq * d, seg, nq, nkv, d, scale, mask)
+    assert rel_err(to_np(o).reshape(T, nq, d), o_ref) < TOL
+    assert np.abs(to_np(lse) - lse_ref).max() < 2e-2
+    dqkv = torch.full((T, Dq), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = bytes_buf(ob.ob_varlen_attn_bwd_workspace_bytes(T, nq))
+    dod = to_dev(d_o.reshape(T, -1))
+    ob.ob_varlen_attn_bwd(dod, qd, kd, vd, o, lse, dqkv[:, :nq * d], dqkv[:, nq * d:(nq + nkv) * d],
+                          dqkv[:, (nq + nkv) * d:], Dq, Dq, nq * d, seg, nq, nkv, d, scale, mask, ws)
+    g = to_np(dqkv)
+    assert np.isfinite(g).all()
+    assert rel_err(g[:, :nq * d].reshape(T, nq, d), dq_ref) < TOL
+    assert rel_err(g[:, nq * d:(nq + nkv) * d].reshape(T, nkv, d), dk_ref) < TOL
+    assert rel_err(g[:, (nq + nkv) * d:].reshape(T, nkv, d), dv_ref) < TOL
+    # bitwise reproducible (no atomics anywhere)
+    dqkv2 = torch.empty_like(dqkv)
+    ob.ob_varlen_attn_bwd(dod, qd, kd, vd, o, lse, dqkv2[:, :nq * d], dqkv2[:, nq * d:(nq + nkv) * d],
+                          dqkv2[:, (nq + nkv) * d:], Dq, Dq, nq * d, seg, nq, nkv, d, scale, mask, ws)
+    assert torch.equal(dqkv.view(torch.int16), dqkv2.view(torch.int16))
+
+
+@pytest.mark.parametrize("mask", [orc.MASK_BIDIR, orc.MASK_CAUSAL])
+def test_mask_and_offsets_bit_exact(mask):
+    lens = si.tiny_segment_lengths(seed=0)
+    cu = si.lengths_to_cu(lens)
+    T = int(cu[-1])
+    seg = ob.Segments(cu)
+    out = torch.empty((T, T), dtype=torch.uint8, device="cuda")
+    ob.ob_debug_materialize_mask(seg, mask, out)
+    assert np.array_equal(out.cpu().numpy().astype(bool), orc.allowed_mask(cu, T, mask))
+    # offsets produced by the library's builders equal the oracle's, bit for bit
+    tiles, tok = si.synthetic_dataset(500, 0)
+    groups, _, _ = ob.ob_pack_isf(tiles, tok, 10 ** 9, 16384, 10 ** 9, 16384 - 128, 10, 0)
+    P, _, _ = orc_pack.isf(tiles, tok, 10 ** 9, 16384, 10 ** 9, 16384 - 128, 10, 0)
+    for g, G in zip(groups[:5], P[:5]):
+        assert ob.ob_build_cu_seqlens_llm(g, tok)[0].tolist() == orc_pack.cu_seqlens_llm(G, tok)
+
+
+# ---- whole block ----------------------------------------------------------------------------
+
+def _check_block(shape, cu, seed, intermediates=True):
+    T = int(cu[-1])
+    w = si.block_weights(shape, seed=seed)
+    x, dy = si.activations(T, shape.hidden, seed=seed)
+    y_ref, cache = orc.block_fwd(shape, w, x, cu)
+    dx_ref, g_ref, _ = orc.block_bwd(shape, w, cache, dy, cu)
+    run, y, dx, g = run_block(shape, w, x, dy, cu)
+    errs = {"y": rel_err(y, y_ref), "dx": rel_err(dx, dx_ref)}
+    for n in g_ref:
+        errs["d" + n] = rel_err(g[n], g_ref[n])
+    if intermediates:
+        nq, nkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+        qkv_ref = np.concatenate([cache["q"].reshape(T, -1), cache["k"].reshape(T, -1),
+                                  cache["v"].reshape(T, -1)], axis=1)
+        views = {"h1": (cache["h1"], (T, shape.hidden)), "qkv": (qkv_ref, (T, shape.d_qkv)),
+                 "o": (cache["o"].reshape(T, -1), (T, nq * d)), "x1": (cache["x1"], (T, shape.hidden)),
+                 "h2": (cache["h2"], (T, shape.hidden)), "up": (cache["up"], (T, shape.up_rows)),
+                 "act": (cache["act"], (T, shape.mlp_dim))}
+        for n, (ref, shp) in views.items():
+            errs["saved." + n] = rel_err(to_np(saved_view(run.desc, T, run.saved, n, shp)), ref)
+    _say("  " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    assert set(g_ref) == set(w)
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
+    return run
+
+
+def test_block_config1_fwd_bwd():
+    shape = si.CONFIGS[1]
+    cu = si.lengths_to_cu(si.tiny_segment_lengths(seed=0))
+    _say(f"block config 1: T={int(cu[-1])} lens={np.diff(cu).tolist()}")
+    _check_block(shape, cu, seed=0)
+
+
+@pytest.mark.parametrize("variant", ["llm-like", "vit-like", "vit-d128-rms"])
+def test_block_small_variants(variant):
+    if variant == "llm-like":
+        shape = si.small_shape(hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, mlp_dim=320,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
+                               use_rotary=True, has_bias=False, norm_eps=1e-6)
+        lens = [300, 1, 140, 259]
+    elif variant == "vit-like":
+        shape = si.small_shape(hidden=192, n_q_heads=3, n_kv_heads=3, head_dim=64, mlp_dim=768,
+                               norm=si.NORM_LAYERNORM, mlp=si.MLP_GELU, mask=si.MASK_BIDIR,
+                               use_rotary=False, has_bias=True)
+        lens = [257, 257, 257]
+    else:
+        shape = si.small_shape(hidden=384, n_q_heads=3, n_kv_heads=3, head_dim=128, mlp_dim=1536,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_GELU, mask=si.MASK_BIDIR,
+                               use_rotary=False, has_bias=False, norm_eps=1e-6)
+        lens = [1025, 130]
+    _say(f"block {variant}: lens={lens}")
+    _check_block(shape, si.lengths_to_cu(lens), seed=3)
+
+
+def _subset_cu(cfg, max_tokens, seed=0):
+    """Whole segments of one balanced mini-batch of `cfg`, up to about max_tokens tokens."""
+    shape = si.CONFIGS[cfg]
+    tiles, tok = si.synthetic_dataset(20000, seed)
+    if shape.kind == "vit":
+        n = max(1, max_tokens // si.VIT_TILE_TOKENS)
+        return ob.ob_build_cu_seqlens_vit(n, si.VIT_TILE_TOKENS)
+    groups, _, _ = ob.ob_pack_isf(tiles, tok, 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128, 10, seed)
+    cu, _ = ob.ob_build_cu_seqlens_llm(groups[0], tok)
+    n = max(1, int(np.searchsorted(cu, max_tokens, side="right")) - 1)
+    return cu[:n + 1].copy()
+
+
+@pytest.mark.parametrize("cfg,max_tokens", [(2, 2100), (3, 2048), (4, 2100), (5, 1600)])
+def test_block_full_hidden_sizes_on_a_segment_subset(cfg, max_tokens):
+    """Configs 2-5 at their full hidden sizes, one block, whole segments of a balanced batch."""
+    shape = si.CONFIGS[cfg]
+    cu = _subset_cu(cfg, max_tokens)
+    _say(f"block config {cfg} ({shape.name}): T={int(cu[-1])} n_seg={len(cu) - 1}")
+    _check_block(shape, cu, seed=cfg, intermediates=False)
+
+
+def test_block_is_bitwise_reproducible_and_accumulates():
+    shape = si.CONFIGS[1]
+    cu = si.lengths_to_cu([200, 333, 90])
+    T = int(cu[-1])
+    w = si.block_weights(shape, seed=9)
+    x_np, dy_np = si.activations(T, shape.hidden, seed=9)
+    seg = ob.Segments(cu)
+    run = BlockRun(shape, w, T)
+    x, dy = to_dev(x_np), to_dev(dy_np)
+    y1 = run.fwd(x, seg).clone()
+    dx1 = run.bwd(x, dy, seg).clone()
+    g1 = {n: t.clone() for n, t in run.g.items()}
+    y2 = run.fwd(x, seg)
+    dx2 = run.bwd(x, dy, seg, accumulate=True)       # grads now hold g + g
+    torch.cuda.synchronize()
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+    assert torch.equal(dx1.view(torch.int16), dx2.view(torch.int16))
+    for n in g1:
+        assert torch.equal((2 * g1[n].float()).to(torch.bfloat16).view(torch.int16),
+                           run.g[n].view(torch.int16)), n
+
+
+def test_config3_full_batch_one_segment_against_oracle():
+    """The launch configuration the bench times (config 3, one full balanced 16K-token batch):
+    the packed result restricted to one sample must equal the oracle run on that sample alone,
+    and with dy zero outside the sample the weight gradients must equal the sample's own."""
+    shape = si.CONFIGS[3]
+    tiles, tok = si.synthetic_dataset(20000, 0)
+    groups, _, _ = ob.ob_pack_isf(tiles, tok, 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128, 10, 0)
+    cu, mx = ob.ob_build_cu_seqlens_llm(groups[0], tok)
+    T = int(cu[-1])
+    lens = np.diff(cu)
+    j = int(np.argmin(np.abs(lens - 700)))            # a mid-sized sample, not tile aligned
+    a, b = int(cu[j]), int(cu[j + 1])
+    _say(f"config 3 full batch: T={T} n_seg={len(lens)} checking segment {j} [{a},{b})")
+    w = si.block_weights(shape, seed=3)
+    x, dy = si.activations(T, shape.hidden, seed=3)
+    dy_masked = np.zeros_like(dy)
+    dy_masked[a:b] = dy[a:b]
+    run, y, dx, g = run_block(shape, w, x, dy_masked, cu)
+    y_ref, cache = orc.block_fwd(shape, w, x[a:b], [0, b - a])
+    dx_ref, g_ref, _ = orc.block_bwd(shape, w, cache, dy[a:b], [0, b - a])
+    errs = {"y": rel_err(y[a:b], y_ref), "dx": rel_err(dx[a:b], dx_ref)}
+    for n in g_ref:
+        errs["d" + n] = rel_err(g[n], g_ref[n])
+    _say("  " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    assert max(errs.values()) <= TOL, errs
+    outside = np.ones(T, bool)
+    outside[a:b] = False
+    assert np.abs(dx[outside]).max() == 0.0

@@ -1,0 +1,166 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+rejects bad arguments without touching a device, and its host packer equals the oracle's."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2407_20761_amd as ob
+import synth_inputs as si
+from oracle import packer as op
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "omnibal.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ob_[a-z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 18
+    for name in declared:
+        assert hasattr(ob.lib, name), name
+    assert declared == set(ob.EXPORTED)
+    assert ob.lib.ob_has_device_code() == 1
+
+
+# ---- packer: bit-exact against the oracle ---------------------------------------------------
+
+@pytest.mark.parametrize("seed", [0, 3])
+def test_pack_isf_equals_oracle(seed):
+    tiles, tok = si.synthetic_dataset(2500, seed)
+    for (Qv, Qt, Qvm, Qtm) in [(10 ** 9, 16384, 10 ** 9, 16384 - 128), (12, 10 ** 9, 12, 10 ** 9),
+                               (42, 16384, 42, 16384 - 128), (14, 9000, 13, 8000)]:
+        g, left, per = ob.ob_pack_isf(tiles, tok, Qv, Qt, Qvm, Qtm, 10, seed)
+        P, L, pi = op.isf(tiles, tok, Qv, Qt, Qvm, Qtm, 10, seed)
+        assert [a.tolist() for a in g] == P
+        assert left.tolist() == L
+        assert per.tolist()[:len(pi)] == pi and not per.tolist()[len(pi):].count(1)
+
+
+def test_pack_isf_tiny_and_degenerate():
+    img, tok = [1, 2, 1, 3, 1, 1], [4, 3, 5, 2, 8, 2]
+    for seed in range(5):
+        g, left, _ = ob.ob_pack_isf(img, tok, 4, 10, 4, 8, 3, seed)
+        P, L, _ = op.isf(img, tok, 4, 10, 4, 8, 3, seed)
+        assert [a.tolist() for a in g] == P and left.tolist() == L
+    g, left, _ = ob.ob_pack_isf([], [], 4, 10, 4, 8, 3, 0)
+    assert g == [] and left.tolist() == []
+    g, left, _ = ob.ob_pack_isf([1], [5], 4, 10, 4, 8, 0, 0)       # zero iterations
+    assert g == [] and left.tolist() == [0]
+    with pytest.raises(ob.OmnibalError) as e:
+        ob.ob_pack_isf(img, tok, 2, 10, 2, 8, 3, 0)                # sample 3 has 3 > 2 tiles
+    assert e.value.status == ob.OB_EINVAL and "sample 3" in str(e.value)
+
+
+def test_pack_random_and_cu_builders_equal_oracle():
+    g, left = ob.ob_pack_random(1003, 7, 11)
+    G, L = op.random_groups(1003, 7, 11)
+    assert [a.tolist() for a in g] == G and left.tolist() == L
+    tiles, tok = si.synthetic_dataset(50, 2)
+    cu, mx = ob.ob_build_cu_seqlens_llm([4, 9, 1], tok)
+    assert cu.tolist() == op.cu_seqlens_llm([4, 9, 1], tok) and mx == max(tok[[4, 9, 1]])
+    assert ob.ob_build_cu_seqlens_vit(12, 1025).tolist() == op.cu_seqlens_vit(12, 1025)
+    with pytest.raises(ob.OmnibalError):
+        ob.ob_build_cu_seqlens_vit(0, 1025)
+
+
+def test_metrics_equal_oracle():
+    for v in ([2, 4], [5, 5, 5], [1, 2, 3, 6], [100, 50], [7]):
+        assert ob.ob_pad_ratio(v) == pytest.approx(op.pad_ratio(v), abs=1e-15)
+        assert ob.ob_dist_ratio(v) == pytest.approx(op.dist_ratio(v), abs=1e-15)
+
+
+# ---- argument validation: every error path returns before any launch -----------------------
+
+def _seg(cu, total=None, max_seqlen=None, fake_dev=True):
+    cu = np.asarray(cu, dtype=np.int32)
+    s = ob.Segments(cu, device=None, max_seqlen=max_seqlen)
+    if fake_dev:
+        s.c.cu_dev = 0x1000                     # never dereferenced: validation fails first
+    if total is not None:
+        s.c.total_tokens = total
+    return s
+
+
+def _attn_status(seg, nq=4, nkv=2, d=64, ldq=256, ldkv=128, ldo=256, mask=1, dtype=0, null_q=False):
+    p = C.c_void_p(0x1000)
+    return ob.lib.ob_varlen_attn_fwd(None if null_q else p, p, p, p, p, ldq, ldkv, ldo,
+                                     C.byref(seg.c), nq, nkv, d, 0.125, mask, dtype, None)
+
+
+def test_attention_argument_validation():
+    good = _seg([0, 5, 9])
+    assert _attn_status(good, null_q=True) == ob.OB_EINVAL
+    assert _attn_status(_seg([1, 5, 9])) == ob.OB_ESEGMENTS               # cu[0] != 0
+    assert "must be 0" in ob.ob_last_error()
+    assert _attn_status(_seg([0, 5, 5, 9])) == ob.OB_ESEGMENTS            # empty segment
+    assert _attn_status(_seg([0, 7, 5, 9])) == ob.OB_ESEGMENTS            # not monotone
+    assert _attn_status(_seg([0, 5, 9], total=10)) == ob.OB_ESEGMENTS     # cu[n] != T
+    assert _attn_status(_seg([0, 5, 9], max_seqlen=3)) == ob.OB_ESEGMENTS
+    assert _attn_status(good, nq=4, nkv=3) == ob.OB_EINVAL
+    assert _attn_status(good, d=96) == ob.OB_EUNSUPPORTED
+    assert _attn_status(good, dtype=ob.OB_FP32) == ob.OB_EUNSUPPORTED
+    assert _attn_status(good, mask=7) == ob.OB_EINVAL
+    assert _attn_status(good, ldq=100) == ob.OB_EINVAL
+    assert _attn_status(_seg([0, 5, 9], fake_dev=False)) == ob.OB_EINVAL  # cu_dev null
+    p = C.c_void_p(0x1000)
+    st = ob.lib.ob_varlen_attn_bwd(p, p, p, p, p, p, p, p, p, 256, 128, 256, C.byref(good.c),
+                                   4, 2, 64, 0.125, 1, 0, p, 16, None)
+    assert st == ob.OB_EWORKSPACE
+
+
+def test_block_argument_validation_and_sizes():
+    shape = si.CONFIGS[1]
+    desc = ob.make_desc(shape)
+    T = 777
+    sb, wb = ob.ob_block_saved_bytes(desc, T), ob.ob_block_workspace_bytes(desc, T)
+    # saved holds h1, qkv, o, x1, h2, up, act (bf16) + lse + two stat arrays (fp32)
+    lower = T * (4 * 256 + 768 + 1024 + 1024) * 2 + 4 * T * 4 + 2 * T * 2 * 4
+    assert lower <= sb <= lower + 10 * 256 and wb > 0
+    offs = [ob.ob_block_saved_offset(desc, T, n) for n in
+            ("h1", "qkv", "o", "lse", "x1", "h2", "up", "act", "stat1", "stat2")]
+    assert offs == sorted(offs) and offs[0] == 0 and all(o % 256 == 0 for o in offs)
+    assert ob.ob_block_saved_offset(desc, T, "nope") == C.c_size_t(-1).value
+
+    p = C.c_void_p(0x1000)
+    w = ob.ob_block_weights(*[0x1000] * 12)
+    seg = _seg([0, 300, 777])
+
+    def fwd(desc_, w_=w, seg_=seg, sb_=sb, wb_=wb, x=p):
+        return ob.lib.ob_block_fwd(C.byref(desc_), C.byref(w_), x, p, p, sb_, C.byref(seg_.c), p,
+                                   wb_, None)
+
+    assert fwd(desc, x=None) == ob.OB_EINVAL
+    assert fwd(desc, sb_=sb - 1) == ob.OB_EWORKSPACE
+    assert fwd(desc, wb_=wb - 1) == ob.OB_EWORKSPACE
+    assert fwd(desc, seg_=_seg([0, 300, 776], total=777)) == ob.OB_ESEGMENTS
+    w_missing = ob.ob_block_weights(*[0x1000] * 12)
+    w_missing.b_qkv = None
+    assert fwd(desc, w_=w_missing) == ob.OB_EINVAL            # has_bias but no bias pointer
+    for field, val, status in (("head_dim", 96, ob.OB_EUNSUPPORTED), ("hidden", 250, ob.OB_EUNSUPPORTED),
+                               ("n_kv_heads", 3, ob.OB_EINVAL), ("dtype", ob.OB_FP32, ob.OB_EUNSUPPORTED),
+                               ("norm", 5, ob.OB_EINVAL), ("hidden", 16384, ob.OB_EUNSUPPORTED)):
+        d2 = ob.make_desc(shape)
+        setattr(d2, field, val)
+        assert fwd(d2) == status, field
+    g = ob.ob_block_grads(*[0x1000] * 12)
+    g.w_o = None
+    st = ob.lib.ob_block_bwd(C.byref(desc), C.byref(w), C.byref(g), 0, p, p, p, p, sb,
+                             C.byref(seg.c), p, wb, None)
+    assert st == ob.OB_EINVAL
+
+
+def test_gemm_argument_validation():
+    p = C.c_void_p(0x1000)
+    call = lambda layout, M, N, K, ws=p, wsb=1 << 40: ob.lib.ob_gemm_bf16(layout, M, N, K, p, p, p,
+                                                                         None, None, ws, wsb, None)
+    assert call(3, 64, 64, 64) == ob.OB_EINVAL
+    assert call(0, 64, 100, 64) == ob.OB_EUNSUPPORTED
+    assert call(0, 64, 64, 100) == ob.OB_EUNSUPPORTED
+    assert call(2, 100, 64, 77) == ob.OB_EUNSUPPORTED
+    assert call(1, 64, 64, 64, wsb=16) == ob.OB_EWORKSPACE
+    assert ob.ob_gemm_workspace_bytes(0, 64, 64, 64) == 0
+    assert ob.ob_gemm_workspace_bytes(2, 128, 64, 100) >= (128 + 64) * 128 * 2
+    assert ob.lib.ob_debug_materialize_mask(C.byref(_seg([0, 4]).c), 1, None, None) == ob.OB_EINVAL
