@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: forward + backward of a transformer-block stack over balanced, packed
+variable-length mini-batches on ONE MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {2,3,4,5}] [--seed S]
+                    [--spread-batches N] [--skip-cpu-baseline]
+
+A step = build the segment offsets of the next balanced mini-batch (host), upload them, run all L
+blocks forward and then backward (every row of the hot path).  Inputs (weights, activations) are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+metric value = algorithmic FLOPs / time: GEMM 2MNK for the four linears (x3 for fwd + dgrad +
+wgrad), attention 4 nq d A(s) per segment (A = s^2, or s(s+1)/2 causal; x3), nothing else counted
+(no masked score entries, no recomputation, no elementwise work).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CUs x 2.4 GHz x 4096 FLOP/clk/CU
+PEAK_HBM_GBS = 8000.0
+PAPER_CONTEXT = ("paper reports ~1.8x end-to-end speed-up (GPU-days, A100) over InternVL-Chat's "
+                 "open-source training code; it publishes no kernel-level number")
+
+
+def step_flops(shape, cu, n_blocks):
+    s = np.diff(np.asarray(cu, dtype=np.int64)).astype(np.float64)
+    T = float(cu[-1])
+    H, d, nq = shape.hidden, shape.head_dim, shape.n_q_heads
+    gemm = 2.0 * H * shape.d_qkv + 2.0 * H * nq * d + 2.0 * H * shape.up_rows + 2.0 * H * shape.mlp_dim
+    area = (s * (s + 1) / 2).sum() if shape.mask == 1 else (s * s).sum()
+    return 3.0 * n_blocks * (T * gemm + 4.0 * nq * d * area)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--spread-batches", type=int, default=50)
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2407_20761_amd as ob
+    import synth_inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    shape = si.CONFIGS[args.config]
+    L = shape.n_blocks
+    desc = ob.make_desc(shape)
+
+    # ---- host side: synthetic dataset -> balanced groups (Alg. 1) and the random baseline ----
+    tiles, tok = si.synthetic_dataset(20000, args.seed)
+    t0 = time.perf_counter()
+    if shape.kind == "llm":        # token budget closes the groups
+        Qv, Qt, Qvm, Qtm = 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128
+    else:                          # tile budget closes the groups
+        Qv, Qt, Qvm, Qtm = shape.budget, 10 ** 9, shape.budget, 10 ** 9
+    groups, leftover, per_iter = ob.ob_pack_isf(tiles, tok, Qv, Qt, Qvm, Qtm, 10, args.seed)
+    packer_ms = (time.perf_counter() - t0) * 1e3
+    B = max(1, int(round(float(np.mean([len(g) for g in groups])))))
+    rgroups, _ = ob.ob_pack_random(len(tiles), B, args.seed)
+
+    def cu_of(group):
+        if shape.kind == "llm":
+            return ob.ob_build_cu_seqlens_llm(group, tok)[0]
+        return ob.ob_build_cu_seqlens_vit(int(tiles[group].sum()), si.VIT_TILE_TOKENS)
+
+    n_spread = min(args.spread_batches, len(groups), len(rgroups))
+    n_used = max(args.steps + args.warmup, n_spread, 1)
+    bal = [groups[i % len(groups)] for i in range(n_used)]
+    rnd = rgroups[:n_spread]
+    Tmax = max(int(cu_of(g)[-1]) for g in bal + rnd)
+
+    # ---- device state, resident before the timed region ---------------------------------------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    weights, grads = [], []
+    for _ in range(L):
+        w = {}
+        for name, shp in si.weight_shapes(shape).items():
+            t = torch.randn(shp, generator=gen, device=dev, dtype=torch.float32) * 0.02
+            if name in ("n1_g", "n2_g"):
+                t += 1.0
+            w[name] = t.to(torch.bfloat16)
+        weights.append(w)
+        grads.append({n: torch.zeros_like(t) for n, t in w.items()})
+    H = shape.hidden
+    acts = [torch.empty((Tmax, H), dtype=torch.bfloat16, device=dev) for _ in range(L + 1)]
+    acts[0].copy_((torch.randn((Tmax, H), generator=gen, device=dev) * 0.02).to(torch.bfloat16))
+    dy = torch.randn((Tmax, H), generator=gen, device=dev).to(torch.bfloat16)
+    gbuf = [torch.empty((Tmax, H), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    saved = [torch.empty(ob.ob_block_saved_bytes(desc, Tmax), dtype=torch.uint8, device=dev)
+             for _ in range(L)]
+    ws = torch.empty(ob.ob_block_workspace_bytes(desc, Tmax), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(group):
+        cu = cu_of(group)                       # host: segment offsets of this mini-batch
+        seg = ob.Segments(cu, device=dev)       # upload
+        T = int(cu[-1])
+        for i in range(L):
+            ob.ob_block_fwd(desc, weights[i], acts[i][:T], acts[i + 1][:T], saved[i], seg, ws, stream)
+        g_in = dy[:T]
+        for i in reversed(range(L)):
+            g_out = gbuf[i & 1][:T]
+            ob.ob_block_bwd(desc, weights[i], grads[i], 0, acts[i][:T], g_in, g_out, saved[i], seg,
+                            ws, stream)
+            g_in = g_out
+        return cu
+
+    for i in range(args.warmup):
+        step(bal[i])
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps ----------------------------------------------------------
+    timed = bal[args.warmup:args.warmup + args.steps]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    flops = 0.0
+    tokens = 0
+    for g in timed:
+        cu = step(g)
+        flops += step_flops(shape, cu, L)
+        tokens += int(cu[-1])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    tflops = flops / elapsed / 1e12
+
+    # ---- same K steps again with every kernel bracketed by HIP events on its stream -----------
+    ob.ob_prof_begin(200000)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for g in timed:
+        step(g)
+    torch.cuda.synchronize()
+    prof_elapsed = time.perf_counter() - t0
+    prof = ob.ob_prof_end()
+    kernels = {}
+    for name, (ms, cnt, work) in prof.items():
+        mfma = name in ("gemm", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv")
+        rate = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
+        kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
+                         "avg_us": 1e3 * ms / cnt, "bound": "mfma" if mfma else "hbm",
+                         "achieved": rate, "unit": "TFLOP/s" if mfma else "GB/s",
+                         "frac": rate / (PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS)}
+    gms, gcnt, gwork = prof["gemm"]
+    g_ach = gwork / (gms * 1e-3) / 1e12
+    roofline = {"kernel": "gemm_nt_kernel (bf16 MFMA 32x32x16)", "bound": "mfma",
+                "achieved": g_ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": g_ach / PEAK_BF16_TFLOPS, "traffic": None,
+                "avg_launch_us": 1e3 * gms / gcnt, "launches": gcnt,
+                "flops_per_launch_avg": gwork / gcnt,
+                "share_of_step_time": gms / (prof_elapsed * 1e3)}
+
+    # ---- step-time spread: balanced vs random grouping ----------------------------------------
+    spread = None
+    if n_spread > 0:
+        def time_batches(batch_list):
+            out, toks = [], []
+            for g in batch_list:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                cu = step(g)
+                e1.record(stream)
+                e1.synchronize()
+                out.append(e0.elapsed_time(e1))
+                toks.append(int(cu[-1]))
+            return np.asarray(out), toks
+
+        def stats(ms, toks):
+            m = float(ms.mean())
+            return {"n": len(ms), "mean_ms": m, "cv": float(ms.std() / m),
+                    "range_over_mean": float((ms.max() - ms.min()) / m),
+                    "time_dist_ratio": float(((ms.max() - ms) / ms.max()).mean()),
+                    "token_dist_ratio": ob.ob_dist_ratio(toks),
+                    "tokens_min": int(min(toks)), "tokens_max": int(max(toks))}
+
+        step(bal[0]); step(rnd[0])
+        torch.cuda.synchronize()
+        bms, btok = time_batches(bal[:n_spread])
+        rms, rtok = time_batches(rnd)
+        pad = float(np.mean([ob.ob_pad_ratio(tok[g].astype(np.int64)) for g in rnd]))
+        spread = {"balanced": stats(bms, btok), "random": stats(rms, rtok),
+                  "random_group_size": B, "random_pad_ratio_if_padded": pad,
+                  "balanced_pad_ratio": 0.0}
+
+    # ---- the oracle on the host cores, bounded sample -----------------------------------------
+    cpu = None
+    if not args.skip_cpu_baseline:
+        from oracle import block as orc
+        cu = cu_of(bal[0])
+        # about 8 TFLOP of oracle work (10-30 s on the host cores), in whole segments
+        per_token = step_flops(shape, np.array([0, 1]), 1)
+        n = max(1, int(np.searchsorted(cu, 8e12 / per_token, side="right")) - 1)
+        cu_s = cu[:n + 1].astype(np.int64)
+        Ts = int(cu_s[-1])
+        w_np = si.block_weights(shape, seed=args.seed)
+        x_np, dy_np = si.activations(Ts, H, seed=args.seed)
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        t0 = time.perf_counter()
+        y_ref, cache = orc.block_fwd(shape, w_np, x_np, cu_s)
+        orc.block_bwd(shape, w_np, cache, dy_np, cu_s)
+        cpu_s = time.perf_counter() - t0
+        cpu_flops = step_flops(shape, cu_s, 1)
+        cpu = {"value": cpu_flops / cpu_s / 1e12, "unit": "TFLOP/s", "cores": int(cores),
+               "kind": "oracle",
+               "sample": f"1 of {L} blocks fwd+bwd, first {n} whole segments ({Ts} tokens) of "
+                         f"balanced batch 0, fp64 numpy, {cpu_s:.1f} s",
+               "full_step_extrapolated_s": step_flops(shape, cu_of(bal[0]), L) / (cpu_flops / cpu_s)}
+
+    out = {
+        "metric": "block_stack_fwd_bwd_tflops", "value": tflops, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {shape.name}, {L} blocks, hidden {H}, "
+                               f"{shape.n_q_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, "
+                               f"mlp {shape.mlp_dim}, balanced packed batches of "
+                               f"{shape.budget} {'tokens' if shape.kind == 'llm' else 'tiles x 1025 tokens'}",
+                   "n_blocks": L, "tokens_per_step": tokens / args.steps, "seed": args.seed,
+                   "grouping": "ISF, 10 iterations, Q' = Q - 128 tokens" if shape.kind == "llm"
+                   else "ISF, 10 iterations, tile budget"},
+        "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops": PEAK_BF16_TFLOPS,
+        "tokens_per_s": tokens / elapsed,
+        "flops_per_step": flops / args.steps,
+        "ms_per_step_with_event_profiling": prof_elapsed * 1e3 / args.steps,
+        "packer": {"ms": packer_ms, "samples": int(len(tiles)), "groups": len(groups),
+                   "leftover": int(len(leftover)), "groups_per_iter": [int(a) for a in per_iter]},
+        "roofline": roofline, "kernels": kernels, "spread": spread, "cpu_baseline": cpu,
+        "context": PAPER_CONTEXT,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

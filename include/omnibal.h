@@ -83,6 +83,18 @@ const char *ob_last_error(void);
 /* 1 when the library was built with its gfx950 kernels (always, for the shipped build). */
 int ob_has_device_code(void);
 
+/* ---- opt-in per-kernel timing for the bench's roofline lines ----------------------------------
+ * Between ob_prof_begin and ob_prof_end every kernel the library launches is bracketed by a pair
+ * of HIP events on its own stream.  ob_prof_end waits for them and returns, per kernel class
+ * (ob_prof_class_name), the summed duration in ms, the launch count and the summed algorithmic
+ * work (FLOPs for the MFMA classes gemm / attn_*, bytes for the HBM-bound classes).  Not thread
+ * safe; at most max_launches launches are recorded (more -> OB_EWORKSPACE from ob_prof_end). */
+int ob_prof_num_classes(void);
+const char *ob_prof_class_name(int cls);
+int ob_prof_begin(int max_launches);
+int ob_prof_end(double *ms_per_class, int64_t *launches_per_class, double *work_per_class,
+                int n_classes);
+
 /* ---- varlen attention (step a4 / b4 of the block) --------------------------------------------
  * For query head a, KV head a / (nq / nkv):  S_ij = scale * q_i . k_j;  allowed(i, j) <=>
  * same segment (and j <= i when causal);  o_i = sum_j softmax_j(S_ij) v_j over allowed j;

@@ -10,6 +10,11 @@ import ctypes as C
 import os
 
 import numpy as np
+# PyTorch must be loaded BEFORE the library: the torch wheel ships its own HIP/HSA runtime
+# (soname libamdhip64.so.7) and libomnibal.so binds to whichever libamdhip64.so.7 is already in
+# the process.  Loading the library first would pull in a second runtime from /opt/rocm, and two
+# HSA runtimes in one process cannot both own the device.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libomnibal.so")
@@ -64,6 +69,10 @@ _i32p, _i64p = C.POINTER(C.c_int32), C.POINTER(C.c_int64)
 _SIGNATURES = {
     "ob_last_error": (C.c_char_p, []),
     "ob_has_device_code": (_I, []),
+    "ob_prof_num_classes": (_I, []),
+    "ob_prof_class_name": (C.c_char_p, [_I]),
+    "ob_prof_begin": (_I, [_I]),
+    "ob_prof_end": (_I, [C.POINTER(C.c_double), _i64p, C.POINTER(C.c_double), _I]),
     "ob_varlen_attn_fwd": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _SEG, _I, _I, _I, _F, _I, _I, _P]),
     "ob_varlen_attn_bwd_workspace_bytes": (_Z, [_I, _I]),
     "ob_varlen_attn_bwd": (_I, [_P] * 9 + [_I, _I, _I, _SEG, _I, _I, _I, _F, _I, _I, _P, _Z, _P]),
@@ -105,16 +114,26 @@ def _ptr(t):
 
 
 def _stream(stream=None):
-    import torch
     s = torch.cuda.current_stream() if stream is None else stream
     return C.c_void_p(s.cuda_stream)
+
+
+def ob_prof_begin(max_launches=65536):
+    _check(lib.ob_prof_begin(int(max_launches)))
+
+
+def ob_prof_end() -> dict:
+    """{class name: (ms, launches, work)} for the classes that were launched"""
+    n = lib.ob_prof_num_classes()
+    ms, cnt, work = (C.c_double * n)(), (C.c_int64 * n)(), (C.c_double * n)()
+    _check(lib.ob_prof_end(ms, cnt, work, n))
+    return {lib.ob_prof_class_name(i).decode(): (ms[i], cnt[i], work[i]) for i in range(n) if cnt[i]}
 
 
 class Segments:
     """Holds the host and device copies of cu_seqlens alive and exposes the C struct."""
 
     def __init__(self, cu_host, device="cuda", max_seqlen=None, cu_dev=None):
-        import torch
         self.cu_host = np.ascontiguousarray(cu_host, dtype=np.int32)
         self.cu_dev = (torch.from_numpy(self.cu_host).to(device) if cu_dev is None and device
                        else cu_dev)

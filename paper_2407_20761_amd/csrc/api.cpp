@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "ob_internal.h"
 
@@ -23,6 +24,32 @@ int check_launch(const char *what) {
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(OB_EHIP, "%s: %s", what, hipGetErrorString(e));
     return OB_OK;
+}
+
+// ---- opt-in kernel timing ------------------------------------------------------------------
+namespace {
+struct ProfState {
+    bool on = false;
+    int used = 0;
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int> cls;
+    std::vector<double> work;
+};
+ProfState g_prof;
+const char *const kClassNames[K_COUNT] = {
+    "gemm", "transpose", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "attn_delta", "norm_fwd",
+    "norm_bwd", "rotary", "act_fwd", "act_bwd", "colsum", "reduce_partials"};
+}  // namespace
+
+ProfScope::ProfScope(int c, hipStream_t s, double work) : slot(-1), stream(s) {
+    if (!g_prof.on || g_prof.used >= (int)g_prof.start.size()) return;
+    slot = g_prof.used++;
+    g_prof.cls[slot] = c;
+    g_prof.work[slot] = work;
+    (void)hipEventRecord(g_prof.start[slot], stream);
+}
+ProfScope::~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(g_prof.stop[slot], stream);
 }
 
 namespace {
@@ -143,6 +170,48 @@ inline const unsigned char *at(const void *base, size_t off) { return (const uns
 using namespace ob;
 
 extern "C" const char *ob_last_error(void) { return g_err; }
+
+extern "C" int ob_prof_num_classes(void) { return K_COUNT; }
+extern "C" const char *ob_prof_class_name(int cls) { return cls >= 0 && cls < K_COUNT ? kClassNames[cls] : ""; }
+
+extern "C" int ob_prof_begin(int max_launches) {
+    if (g_prof.on) return fail(OB_EINVAL, "ob_prof_begin: already profiling");
+    if (max_launches < 1 || max_launches > (1 << 20)) return fail(OB_EINVAL, "ob_prof_begin: max_launches out of range");
+    g_prof.start.assign(max_launches, nullptr);
+    g_prof.stop.assign(max_launches, nullptr);
+    g_prof.cls.assign(max_launches, 0);
+    g_prof.work.assign(max_launches, 0.0);
+    for (int i = 0; i < max_launches; ++i)
+        if (hipEventCreate(&g_prof.start[i]) != hipSuccess || hipEventCreate(&g_prof.stop[i]) != hipSuccess)
+            return fail(OB_EHIP, "ob_prof_begin: hipEventCreate failed");
+    g_prof.used = 0;
+    g_prof.on = true;
+    return OB_OK;
+}
+
+extern "C" int ob_prof_end(double *ms_per_class, int64_t *launches_per_class, double *work_per_class,
+                           int n_classes) {
+    if (!g_prof.on) return fail(OB_EINVAL, "ob_prof_end: not profiling");
+    if (!ms_per_class || !launches_per_class || !work_per_class || n_classes < K_COUNT)
+        return fail(OB_EINVAL, "ob_prof_end: output arrays must hold ob_prof_num_classes() entries");
+    g_prof.on = false;
+    for (int c = 0; c < K_COUNT; ++c) { ms_per_class[c] = 0; launches_per_class[c] = 0; work_per_class[c] = 0; }
+    int rc = OB_OK;
+    for (int i = 0; i < g_prof.used; ++i) {
+        float ms = 0.f;
+        if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess ||
+            hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess)
+            rc = fail(OB_EHIP, "ob_prof_end: event query failed");
+        ms_per_class[g_prof.cls[i]] += ms;
+        launches_per_class[g_prof.cls[i]] += 1;
+        work_per_class[g_prof.cls[i]] += g_prof.work[i];
+    }
+    const bool overflow = g_prof.used >= (int)g_prof.start.size();
+    for (size_t i = 0; i < g_prof.start.size(); ++i) { (void)hipEventDestroy(g_prof.start[i]); (void)hipEventDestroy(g_prof.stop[i]); }
+    g_prof.start.clear(); g_prof.stop.clear(); g_prof.used = 0;
+    if (rc == OB_OK && overflow) return fail(OB_EWORKSPACE, "ob_prof_end: more launches than max_launches; totals are partial");
+    return rc;
+}
 extern "C" int ob_has_device_code(void) { return 1; }
 
 extern "C" int ob_varlen_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,

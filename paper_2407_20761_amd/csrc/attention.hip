@@ -418,6 +418,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
         }
 }
 
+// algorithmic forward FLOPs: 4 nq d sum_seg A(s), A = s^2 or s (s + 1) / 2 (causal)
+double attn_flops(const ob_segments *seg, int nq, int d, bool causal) {
+    double area = 0;
+    for (int j = 0; j < seg->n_seg; ++j) {
+        const double len = seg->cu_host[j + 1] - seg->cu_host[j];
+        area += causal ? len * (len + 1) / 2 : len * len;
+    }
+    return 4.0 * nq * d * area;
+}
+
 int count_tiles(const ob_segments *seg, int tile_rows) {
     long n = 0;
     for (int j = 0; j < seg->n_seg; ++j)
@@ -443,6 +453,7 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
                      int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale,
                      int mask, hipStream_t s) {
     const bool causal = mask == OB_MASK_SEG_CAUSAL;
+    ProfScope prof(K_ATTN_FWD, s, attn_flops(seg, nq, d, causal));
     const dim3 grid(count_tiles(seg, QT), nq);
     OB_ATTN_DISPATCH(attn_fwd_kernel, grid, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
                      (__bf16 *)o, lse, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, seg->total_tokens,
@@ -456,9 +467,13 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     const bool causal = mask == OB_MASK_SEG_CAUSAL;
     const int tiles = count_tiles(seg, QT);
     const dim3 grid_q(tiles, nq), grid_kv(tiles, nkv);
+    {
+    ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
     OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, (const __bf16 *)d_o, (const __bf16 *)q,
                      (const __bf16 *)k, (const __bf16 *)v, lse, delta, (__bf16 *)dq, ldq, ldkv, ldo,
                      seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
+    }
+    ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
     OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_kv, (const __bf16 *)d_o, (const __bf16 *)q,
                      (const __bf16 *)k, (const __bf16 *)v, lse, delta, (__bf16 *)dk, (__bf16 *)dv, ldq,
                      ldkv, ldo, seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);

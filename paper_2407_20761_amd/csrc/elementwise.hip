@@ -173,16 +173,35 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
 }
 
 // out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]; fixed summation order.
+// A workgroup owns 32 columns; its 8 groups of 32 lanes each sum every 8th partial (four
+// independent chains per lane to keep loads in flight), then the 8 sums are combined in LDS.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial,
                                                               int n_part, int stride,
                                                               __bf16 *__restrict__ out, int C,
                                                               int accumulate) {
-    const int c = blockIdx.x * 256 + threadIdx.x;
-    if (c >= C) return;
-    float s = 0.f;
-    for (int p = 0; p < n_part; ++p) s += partial[(size_t)p * stride + c];
-    if (accumulate) s += (float)out[c];
-    out[c] = (__bf16)s;
+    __shared__ float red[8][32];
+    const int col = threadIdx.x & 31, pl = threadIdx.x >> 5;
+    const int c = blockIdx.x * 32 + col;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (c < C) {
+        int p = pl;
+        for (; p + 24 < n_part; p += 32) {
+            s0 += partial[(size_t)p * stride + c];
+            s1 += partial[(size_t)(p + 8) * stride + c];
+            s2 += partial[(size_t)(p + 16) * stride + c];
+            s3 += partial[(size_t)(p + 24) * stride + c];
+        }
+        for (; p < n_part; p += 8) s0 += partial[(size_t)p * stride + c];
+    }
+    red[pl][col] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (pl == 0 && c < C) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += red[i][col];
+        if (accumulate) s += (float)out[c];
+        out[c] = (__bf16)s;
+    }
 }
 
 // partial[blockIdx.y][c] = sum over the rows blockIdx.y, +gridDim.y, ... of in[row][c]
@@ -345,6 +364,7 @@ __global__ __launch_bounds__(256) void mask_kernel(const int32_t *__restrict__ c
 
 void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *beta, void *h,
                      float *stats, int T, int H, float eps, hipStream_t s) {
+    ProfScope prof(K_NORM_FWD, s, 4.0 * T * H);
     if (norm == OB_LAYERNORM)
         hipLaunchKernelGGL(norm_fwd_kernel<true>, dim3(T), dim3(NORM_THREADS), 0, s, (const __bf16 *)x,
                            (const __bf16 *)gamma, (const __bf16 *)beta, (__bf16 *)h, stats, T, H, eps);
@@ -357,6 +377,7 @@ int norm_bwd_partials(int T) { return T < 1024 ? T : 1024; }
 
 void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
                      const void *dres, void *dx, float *partial, int T, int H, hipStream_t s) {
+    ProfScope prof(K_NORM_BWD, s, 8.0 * T * H);
     const int nb = norm_bwd_partials(T);
     if (norm == OB_LAYERNORM)
         hipLaunchKernelGGL(norm_bwd_kernel<true>, dim3(nb), dim3(NORM_THREADS), 0, s, (const __bf16 *)dh,
@@ -370,24 +391,28 @@ void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats
 
 void launch_reduce_partials(const float *partial, int n_part, int stride, void *out, int C,
                             int accumulate, hipStream_t s) {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C + 255) / 256), dim3(256), 0, s, partial, n_part,
+    ProfScope prof(K_REDUCE, s, 4.0 * n_part * C);
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C + 31) / 32), dim3(256), 0, s, partial, n_part,
                        stride, (__bf16 *)out, C, accumulate);
 }
 
 int colsum_partials(int T) { return T < 256 ? T : 256; }
 
 void launch_colsum(const void *in, int T, int C, int ld, float *partial, hipStream_t s) {
+    ProfScope prof(K_COLSUM, s, 2.0 * T * C);
     dim3 grid((C / 8 + 255) / 256, colsum_partials(T));
     hipLaunchKernelGGL(colsum_kernel, grid, dim3(256), 0, s, (const __bf16 *)in, T, C, ld, partial);
 }
 
 void launch_rotary(void *qkv, int ld, int T, int n_heads_rot, int d, const int32_t *cu_dev, int n_seg,
                    float base, float sign, hipStream_t s) {
+    ProfScope prof(K_ROTARY, s, 4.0 * T * n_heads_rot * d);
     hipLaunchKernelGGL(rotary_kernel, dim3(T), dim3(256), 0, s, (__bf16 *)qkv, ld, T, n_heads_rot, d,
                        cu_dev, n_seg, log2f(base), sign);
 }
 
 void launch_act_fwd(int mlp, const void *up, void *act, int T, int F, hipStream_t s) {
+    ProfScope prof(K_ACT_FWD, s, (mlp == OB_SWIGLU ? 6.0 : 4.0) * T * F);
     const long n_vec = (long)T * (F / 8);
     const int blocks = (int)((n_vec + 255) / 256 < 65536 ? (n_vec + 255) / 256 : 65536);
     if (mlp == OB_SWIGLU)
@@ -399,6 +424,7 @@ void launch_act_fwd(int mlp, const void *up, void *act, int T, int F, hipStream_
 }
 
 void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T, int F, hipStream_t s) {
+    ProfScope prof(K_ACT_BWD, s, (mlp == OB_SWIGLU ? 10.0 : 6.0) * T * F);
     const long n_vec = (long)T * (F / 8);
     const int blocks = (int)((n_vec + 255) / 256 < 65536 ? (n_vec + 255) / 256 : 65536);
     if (mlp == OB_SWIGLU)
@@ -411,6 +437,7 @@ void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T,
 
 void launch_attn_delta(const void *d_o, const void *o, int ldo, float *delta, int T, int nq, int d,
                        hipStream_t s) {
+    ProfScope prof(K_ATTN_DELTA, s, 4.0 * T * nq * d);
     const long threads = (long)T * nq * (d / 8);
     hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
                        (const __bf16 *)d_o, (const __bf16 *)o, ldo, delta, T, nq, d);

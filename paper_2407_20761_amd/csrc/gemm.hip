@@ -213,7 +213,8 @@ void launch_nt(int M, int N, int K, const void *A, int lda, const void *B, int l
 }  // namespace
 
 void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
-                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s) {
+                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s, int k_algo) {
+    ProfScope prof(K_GEMM, s, 2.0 * M * N * (k_algo > 0 ? k_algo : K));
     // big tiles when they still fill the 256 CUs a few times over, smaller ones otherwise
     const long tiles_big = (long)((M + 255) / 256) * ((N + 255) / 256);
     if (tiles_big >= 512)
@@ -224,6 +225,7 @@ void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, 
 
 void launch_transpose_pad(const void *in, int rows, int cols, int ld_in, void *out, int rows_pad,
                           hipStream_t s) {
+    ProfScope prof(K_TRANSPOSE, s, 2.0 * rows * cols + 2.0 * rows_pad * cols);
     dim3 grid((rows_pad + 63) / 64, (cols + 63) / 64);
     hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, (const unsigned short *)in,
                        rows, cols, ld_in, (unsigned short *)out, rows_pad);
@@ -255,7 +257,7 @@ int gemm_any(int layout, int M, int N, int K, const void *A, const void *B, void
         unsigned char *bt = at + align_up((size_t)M * kp * 2, 256);
         launch_transpose_pad(A, K, M, M, at, kp, s);  // A[K,M] -> At[M,kp]
         launch_transpose_pad(B, K, N, N, bt, kp, s);  // B[K,N] -> Bt[N,kp]
-        launch_gemm_nt(M, N, kp, at, kp, bt, kp, C, N, bias, R, N, s);
+        launch_gemm_nt(M, N, kp, at, kp, bt, kp, C, N, bias, R, N, s, K);
     }
     return check_launch("gemm");
 }

@@ -14,10 +14,26 @@ int check_launch(const char *what);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// ---- opt-in per-kernel-class timing (ob_prof_begin / ob_prof_end) --------------------------
+enum KClass {
+    K_GEMM = 0, K_TRANSPOSE, K_ATTN_FWD, K_ATTN_BWD_DQ, K_ATTN_BWD_DKV, K_ATTN_DELTA, K_NORM_FWD,
+    K_NORM_BWD, K_ROTARY, K_ACT_FWD, K_ACT_BWD, K_COLSUM, K_REDUCE, K_COUNT
+};
+// Brackets one kernel launch with a pair of events on its stream while profiling is on;
+// `work` is the launch's algorithmic FLOPs (MFMA kernels) or bytes (HBM-bound kernels).
+struct ProfScope {
+    ProfScope(int cls, hipStream_t s, double work);
+    ~ProfScope();
+    int slot;
+    hipStream_t stream;
+};
+
 // ---- GEMM (gemm.hip) ---------------------------------------------------------------------
 // C[M,N] = A[M,K] B[N,K]^T (+bias[N]) (+R[M,N]); K % 64 == 0, N % 8 == 0, any M.
+// k_algo (<= K, 0 = K): the contraction length that counts as algorithmic work when K is padded.
 void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
-                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s);
+                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s,
+                    int k_algo = 0);
 // out[c, r] = in[r, c] for r < rows, 0 for rows <= r < rows_pad; in ld = ld_in, out ld = rows_pad
 void launch_transpose_pad(const void *in, int rows, int cols, int ld_in, void *out, int rows_pad,
                           hipStream_t s);
