@@ -9,6 +9,8 @@
 // lane l supplies row (l % 32), k = 8 (l / 32) .. +7 of each operand, i.e. one 16-byte LDS read.
 // The weight rows are fed as the MFMA's first operand so that a lane's four consecutive
 // accumulator registers are four consecutive columns n of one output row m (8-byte stores).
+#include <cmath>
+
 #include "ob_internal.h"
 
 namespace ob {
@@ -20,9 +22,10 @@ typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 namespace {
 
-constexpr int BK = 64;  // k per LDS stage: 8 chunks of 16 bytes per row
+#define OB_LDS __attribute__((address_space(3)))
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+constexpr int BK = 64;           // k per LDS stage: 8 chunks of 16 bytes = 128 bytes per row
+constexpr int ROW_BYTES = BK * 2;
 
 // tile id -> (tile_m, tile_n): each XCD (blocks are dealt round-robin to the 8 XCDs) gets one
 // contiguous range of tile ids, and ids walk groups of GM tile-rows column by column, so the
@@ -43,112 +46,165 @@ __device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int &tm, i
 }
 
 template <int BM, int BN, int WM, int WN>
+struct Cfg {
+    static constexpr int NW = WM * WN, NT = NW * 64;
+    static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 MFMA tiles per wave
+    // a wave instruction of the LDS-direct load fills 1 KB = 8 rows of a tile
+    static constexpr int A_LD = BM / 8 / NW, B_LD = BN / 8 / NW;
+    static constexpr int STAGE = (BM + BN) * ROW_BYTES;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wave count mismatch");
+};
+
+// Per-thread addressing state.  LDS tiles are [row][8 chunks of 16 B]; the chunk stored at
+// physical position p of row r is logical chunk p ^ f(r), f(r) = (r ^ ((r >> 3) & 1)) & 7, which
+// keeps the 16-byte reads of 8 as well as of 16 consecutive rows on distinct banks.
+template <int BM, int BN, int WM, int WN>
+struct Ctx {
+    using C = Cfg<BM, BN, WM, WN>;
+    const unsigned char *a_base, *b_base;        // tile origin in A / B (wave-uniform)
+    uint32_t a_off[C::A_LD], b_off[C::B_LD];     // this lane's byte offset for each of its loads
+    int wave;
+    int xa[BK / 16], xb[BK / 16];                // this lane's LDS read offset for k-step t
+};
+
+// Asynchronous global -> LDS copy of one K-step's A and B tiles: lane l of a wave instruction
+// supplies the global address of the 16 bytes that land at LDS base + 16 l.
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void issue_loads(unsigned char OB_LDS *__restrict__ dst,
+                                            const Ctx<BM, BN, WM, WN> &c, int kbytes) {
+    using C = Cfg<BM, BN, WM, WN>;
+#pragma unroll
+    for (int p = 0; p < C::A_LD; ++p)
+        __builtin_amdgcn_global_load_lds(c.a_base + kbytes + c.a_off[p],
+                                         dst + (c.wave * C::A_LD + p) * 1024, 16, 0, 0);
+#pragma unroll
+    for (int p = 0; p < C::B_LD; ++p)
+        __builtin_amdgcn_global_load_lds(c.b_base + kbytes + c.b_off[p],
+                                         dst + BM * ROW_BYTES + (c.wave * C::B_LD + p) * 1024, 16, 0, 0);
+}
+
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void load_frags(const unsigned char OB_LDS *__restrict__ src,
+                                           const Ctx<BM, BN, WM, WN> &c, int t,
+                                           bf16x8 (&af)[Cfg<BM, BN, WM, WN>::TM],
+                                           bf16x8 (&bfr)[Cfg<BM, BN, WM, WN>::TN]) {
+    using C = Cfg<BM, BN, WM, WN>;
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) af[i] = *(const bf16x8 OB_LDS *)(src + c.xa[t] + i * 32 * ROW_BYTES);
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) bfr[j] = *(const bf16x8 OB_LDS *)(src + c.xb[t] + j * 32 * ROW_BYTES);
+}
+
+// Multiply one LDS stage (4 k-steps of 16).  The fragments of k-step t+1 are read while the
+// MFMAs of k-step t run; the scheduling groups pin "one LDS read, one MFMA" pairs at the front of
+// each k-step so every read has at least half a k-step of MFMA work to hide behind.
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void compute_stage(const unsigned char OB_LDS *__restrict__ src,
+                                              const Ctx<BM, BN, WM, WN> &c,
+                                              f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
+    using C = Cfg<BM, BN, WM, WN>;
+    bf16x8 af[2][C::TM], bfr[2][C::TN];
+    load_frags<BM, BN, WM, WN>(src, c, 0, af[0], bfr[0]);
+#pragma unroll
+    for (int t = 0; t < BK / 16; ++t) {
+        if (t + 1 < BK / 16) load_frags<BM, BN, WM, WN>(src, c, t + 1, af[(t + 1) & 1], bfr[(t + 1) & 1]);
+#pragma unroll
+        for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[t & 1][j], af[t & 1][i],
+                                                                   acc[i][j], 0, 0, 0);
+        if (t + 1 < BK / 16) {
+#pragma unroll
+            for (int r = 0; r < C::TM + C::TN; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// C[M,N] = A[M,K] B[N,K]^T (+bias) (+R).  Two LDS stages; the copy of K-step kt+1 is in flight
+// while K-step kt is multiplied; one barrier per K-step.
+template <int BM, int BN, int WM, int WN>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
     int M, int N, int K, const __bf16 *__restrict__ A, int lda, const __bf16 *__restrict__ B,
-    int ldb, __bf16 *__restrict__ C, int ldc, const __bf16 *__restrict__ bias,
+    int ldb, __bf16 *__restrict__ Cm, int ldc, const __bf16 *__restrict__ bias,
     const __bf16 *R, int ldr, int tiles_m, int tiles_n) {
-    constexpr int NT = WM * WN * 64;
-    constexpr int TM = BM / WM / 32;  // 32-row MFMA tiles per wave along m
-    constexpr int TN = BN / WN / 32;
-    constexpr int A_CHUNKS = BM * 8 / NT;  // 16-byte chunks per thread per stage
-    constexpr int B_CHUNKS = BN * 8 / NT;
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/thread mismatch");
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    // [2 stages][A tile BM*64 | B tile BN*64] bf16
-    constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-    auto a_tile = [&](int s) { return smem + s * STAGE_BYTES; };
-    auto b_tile = [&](int s) { return smem + s * STAGE_BYTES + BM * BK * 2; };
+    using C = Cfg<BM, BN, WM, WN>;
+    __shared__ __attribute__((aligned(1024))) unsigned char st0[C::STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char st1[C::STAGE];
 
     int tile_m, tile_n;
     tile_coords(tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = tile_m * BM, n0 = tile_n * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    Ctx<BM, BN, WM, WN> c;
+    c.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = c.wave / WN, wn = c.wave % WN;
     const int lx = lane & 31, lh = lane >> 5;
 
-    // global -> register staging addresses (row clamped into the matrix; out-of-range rows are
-    // computed on duplicate data and never stored)
-    const __bf16 *a_src[A_CHUNKS];
-    const __bf16 *b_src[B_CHUNKS];
-    int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
+    // rows past the matrix edge are clamped onto its last row: they are multiplied as duplicate
+    // data and never stored
+    c.a_base = (const unsigned char *)(A + (size_t)m0 * lda);
+    c.b_base = (const unsigned char *)(B + (size_t)n0 * ldb);
 #pragma unroll
-    for (int p = 0; p < A_CHUNKS; ++p) {
-        const int q = tid + p * NT, row = q >> 3, c = q & 7;
-        a_src[p] = A + (size_t)min(m0 + row, M - 1) * lda + c * 8;
-        a_dst[p] = row * (BK * 2) + swz(row, c) * 16;
+    for (int p = 0; p < C::A_LD; ++p) {
+        const int blk = c.wave * C::A_LD + p, row = blk * 8 + (lane >> 3);
+        const int ch = (lane & 7) ^ (((lane >> 3) ^ (blk & 1)) & 7);
+        c.a_off[p] = ((uint32_t)min(row, M - 1 - m0) * (uint32_t)lda + ch * 8) * 2u;
     }
 #pragma unroll
-    for (int p = 0; p < B_CHUNKS; ++p) {
-        const int q = tid + p * NT, row = q >> 3, c = q & 7;
-        b_src[p] = B + (size_t)min(n0 + row, N - 1) * ldb + c * 8;
-        b_dst[p] = row * (BK * 2) + swz(row, c) * 16;
+    for (int p = 0; p < C::B_LD; ++p) {
+        const int blk = c.wave * C::B_LD + p, row = blk * 8 + (lane >> 3);
+        const int ch = (lane & 7) ^ (((lane >> 3) ^ (blk & 1)) & 7);
+        c.b_off[p] = ((uint32_t)min(row, N - 1 - n0) * (uint32_t)ldb + ch * 8) * 2u;
+    }
+    const int f = (lx ^ ((lx >> 3) & 1)) & 7;
+#pragma unroll
+    for (int t = 0; t < BK / 16; ++t) {
+        c.xa[t] = (wm * (BM / WM) + lx) * ROW_BYTES + (((2 * t + lh) ^ f) * 16);
+        c.xb[t] = BM * ROW_BYTES + (wn * (BN / WN) + lx) * ROW_BYTES + (((2 * t + lh) ^ f) * 16);
     }
 
-    f32x16 acc[TM][TN];
+    f32x16 acc[C::TM][C::TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int j = 0; j < C::TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    u32x4 a_reg[A_CHUNKS], b_reg[B_CHUNKS];
-    auto load_global = [&](int k0) {
-#pragma unroll
-        for (int p = 0; p < A_CHUNKS; ++p) a_reg[p] = *(const u32x4 *)(a_src[p] + k0);
-#pragma unroll
-        for (int p = 0; p < B_CHUNKS; ++p) b_reg[p] = *(const u32x4 *)(b_src[p] + k0);
-    };
-    auto store_lds = [&](int s) {
-#pragma unroll
-        for (int p = 0; p < A_CHUNKS; ++p) *(u32x4 *)(a_tile(s) + a_dst[p]) = a_reg[p];
-#pragma unroll
-        for (int p = 0; p < B_CHUNKS; ++p) *(u32x4 *)(b_tile(s) + b_dst[p]) = b_reg[p];
-    };
-
+    unsigned char OB_LDS *s0 = (unsigned char OB_LDS *)st0;
+    unsigned char OB_LDS *s1 = (unsigned char OB_LDS *)st1;
     const int nk = K / BK;
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int s = kt & 1;
-        if (kt + 1 < nk) load_global((kt + 1) * BK);
-        const unsigned char *as = a_tile(s) + (wm * (BM / WM)) * (BK * 2);
-        const unsigned char *bs = b_tile(s) + (wn * (BN / WN)) * (BK * 2);
-#pragma unroll
-        for (int t = 0; t < BK / 16; ++t) {
-            bf16x8 af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row = i * 32 + lx;
-                af[i] = *(const bf16x8 *)(as + row * (BK * 2) +
-                                          swz(wm * (BM / WM) + row, 2 * t + lh) * 16);
-            }
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int row = j * 32 + lx;
-                bfr[j] = *(const bf16x8 *)(bs + row * (BK * 2) +
-                                           swz(wn * (BN / WN) + row, 2 * t + lh) * 16);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j],
-                                                                       0, 0, 0);
-        }
-        if (kt + 1 < nk) store_lds(s ^ 1);
+    constexpr int WAIT_VM0 = 0x0F70;  // s_waitcnt vmcnt(0) only
+    issue_loads<BM, BN, WM, WN>(s0, c, 0);
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
         __syncthreads();
+        issue_loads<BM, BN, WM, WN>(s1, c, (kt + 1) * ROW_BYTES);
+        compute_stage<BM, BN, WM, WN>(s0, c, acc);
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+        __syncthreads();
+        if (kt + 2 < nk) issue_loads<BM, BN, WM, WN>(s0, c, (kt + 2) * ROW_BYTES);
+        compute_stage<BM, BN, WM, WN>(s1, c, acc);
+    }
+    if (kt < nk) {
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+        __syncthreads();
+        compute_stage<BM, BN, WM, WN>(s0, c, acc);
     }
 
     // epilogue: lane holds, per MFMA tile, column m = lx and rows n = 8 g + 4 lh + (0..3)
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < C::TM; ++i) {
         const int m = m0 + wm * (BM / WM) + i * 32 + lx;
         if (m >= M) continue;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+        for (int j = 0; j < C::TN; ++j) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int n = n0 + wn * (BN / WN) + j * 32 + g * 8 + lh * 4;
@@ -169,7 +225,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
-                *(bf16x4 *)(C + (size_t)m * ldc + n) = o;
+                *(bf16x4 *)(Cm + (size_t)m * ldc + n) = o;
             }
         }
     }
@@ -198,14 +254,8 @@ template <int BM, int BN, int WM, int WN>
 void launch_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
                const void *bias, const void *R, int ldr, hipStream_t s) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    constexpr int smem = 2 * (BM + BN) * BK * 2;
     auto kern = gemm_nt_kernel<BM, BN, WM, WN>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), smem, s, M, N, K,
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), 0, s, M, N, K,
                        (const __bf16 *)A, lda, (const __bf16 *)B, ldb, (__bf16 *)C, ldc,
                        (const __bf16 *)bias, (const __bf16 *)R, ldr, tiles_m, tiles_n);
 }
@@ -215,10 +265,14 @@ void launch_nt(int M, int N, int K, const void *A, int lda, const void *B, int l
 void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
                     int ldc, const void *bias, const void *R, int ldr, hipStream_t s, int k_algo) {
     ProfScope prof(K_GEMM, s, 2.0 * M * N * (k_algo > 0 ? k_algo : K));
-    // big tiles when they still fill the 256 CUs a few times over, smaller ones otherwise
-    const long tiles_big = (long)((M + 255) / 256) * ((N + 255) / 256);
-    if (tiles_big >= 512)
-        launch_nt<256, 256, 2, 4>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
+    // 256x256 tiles run one workgroup per CU, 128x128 tiles two; take the shape whose last round
+    // of tiles leaves fewer CUs idle (the small tile pays ~15 % in operand re-reads)
+    const double big = (double)((M + 255) / 256) * ((N + 255) / 256);
+    const double small = (double)((M + 127) / 128) * ((N + 127) / 128);
+    const double eff_big = big / (ceil(big / 256.0) * 256.0);
+    const double eff_small = 0.85 * small / (ceil(small / 512.0) * 512.0);
+    if (eff_big >= eff_small)
+        launch_nt<256, 256, 2, 2>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
     else
         launch_nt<128, 128, 2, 2>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
 }
