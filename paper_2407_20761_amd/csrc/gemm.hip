@@ -19,6 +19,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace {
 
@@ -198,34 +199,57 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
         compute_stage<BM, BN, WM, WN>(s0, c, acc);
     }
 
-    // epilogue: lane holds, per MFMA tile, column m = lx and rows n = 8 g + 4 lh + (0..3)
+    // Epilogue.  A lane holds, per MFMA tile, output row m = lx and columns n = 8 g + 4 lh + (0..3):
+    // stored directly, every lane of a store would touch a different cache line.  Instead each
+    // wave transposes 32-row slabs of its tile through its share of the (now idle) stage buffers
+    // as fp32, and reads them back so that 16 (or 8) consecutive lanes cover one contiguous row
+    // segment; bias and residual are added on the way out, then one rounding to bf16.
+    __syncthreads();  // every wave is done reading the last stage
+    constexpr int CW = BN / WN;            // columns of the wave's tile
+    constexpr int RSTR = CW * 4 + 16;      // fp32 row stride in LDS, padded against bank conflicts
+    constexpr int LPR = CW / 8;            // lanes per row on the way out (8 columns each)
+    constexpr int RPI = 64 / LPR;          // rows per read instruction
+    static_assert(32 * RSTR <= C::STAGE / (C::NW / 2), "slab does not fit the wave's LDS share");
+    unsigned char OB_LDS *slab = (c.wave < C::NW / 2 ? s0 : s1) + (c.wave % (C::NW / 2)) * (C::STAGE / (C::NW / 2));
+    const int n_out = n0 + wn * CW + (lane % LPR) * 8;
+    float bv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) bv[e] = 0.f;
+    if (bias && n_out < N) {
+        const bf16x8 b8 = *(const bf16x8 *)(bias + n_out);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bv[e] = (float)b8[e];
+    }
 #pragma unroll
     for (int i = 0; i < C::TM; ++i) {
-        const int m = m0 + wm * (BM / WM) + i * 32 + lx;
-        if (m >= M) continue;
 #pragma unroll
-        for (int j = 0; j < C::TN; ++j) {
+        for (int j = 0; j < C::TN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * (BN / WN) + j * 32 + g * 8 + lh * 4;
-                if (n >= N) continue;
-                float v[4];
+                f32x4 v;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e];
-                if (bias) {
-                    const bf16x4 bv = *(const bf16x4 *)(bias + n);
+                *(f32x4 OB_LDS *)(slab + lx * RSTR + (j * 32 + g * 8 + lh * 4) * 4) = v;
+            }
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += (float)bv[e];
-                }
+        for (int r = 0; r < 32 / RPI; ++r) {
+            const int row = r * RPI + lane / LPR;
+            const f32x4 lo = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32);
+            const f32x4 hi = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32 + 16);
+            const int m = m0 + wm * (BM / WM) + i * 32 + row;
+            if (m < M && n_out < N) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[e] = lo[e] + bv[e]; v[4 + e] = hi[e] + bv[4 + e]; }
                 if (R) {
-                    const bf16x4 rv = *(const bf16x4 *)(R + (size_t)m * ldr + n);
+                    const bf16x8 r8 = *(const bf16x8 *)(R + (size_t)m * ldr + n_out);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
+                    for (int e = 0; e < 8; ++e) v[e] += (float)r8[e];
                 }
-                bf16x4 o;
+                bf16x8 o;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
-                *(bf16x4 *)(Cm + (size_t)m * ldc + n) = o;
+                for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
+                *(bf16x8 *)(Cm + (size_t)m * ldc + n_out) = o;
             }
         }
     }
