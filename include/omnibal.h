@@ -139,7 +139,8 @@ size_t ob_block_saved_offset(const ob_block_desc *desc, int total_tokens, const 
  *   layout 1 ("NN"): A [M,K], B [K,N]        -- dgrad    da = dy W
  *   layout 2 ("TN"): A [K,M], B [K,N]        -- wgrad    dW = dy^T a   (K = tokens)
  * `R` may equal `C` (in-place accumulate).  N and the feature side of K must be multiples of 64.
- * ws: ob_gemm_workspace_bytes() bytes of scratch (operand re-layout for NN / TN). */
+ * All three layouts run natively (a K-major operand is transposed by the LDS read), so
+ * ob_gemm_workspace_bytes() is 0 and ws may be NULL; the arguments are kept for ABI stability. */
 size_t ob_gemm_workspace_bytes(int layout, int M, int N, int K);
 int ob_gemm_bf16(int layout, int M, int N, int K, const void *A, const void *B, void *C,
                  const void *bias, const void *R, void *ws, size_t ws_bytes, void *hip_stream);

@@ -37,7 +37,7 @@ struct ProfState {
 };
 ProfState g_prof;
 const char *const kClassNames[K_COUNT] = {
-    "gemm", "transpose", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "attn_delta", "norm_fwd",
+    "gemm", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "attn_delta", "norm_fwd",
     "norm_bwd", "rotary", "act_fwd", "act_bwd", "colsum", "reduce_partials"};
 }  // namespace
 

@@ -1,14 +1,19 @@
 // bf16 MFMA GEMM for gfx950 (steps a2, a5, a7, a9 and their dgrad / wgrad counterparts).
 //
-//   C[M,N] = A[M,K] * B[N,K]^T (+ bias[N]) (+ R[M,N])      bf16 in, fp32 accumulate, bf16 out
+//   C[M,N] = op(A) * op(B) (+ bias[N]) (+ R[M,N])      bf16 in, fp32 accumulate, bf16 out
+//   "NT" A[M,K] B[N,K] (forward)   "NN" A[M,K] B[K,N] (dgrad)   "TN" A[K,M] B[K,N] (wgrad, K = tokens)
 //
-// One workgroup owns a BM x BN tile of C and walks K in steps of 64.  Both operands are
-// K-contiguous, so a 16-byte global load is 8 consecutive k of one row; tiles are staged in LDS
-// as [row][64 k] with the 16-byte chunk index XOR-swizzled by the row so that the 32 rows a
-// wavefront reads for one MFMA operand fall into different banks.  The MFMA is 32x32x16 bf16:
-// lane l supplies row (l % 32), k = 8 (l / 32) .. +7 of each operand, i.e. one 16-byte LDS read.
-// The weight rows are fed as the MFMA's first operand so that a lane's four consecutive
-// accumulator registers are four consecutive columns n of one output row m (8-byte stores).
+// One workgroup (4 wavefronts, each a 128x128 block of 4x4 MFMA 32x32x16 tiles, 256 accumulator
+// registers) owns a 256x256 tile of C and walks K in steps of 64 over two LDS stages.  Tiles are
+// copied global -> LDS asynchronously by buffer loads that write LDS directly (no registers in
+// between); the hardware range check of the buffer descriptor turns every access past the end of
+// an operand (row tails of M / N, the ragged token tail of K) into zeros.  A K-contiguous operand
+// is staged as [row][64 k] and a fragment is one 16-byte LDS read; a K-major operand is staged as
+// it lies in memory, [k][rows], and the fragment comes out of two transposing LDS reads, so dgrad
+// and wgrad need no re-layout pass.  16-byte chunks are XOR-swizzled on the way in (the global
+// address of each lane's chunk is free to choose) so that LDS reads are bank-conflict free.
+// The weight-side rows are the MFMA's first operand, so a lane's accumulators are runs of four
+// consecutive output columns; the epilogue transposes them through LDS into full-row stores.
 #include <cmath>
 
 #include "ob_internal.h"
@@ -50,65 +55,133 @@ template <int BM, int BN, int WM, int WN>
 struct Cfg {
     static constexpr int NW = WM * WN, NT = NW * 64;
     static constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 MFMA tiles per wave
-    // a wave instruction of the LDS-direct load fills 1 KB = 8 rows of a tile
+    // a wave instruction of the LDS-direct load fills 1 KB of a tile; a tile is X rows x 64 k
     static constexpr int A_LD = BM / 8 / NW, B_LD = BN / 8 / NW;
     static constexpr int STAGE = (BM + BN) * ROW_BYTES;
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile / wave count mismatch");
 };
 
-// Per-thread addressing state.  LDS tiles are [row][8 chunks of 16 B]; the chunk stored at
-// physical position p of row r is logical chunk p ^ f(r), f(r) = (r ^ ((r >> 3) & 1)) & 7, which
-// keeps the 16-byte reads of 8 as well as of 16 consecutive rows on distinct banks.
-template <int BM, int BN, int WM, int WN>
-struct Ctx {
-    using C = Cfg<BM, BN, WM, WN>;
-    const unsigned char *a_base, *b_base;        // tile origin in A / B (wave-uniform)
-    uint32_t a_off[C::A_LD], b_off[C::B_LD];     // this lane's byte offset for each of its loads
-    int wave;
-    int xa[BK / 16], xb[BK / 16];                // this lane's LDS read offset for k-step t
+// One operand's tile in LDS, in one of two layouts.
+//
+// KMAJOR = false: the source is [X, K] with k contiguous.  LDS holds [x][8 chunks of 16 B]; the
+//   chunk at physical position p of row x is logical chunk p ^ f(x), f(x) = (x ^ ((x >> 3) & 1)) & 7,
+//   so the 16-byte reads of 16 consecutive rows hit distinct banks.  A fragment (row x, 8
+//   consecutive k) is one 16-byte read.
+// KMAJOR = true: the source is [K, X] with x contiguous.  LDS holds [k][X / 8 chunks of 16 B]
+//   (8 x-values per chunk); the chunk at physical position p of row k is logical chunk
+//   p ^ 4 (k & 3).  A fragment is two transposing 8-byte reads (ds_read_b64_tr_b16): inside a
+//   group of 16 lanes, lane 4 k' + c addresses the 4 x-values [4c, 4c+4) of row k' of a 4 x 16
+//   block, and lane p receives column p, i.e. 4 consecutive k of one x.
+template <int X, int NW, bool KMAJOR>
+struct Operand {
+    static constexpr int LD = X / 8 / NW;        // wave-level 1 KB loads per stage
+    static constexpr int ROWB = X * 2;           // LDS bytes per k-row (k-major layout)
+    const unsigned char *base;                   // advances every K step
+    uint32_t nrec, step;                         // bytes left from `base`; bytes per K step
+    uint32_t voff[LD];                           // this lane's byte offset for each of its loads
+    int rd[KMAJOR ? X / 32 : BK / 16];           // this lane's LDS read offsets (per tile i / per k-step t)
+
+    // ld = source leading dimension (elements); x0 = first tile row; extent = rows (k-major: K)
+    __device__ __forceinline__ void init(const __bf16 *src, int ld, int x0, long total_bytes, int wave,
+                                         int lane, int wave_x0, int tiles) {
+        if (!KMAJOR) {
+            base = (const unsigned char *)(src + (size_t)x0 * ld);
+            const long left = total_bytes - (long)x0 * ld * 2;
+            nrec = (uint32_t)(left > 0xFFFFFFFFl ? 0xFFFFFFFFl : left);
+            step = ROW_BYTES;
+#pragma unroll
+            for (int p = 0; p < LD; ++p) {
+                const int blk = wave * LD + p, row = blk * 8 + (lane >> 3);
+                const int ch = (lane & 7) ^ (((lane >> 3) ^ (blk & 1)) & 7);
+                voff[p] = ((uint32_t)row * (uint32_t)ld + ch * 8) * 2u;
+            }
+            const int lx = lane & 31, lh = lane >> 5;
+            const int f = (lx ^ ((lx >> 3) & 1)) & 7;
+#pragma unroll
+            for (int t = 0; t < BK / 16; ++t) rd[t] = (wave_x0 + lx) * ROW_BYTES + (((2 * t + lh) ^ f) * 16);
+        } else {
+            base = (const unsigned char *)(src + x0);
+            const long left = total_bytes - (long)x0 * 2;
+            nrec = (uint32_t)(left > 0xFFFFFFFFl ? 0xFFFFFFFFl : left);
+            step = (uint32_t)BK * (uint32_t)ld * 2u;
+            constexpr int KPB = 1024 / ROWB, CPR = ROWB / 16;   // k-rows per 1 KB load, chunks per row
+#pragma unroll
+            for (int p = 0; p < LD; ++p) {
+                const int blk = wave * LD + p, k = blk * KPB + lane / CPR;
+                const int ch = (lane % CPR) ^ (4 * (k & 3));
+                voff[p] = ((uint32_t)k * (uint32_t)ld + ch * 8) * 2u;
+            }
+            const int b = lane >> 4, q = lane & 15, kq = q >> 2, c = q & 3, hb = b >> 1, nb = 16 * (b & 1);
+#pragma unroll
+            for (int i = 0; i < X / 32; ++i) {
+                if (i >= tiles) { rd[i] = 0; continue; }
+                const int chunk = (wave_x0 + 32 * i + nb) / 8 + (c >> 1);
+                rd[i] = (8 * hb + kq) * ROWB + ((chunk ^ (4 * kq)) * 16) + (c & 1) * 8;
+            }
+        }
+    }
+    __device__ __forceinline__ void advance() {
+        base += step;
+        nrec = nrec > step ? nrec - step : 0u;
+    }
+    // asynchronous global -> LDS copy of this wave's share of the tile; loads past the end of the
+    // source (rows beyond M / N / K) deliver zeros
+    __device__ __forceinline__ void issue(unsigned char OB_LDS *__restrict__ dst, int wave) const {
+        // the descriptor must sit in scalar registers: pin its (uniform) parts explicitly
+        const uint64_t b = (uint64_t)base;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void *)(((uint64_t)hi << 32) | lo), 0, (int)__builtin_amdgcn_readfirstlane(nrec), 0x00020000);
+#pragma unroll
+        for (int p = 0; p < LD; ++p)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst + (wave * LD + p) * 1024, 16, voff[p], 0, 0, 0);
+    }
+    // fragment for MFMA tile i (32 x-values) at k-step t: lane l holds x = l % 32, k = 8 (l / 32) .. +7
+    __device__ __forceinline__ bf16x8 frag(const unsigned char OB_LDS *__restrict__ tile, int i, int t) const {
+        if (!KMAJOR) {
+            return *(const bf16x8 OB_LDS *)(tile + rd[t] + i * 32 * ROW_BYTES);
+        } else {
+#if defined(__HIP_DEVICE_COMPILE__)  // the gfx950-only builtin must not be seen by the host pass
+            typedef __attribute__((ext_vector_type(4))) short s16x4;
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 OB_LDS *)(tile + rd[i] + (16 * t) * ROWB));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (s16x4 OB_LDS *)(tile + rd[i] + (16 * t + 4) * ROWB));
+            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v);
+#else
+            return bf16x8{};
+#endif
+        }
+    }
 };
-
-// Asynchronous global -> LDS copy of one K-step's A and B tiles: lane l of a wave instruction
-// supplies the global address of the 16 bytes that land at LDS base + 16 l.
-template <int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void issue_loads(unsigned char OB_LDS *__restrict__ dst,
-                                            const Ctx<BM, BN, WM, WN> &c, int kbytes) {
-    using C = Cfg<BM, BN, WM, WN>;
-#pragma unroll
-    for (int p = 0; p < C::A_LD; ++p)
-        __builtin_amdgcn_global_load_lds(c.a_base + kbytes + c.a_off[p],
-                                         dst + (c.wave * C::A_LD + p) * 1024, 16, 0, 0);
-#pragma unroll
-    for (int p = 0; p < C::B_LD; ++p)
-        __builtin_amdgcn_global_load_lds(c.b_base + kbytes + c.b_off[p],
-                                         dst + BM * ROW_BYTES + (c.wave * C::B_LD + p) * 1024, 16, 0, 0);
-}
-
-template <int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void load_frags(const unsigned char OB_LDS *__restrict__ src,
-                                           const Ctx<BM, BN, WM, WN> &c, int t,
-                                           bf16x8 (&af)[Cfg<BM, BN, WM, WN>::TM],
-                                           bf16x8 (&bfr)[Cfg<BM, BN, WM, WN>::TN]) {
-    using C = Cfg<BM, BN, WM, WN>;
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i) af[i] = *(const bf16x8 OB_LDS *)(src + c.xa[t] + i * 32 * ROW_BYTES);
-#pragma unroll
-    for (int j = 0; j < C::TN; ++j) bfr[j] = *(const bf16x8 OB_LDS *)(src + c.xb[t] + j * 32 * ROW_BYTES);
-}
 
 // Multiply one LDS stage (4 k-steps of 16).  The fragments of k-step t+1 are read while the
 // MFMAs of k-step t run; the scheduling groups pin "one LDS read, one MFMA" pairs at the front of
-// each k-step so every read has at least half a k-step of MFMA work to hide behind.
-template <int BM, int BN, int WM, int WN>
+// each k-step so every read has MFMA work to hide behind.
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __device__ __forceinline__ void compute_stage(const unsigned char OB_LDS *__restrict__ src,
-                                              const Ctx<BM, BN, WM, WN> &c,
+                                              const Operand<BM, WM * WN, AK> &opa,
+                                              const Operand<BN, WM * WN, BKM> &opb,
                                               f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
     using C = Cfg<BM, BN, WM, WN>;
+    const unsigned char OB_LDS *as = src;
+    const unsigned char OB_LDS *bs = src + BM * ROW_BYTES;
     bf16x8 af[2][C::TM], bfr[2][C::TN];
-    load_frags<BM, BN, WM, WN>(src, c, 0, af[0], bfr[0]);
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) af[0][i] = opa.frag(as, i, 0);
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) bfr[0][j] = opb.frag(bs, j, 0);
 #pragma unroll
     for (int t = 0; t < BK / 16; ++t) {
-        if (t + 1 < BK / 16) load_frags<BM, BN, WM, WN>(src, c, t + 1, af[(t + 1) & 1], bfr[(t + 1) & 1]);
+        if (t + 1 < BK / 16) {
+#pragma unroll
+            for (int i = 0; i < C::TM; ++i) af[(t + 1) & 1][i] = opa.frag(as, i, t + 1);
+#pragma unroll
+            for (int j = 0; j < C::TN; ++j) bfr[(t + 1) & 1][j] = opb.frag(bs, j, t + 1);
+        }
 #pragma unroll
         for (int i = 0; i < C::TM; ++i)
 #pragma unroll
@@ -116,20 +189,23 @@ __device__ __forceinline__ void compute_stage(const unsigned char OB_LDS *__rest
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[t & 1][j], af[t & 1][i],
                                                                    acc[i][j], 0, 0, 0);
         if (t + 1 < BK / 16) {
+            constexpr int READS = C::TM * (AK ? 2 : 1) + C::TN * (BKM ? 2 : 1);
+            constexpr int PER = READS > C::TM * C::TN ? 2 : 1;   // LDS reads per MFMA in the front part
 #pragma unroll
-            for (int r = 0; r < C::TM + C::TN; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // one LDS read
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+            for (int r = 0; r < READS / PER; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);  // LDS reads
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
             }
         }
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// C[M,N] = A[M,K] B[N,K]^T (+bias) (+R).  Two LDS stages; the copy of K-step kt+1 is in flight
-// while K-step kt is multiplied; one barrier per K-step.
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
+// C[M,N] = op(A) op(B) (+bias) (+R): A is [M,K] (AK = false) or [K,M] (AK = true); B is [N,K]
+// (BKM = false) or [K,N] (BKM = true).  Two LDS stages; the copy of K-step kt+1 is in flight while
+// K-step kt is multiplied; one barrier per K-step.
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     int M, int N, int K, const __bf16 *__restrict__ A, int lda, const __bf16 *__restrict__ B,
     int ldb, __bf16 *__restrict__ Cm, int ldc, const __bf16 *__restrict__ bias,
     const __bf16 *R, int ldr, int tiles_m, int tiles_n) {
@@ -139,35 +215,19 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
 
     int tile_m, tile_n;
     tile_coords(tiles_m, tiles_n, tile_m, tile_n);
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    // the divisions above run on the vector ALU; pin the (uniform) results to scalar registers so
+    // the buffer descriptors built from them are scalar too
+    const int m0 = __builtin_amdgcn_readfirstlane(tile_m) * BM;
+    const int n0 = __builtin_amdgcn_readfirstlane(tile_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
-    Ctx<BM, BN, WM, WN> c;
-    c.wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = c.wave / WN, wn = c.wave % WN;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
     const int lx = lane & 31, lh = lane >> 5;
 
-    // rows past the matrix edge are clamped onto its last row: they are multiplied as duplicate
-    // data and never stored
-    c.a_base = (const unsigned char *)(A + (size_t)m0 * lda);
-    c.b_base = (const unsigned char *)(B + (size_t)n0 * ldb);
-#pragma unroll
-    for (int p = 0; p < C::A_LD; ++p) {
-        const int blk = c.wave * C::A_LD + p, row = blk * 8 + (lane >> 3);
-        const int ch = (lane & 7) ^ (((lane >> 3) ^ (blk & 1)) & 7);
-        c.a_off[p] = ((uint32_t)min(row, M - 1 - m0) * (uint32_t)lda + ch * 8) * 2u;
-    }
-#pragma unroll
-    for (int p = 0; p < C::B_LD; ++p) {
-        const int blk = c.wave * C::B_LD + p, row = blk * 8 + (lane >> 3);
-        const int ch = (lane & 7) ^ (((lane >> 3) ^ (blk & 1)) & 7);
-        c.b_off[p] = ((uint32_t)min(row, N - 1 - n0) * (uint32_t)ldb + ch * 8) * 2u;
-    }
-    const int f = (lx ^ ((lx >> 3) & 1)) & 7;
-#pragma unroll
-    for (int t = 0; t < BK / 16; ++t) {
-        c.xa[t] = (wm * (BM / WM) + lx) * ROW_BYTES + (((2 * t + lh) ^ f) * 16);
-        c.xb[t] = BM * ROW_BYTES + (wn * (BN / WN) + lx) * ROW_BYTES + (((2 * t + lh) ^ f) * 16);
-    }
+    Operand<BM, C::NW, AK> opa;
+    Operand<BN, C::NW, BKM> opb;
+    opa.init(A, lda, m0, (AK ? (long)K : (long)M) * lda * 2, wave, lane, wm * (BM / WM), C::TM);
+    opb.init(B, ldb, n0, (BKM ? (long)K : (long)N) * ldb * 2, wave, lane, wn * (BN / WN), C::TN);
 
     f32x16 acc[C::TM][C::TN];
 #pragma unroll
@@ -179,25 +239,33 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
 
     unsigned char OB_LDS *s0 = (unsigned char OB_LDS *)st0;
     unsigned char OB_LDS *s1 = (unsigned char OB_LDS *)st1;
-    const int nk = K / BK;
+    const int nk = (K + BK - 1) / BK;
     constexpr int WAIT_VM0 = 0x0F70;  // s_waitcnt vmcnt(0) only
-    issue_loads<BM, BN, WM, WN>(s0, c, 0);
+#define OB_ISSUE(dst)                         \
+    do {                                      \
+        opa.issue((dst), wave);               \
+        opb.issue((dst) + BM * ROW_BYTES, wave); \
+        opa.advance();                        \
+        opb.advance();                        \
+    } while (0)
+    OB_ISSUE(s0);
     int kt = 0;
     for (; kt + 2 <= nk; kt += 2) {
         __builtin_amdgcn_s_waitcnt(WAIT_VM0);
         __syncthreads();
-        issue_loads<BM, BN, WM, WN>(s1, c, (kt + 1) * ROW_BYTES);
-        compute_stage<BM, BN, WM, WN>(s0, c, acc);
+        OB_ISSUE(s1);
+        compute_stage<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, acc);
         __builtin_amdgcn_s_waitcnt(WAIT_VM0);
         __syncthreads();
-        if (kt + 2 < nk) issue_loads<BM, BN, WM, WN>(s0, c, (kt + 2) * ROW_BYTES);
-        compute_stage<BM, BN, WM, WN>(s1, c, acc);
+        if (kt + 2 < nk) OB_ISSUE(s0);
+        compute_stage<BM, BN, WM, WN, AK, BKM>(s1, opa, opb, acc);
     }
     if (kt < nk) {
         __builtin_amdgcn_s_waitcnt(WAIT_VM0);
         __syncthreads();
-        compute_stage<BM, BN, WM, WN>(s0, c, acc);
+        compute_stage<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, acc);
     }
+#undef OB_ISSUE
 
     // Epilogue.  A lane holds, per MFMA tile, output row m = lx and columns n = 8 g + 4 lh + (0..3):
     // stored directly, every lane of a store would touch a different cache line.  Instead each
@@ -210,7 +278,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
     constexpr int LPR = CW / 8;            // lanes per row on the way out (8 columns each)
     constexpr int RPI = 64 / LPR;          // rows per read instruction
     static_assert(32 * RSTR <= C::STAGE / (C::NW / 2), "slab does not fit the wave's LDS share");
-    unsigned char OB_LDS *slab = (c.wave < C::NW / 2 ? s0 : s1) + (c.wave % (C::NW / 2)) * (C::STAGE / (C::NW / 2));
+    unsigned char OB_LDS *slab = (wave < C::NW / 2 ? s0 : s1) + (wave % (C::NW / 2)) * (C::STAGE / (C::NW / 2));
     const int n_out = n0 + wn * CW + (lane % LPR) * 8;
     float bv[8];
 #pragma unroll
@@ -255,40 +323,32 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_nt_kernel(
     }
 }
 
-// out[c][r] = in[r][c]; rows r in [rows, rows_pad) are written as zero.  64x64 tiles via LDS.
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const unsigned short *__restrict__ in,
-                                                            int rows, int cols, int ld_in,
-                                                            unsigned short *__restrict__ out,
-                                                            int rows_pad) {
-    __shared__ unsigned short tile[64][66];
-    const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int i = ty; i < 64; i += 4) {
-        const int r = r0 + i, c = c0 + tx;
-        tile[i][tx] = (r < rows && c < cols) ? in[(size_t)r * ld_in + c] : (unsigned short)0;
-    }
-    __syncthreads();
-    for (int i = ty; i < 64; i += 4) {
-        const int c = c0 + i, r = r0 + tx;
-        if (c < cols && r < rows_pad) out[(size_t)c * rows_pad + r] = tile[tx][i];
-    }
-}
+// Explicit instantiations: without them hipcc's host pass references but does not emit the launch
+// stubs of the variants whose only use sits two templates deep.
+#define OB_GEMM_INSTANCE(BM, BN, AK, BKM)                                                          \
+    template __global__ void gemm_kernel<BM, BN, 2, 2, AK, BKM>(                                   \
+        int, int, int, const __bf16 *, int, const __bf16 *, int, __bf16 *, int, const __bf16 *,    \
+        const __bf16 *, int, int, int);
+OB_GEMM_INSTANCE(256, 256, false, false)
+OB_GEMM_INSTANCE(128, 128, false, false)
+OB_GEMM_INSTANCE(256, 256, false, true)
+OB_GEMM_INSTANCE(128, 128, false, true)
+OB_GEMM_INSTANCE(256, 256, true, true)
+OB_GEMM_INSTANCE(128, 128, true, true)
+#undef OB_GEMM_INSTANCE
 
-template <int BM, int BN, int WM, int WN>
-void launch_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
-               const void *bias, const void *R, int ldr, hipStream_t s) {
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+void launch_tile(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
+                 const void *bias, const void *R, int ldr, hipStream_t s) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    auto kern = gemm_nt_kernel<BM, BN, WM, WN>;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(WM * WN * 64), 0, s, M, N, K,
-                       (const __bf16 *)A, lda, (const __bf16 *)B, ldb, (__bf16 *)C, ldc,
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, AK, BKM>), dim3(tiles_m * tiles_n), dim3(WM * WN * 64),
+                       0, s, M, N, K, (const __bf16 *)A, lda, (const __bf16 *)B, ldb, (__bf16 *)C, ldc,
                        (const __bf16 *)bias, (const __bf16 *)R, ldr, tiles_m, tiles_n);
 }
 
-}  // namespace
-
-void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
-                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s, int k_algo) {
-    ProfScope prof(K_GEMM, s, 2.0 * M * N * (k_algo > 0 ? k_algo : K));
+template <bool AK, bool BKM>
+void launch_layout(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
+                   const void *bias, const void *R, int ldr, hipStream_t s) {
     // 256x256 tiles run one workgroup per CU, 128x128 tiles two; take the shape whose last round
     // of tiles leaves fewer CUs idle (the small tile pays ~15 % in operand re-reads)
     const double big = (double)((M + 255) / 256) * ((N + 255) / 256);
@@ -296,47 +356,32 @@ void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, 
     const double eff_big = big / (ceil(big / 256.0) * 256.0);
     const double eff_small = 0.85 * small / (ceil(small / 512.0) * 512.0);
     if (eff_big >= eff_small)
-        launch_nt<256, 256, 2, 2>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
+        launch_tile<256, 256, 2, 2, AK, BKM>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
     else
-        launch_nt<128, 128, 2, 2>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
+        launch_tile<128, 128, 2, 2, AK, BKM>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
 }
 
-void launch_transpose_pad(const void *in, int rows, int cols, int ld_in, void *out, int rows_pad,
-                          hipStream_t s) {
-    ProfScope prof(K_TRANSPOSE, s, 2.0 * rows * cols + 2.0 * rows_pad * cols);
-    dim3 grid((rows_pad + 63) / 64, (cols + 63) / 64);
-    hipLaunchKernelGGL(transpose_pad_kernel, grid, dim3(256), 0, s, (const unsigned short *)in,
-                       rows, cols, ld_in, (unsigned short *)out, rows_pad);
+}  // namespace
+
+void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
+                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s, int k_algo) {
+    ProfScope prof(K_GEMM, s, 2.0 * M * N * (k_algo > 0 ? k_algo : K));
+    launch_layout<false, false>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
 }
 
-size_t gemm_workspace_bytes(int layout, int M, int N, int K) {
-    if (layout == 1) return align_up((size_t)N * K * 2, 256);
-    if (layout == 2) {
-        const size_t kp = align_up((size_t)K, 64);
-        return align_up((size_t)M * kp * 2, 256) + align_up((size_t)N * kp * 2, 256);
-    }
-    return 0;
-}
+size_t gemm_workspace_bytes(int, int, int, int) { return 0; }
 
-// layout 0: A[M,K] B[N,K]; 1: A[M,K] B[K,N]; 2: A[K,M] B[K,N].  NN / TN operands are re-laid
-// out K-contiguous in `ws` first (zero-padded along K to a multiple of 64 for TN).
+// layout 0 ("NT"): A[M,K] B[N,K]; 1 ("NN"): A[M,K] B[K,N]; 2 ("TN"): A[K,M] B[K,N].  All three
+// run natively: a K-major operand is staged as it lies in memory and transposed by the LDS read.
 int gemm_any(int layout, int M, int N, int K, const void *A, const void *B, void *C,
-             const void *bias, const void *R, void *ws, size_t ws_bytes, hipStream_t s) {
-    if (ws_bytes < gemm_workspace_bytes(layout, M, N, K))
-        return fail(OB_EWORKSPACE, "gemm: workspace too small");
-    if (layout == 0) {
-        launch_gemm_nt(M, N, K, A, K, B, K, C, N, bias, R, N, s);
-    } else if (layout == 1) {
-        launch_transpose_pad(B, K, N, N, ws, K, s);  // B[K,N] -> Bt[N,K]
-        launch_gemm_nt(M, N, K, A, K, ws, K, C, N, bias, R, N, s);
-    } else {
-        const int kp = (int)align_up((size_t)K, 64);
-        unsigned char *at = (unsigned char *)ws;
-        unsigned char *bt = at + align_up((size_t)M * kp * 2, 256);
-        launch_transpose_pad(A, K, M, M, at, kp, s);  // A[K,M] -> At[M,kp]
-        launch_transpose_pad(B, K, N, N, bt, kp, s);  // B[K,N] -> Bt[N,kp]
-        launch_gemm_nt(M, N, kp, at, kp, bt, kp, C, N, bias, R, N, s, K);
-    }
+             const void *bias, const void *R, void *, size_t, hipStream_t s) {
+    ProfScope prof(K_GEMM, s, 2.0 * M * N * K);
+    if (layout == 0)
+        launch_layout<false, false>(M, N, K, A, K, B, K, C, N, bias, R, N, s);
+    else if (layout == 1)
+        launch_layout<false, true>(M, N, K, A, K, B, N, C, N, bias, R, N, s);
+    else
+        launch_layout<true, true>(M, N, K, A, M, B, N, C, N, bias, R, N, s);
     return check_launch("gemm");
 }
 

@@ -16,7 +16,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- opt-in per-kernel-class timing (ob_prof_begin / ob_prof_end) --------------------------
 enum KClass {
-    K_GEMM = 0, K_TRANSPOSE, K_ATTN_FWD, K_ATTN_BWD_DQ, K_ATTN_BWD_DKV, K_ATTN_DELTA, K_NORM_FWD,
+    K_GEMM = 0, K_ATTN_FWD, K_ATTN_BWD_DQ, K_ATTN_BWD_DKV, K_ATTN_DELTA, K_NORM_FWD,
     K_NORM_BWD, K_ROTARY, K_ACT_FWD, K_ACT_BWD, K_COLSUM, K_REDUCE, K_COUNT
 };
 // Brackets one kernel launch with a pair of events on its stream while profiling is on;
@@ -34,9 +34,6 @@ struct ProfScope {
 void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
                     int ldc, const void *bias, const void *R, int ldr, hipStream_t s,
                     int k_algo = 0);
-// out[c, r] = in[r, c] for r < rows, 0 for rows <= r < rows_pad; in ld = ld_in, out ld = rows_pad
-void launch_transpose_pad(const void *in, int rows, int cols, int ld_in, void *out, int rows_pad,
-                          hipStream_t s);
 size_t gemm_workspace_bytes(int layout, int M, int N, int K);
 int gemm_any(int layout, int M, int N, int K, const void *A, const void *B, void *C,
              const void *bias, const void *R, void *ws, size_t ws_bytes, hipStream_t s);

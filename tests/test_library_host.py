@@ -160,7 +160,6 @@ def test_gemm_argument_validation():
     assert call(0, 64, 100, 64) == ob.OB_EUNSUPPORTED
     assert call(0, 64, 64, 100) == ob.OB_EUNSUPPORTED
     assert call(2, 100, 64, 77) == ob.OB_EUNSUPPORTED
-    assert call(1, 64, 64, 64, wsb=16) == ob.OB_EWORKSPACE
-    assert ob.ob_gemm_workspace_bytes(0, 64, 64, 64) == 0
-    assert ob.ob_gemm_workspace_bytes(2, 128, 64, 100) >= (128 + 64) * 128 * 2
+    for layout in (0, 1, 2):                      # all three layouts run without scratch
+        assert ob.ob_gemm_workspace_bytes(layout, 128, 64, 128) == 0
     assert ob.lib.ob_debug_materialize_mask(C.byref(_seg([0, 4]).c), 1, None, None) == ob.OB_EINVAL
