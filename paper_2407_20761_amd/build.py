@@ -33,6 +33,8 @@ def _compile(src: str) -> str:
 
 
 def build_library(verbose: bool = True) -> str:
+    if os.path.exists(LIB):
+        os.remove(LIB)      # a failed build must not leave a stale library behind
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs]
