@@ -158,52 +158,87 @@ struct Operand {
     }
 };
 
-// Multiply one LDS stage (4 k-steps of 16).  The fragments of k-step t+1 are read while the
-// MFMAs of k-step t run; the scheduling groups pin "one LDS read, one MFMA" pairs at the front of
-// each k-step so every read has MFMA work to hide behind.
-template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
-__device__ __forceinline__ void compute_stage(const unsigned char OB_LDS *__restrict__ src,
-                                              const Operand<BM, WM * WN, AK> &opa,
-                                              const Operand<BN, WM * WN, BKM> &opb,
-                                              f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
+// MFMA work of one k-step (16 k) on fragments already in registers.
+template <int BM, int BN, int WM, int WN>
+__device__ __forceinline__ void mfma_step(const bf16x8 (&af)[Cfg<BM, BN, WM, WN>::TM],
+                                          const bf16x8 (&bfr)[Cfg<BM, BN, WM, WN>::TN],
+                                          f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
     using C = Cfg<BM, BN, WM, WN>;
-    const unsigned char OB_LDS *as = src;
-    const unsigned char OB_LDS *bs = src + BM * ROW_BYTES;
-    bf16x8 af[2][C::TM], bfr[2][C::TN];
 #pragma unroll
-    for (int i = 0; i < C::TM; ++i) af[0][i] = opa.frag(as, i, 0);
+    for (int i = 0; i < C::TM; ++i)
 #pragma unroll
-    for (int j = 0; j < C::TN; ++j) bfr[0][j] = opb.frag(bs, j, 0);
+        for (int j = 0; j < C::TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+}
+
+// scheduling hint for "fragment reads of the next k-step + MFMAs of this one": pin "LDS read(s),
+// one MFMA" pairs at the front so every read has MFMA work to hide behind
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__device__ __forceinline__ void pin_reads_into_mfmas() {
+    using C = Cfg<BM, BN, WM, WN>;
+    constexpr int READS = C::TM * (AK ? 2 : 1) + C::TN * (BKM ? 2 : 1);
+    constexpr int PER = READS > C::TM * C::TN ? 2 : 1;
 #pragma unroll
-    for (int t = 0; t < BK / 16; ++t) {
-        if (t + 1 < BK / 16) {
+    for (int r = 0; r < READS / PER; ++r) {
+        __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);  // LDS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
+    }
+}
+
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__device__ __forceinline__ void read_frags(const unsigned char OB_LDS *__restrict__ src,
+                                           const Operand<BM, WM * WN, AK> &opa,
+                                           const Operand<BN, WM * WN, BKM> &opb, int t,
+                                           bf16x8 (&af)[Cfg<BM, BN, WM, WN>::TM],
+                                           bf16x8 (&bfr)[Cfg<BM, BN, WM, WN>::TN]) {
+    using C = Cfg<BM, BN, WM, WN>;
 #pragma unroll
-            for (int i = 0; i < C::TM; ++i) af[(t + 1) & 1][i] = opa.frag(as, i, t + 1);
+    for (int i = 0; i < C::TM; ++i) af[i] = opa.frag(src, i, t);
 #pragma unroll
-            for (int j = 0; j < C::TN; ++j) bfr[(t + 1) & 1][j] = opb.frag(bs, j, t + 1);
-        }
+    for (int j = 0; j < C::TN; ++j) bfr[j] = opb.frag(src + BM * ROW_BYTES, j, t);
+}
+
+// k-steps 0 .. 2 of the stage in `cur`: the fragments of k-step 0 are already in af[0] / bfr[0];
+// on return the fragments of k-step 3 are in af[1] / bfr[1] and `cur` is not read again.
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__device__ __forceinline__ void stage_front(const unsigned char OB_LDS *__restrict__ cur,
+                                            const Operand<BM, WM * WN, AK> &opa,
+                                            const Operand<BN, WM * WN, BKM> &opb,
+                                            bf16x8 (&af)[2][Cfg<BM, BN, WM, WN>::TM],
+                                            bf16x8 (&bfr)[2][Cfg<BM, BN, WM, WN>::TN],
+                                            f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
 #pragma unroll
-        for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-            for (int j = 0; j < C::TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[t & 1][j], af[t & 1][i],
-                                                                   acc[i][j], 0, 0, 0);
-        if (t + 1 < BK / 16) {
-            constexpr int READS = C::TM * (AK ? 2 : 1) + C::TN * (BKM ? 2 : 1);
-            constexpr int PER = READS > C::TM * C::TN ? 2 : 1;   // LDS reads per MFMA in the front part
-#pragma unroll
-            for (int r = 0; r < READS / PER; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);  // LDS reads
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
-            }
-        }
+    for (int t = 0; t < 3; ++t) {
+        read_frags<BM, BN, WM, WN, AK, BKM>(cur, opa, opb, t + 1, af[(t + 1) & 1], bfr[(t + 1) & 1]);
+        mfma_step<BM, BN, WM, WN>(af[t & 1], bfr[t & 1], acc);
+        pin_reads_into_mfmas<BM, BN, WM, WN, AK, BKM>();
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
+// k-step 3 of the current stage (fragments in af[1] / bfr[1]) overlapped with the fragment reads
+// of k-step 0 of the stage in `nxt` (into af[0] / bfr[0]).
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM, bool NEXT>
+__device__ __forceinline__ void stage_back(const unsigned char OB_LDS *__restrict__ nxt,
+                                           const Operand<BM, WM * WN, AK> &opa,
+                                           const Operand<BN, WM * WN, BKM> &opb,
+                                           bf16x8 (&af)[2][Cfg<BM, BN, WM, WN>::TM],
+                                           bf16x8 (&bfr)[2][Cfg<BM, BN, WM, WN>::TN],
+                                           f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
+    if (NEXT) read_frags<BM, BN, WM, WN, AK, BKM>(nxt, opa, opb, 0, af[0], bfr[0]);
+    mfma_step<BM, BN, WM, WN>(af[1], bfr[1], acc);
+    if (NEXT) pin_reads_into_mfmas<BM, BN, WM, WN, AK, BKM>();
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // C[M,N] = op(A) op(B) (+bias) (+R): A is [M,K] (AK = false) or [K,M] (AK = true); B is [N,K]
-// (BKM = false) or [K,N] (BKM = true).  Two LDS stages; the copy of K-step kt+1 is in flight while
-// K-step kt is multiplied; one barrier per K-step.
+// (BKM = false) or [K,N] (BKM = true).
+//
+// Two LDS stages.  The barrier of a K step sits between its third and fourth k-step: by then the
+// step's last LDS reads have been issued (their data is needed only by the MFMAs after the
+// barrier), so behind the barrier the buffer can be refilled with K step s+2, and the first
+// fragments of step s+1 (landed since the previous barrier) are read while the fourth k-step's
+// MFMAs run.  No LDS latency and no barrier skew is exposed between K steps.
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     int M, int N, int K, const __bf16 *__restrict__ A, int lda, const __bf16 *__restrict__ B,
@@ -241,31 +276,45 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     unsigned char OB_LDS *s1 = (unsigned char OB_LDS *)st1;
     const int nk = (K + BK - 1) / BK;
     constexpr int WAIT_VM0 = 0x0F70;  // s_waitcnt vmcnt(0) only
-#define OB_ISSUE(dst)                         \
-    do {                                      \
-        opa.issue((dst), wave);               \
+#define OB_ISSUE(dst)                            \
+    do {                                         \
+        opa.issue((dst), wave);                  \
         opb.issue((dst) + BM * ROW_BYTES, wave); \
-        opa.advance();                        \
-        opb.advance();                        \
+        opa.advance();                           \
+        opb.advance();                           \
     } while (0)
+#define OB_SYNC()                                 \
+    do {                                          \
+        __builtin_amdgcn_s_waitcnt(0);            \
+        __syncthreads();                          \
+    } while (0)
+    bf16x8 af[2][C::TM], bfr[2][C::TN];
     OB_ISSUE(s0);
+    OB_SYNC();
+    if (nk > 1) OB_ISSUE(s1);
+    read_frags<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, 0, af[0], bfr[0]);
     int kt = 0;
-    for (; kt + 2 <= nk; kt += 2) {
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-        __syncthreads();
-        OB_ISSUE(s1);
-        compute_stage<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, acc);
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-        __syncthreads();
-        if (kt + 2 < nk) OB_ISSUE(s0);
-        compute_stage<BM, BN, WM, WN, AK, BKM>(s1, opa, opb, acc);
+    for (; kt + 2 < nk; kt += 2) {       // two K steps per trip: stage 0 then stage 1, both with successors
+        stage_front<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, af, bfr, acc);
+        OB_SYNC();                       // stage 1 landed everywhere; nobody reads stage 0 any more
+        OB_ISSUE(s0);                    // K step kt + 2
+        stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, opa, opb, af, bfr, acc);
+        stage_front<BM, BN, WM, WN, AK, BKM>(s1, opa, opb, af, bfr, acc);
+        OB_SYNC();
+        if (kt + 3 < nk) OB_ISSUE(s1);   // K step kt + 3
+        stage_back<BM, BN, WM, WN, AK, BKM, true>(s0, opa, opb, af, bfr, acc);
     }
-    if (kt < nk) {
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-        __syncthreads();
-        compute_stage<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, acc);
+    // here kt is even, stage 0 holds K step kt (its first fragments are in registers) and, when
+    // kt + 1 < nk, stage 1 holds or is receiving K step kt + 1
+    stage_front<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, af, bfr, acc);
+    if (kt + 1 < nk) {
+        OB_SYNC();
+        stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, opa, opb, af, bfr, acc);
+        stage_front<BM, BN, WM, WN, AK, BKM>(s1, opa, opb, af, bfr, acc);
     }
+    stage_back<BM, BN, WM, WN, AK, BKM, false>(s0, opa, opb, af, bfr, acc);
 #undef OB_ISSUE
+#undef OB_SYNC
 
     // Epilogue.  A lane holds, per MFMA tile, output row m = lx and columns n = 8 g + 4 lh + (0..3):
     // stored directly, every lane of a store would touch a different cache line.  Instead each
