@@ -102,13 +102,13 @@ int ob_prof_end(double *ms_per_class, int64_t *launches_per_class, double *work_
  * q, o, d_o, dq: rows of nq*d elements with row strides ldq / ldo (in elements); k, v, dk, dv:
  * rows of nkv*d elements with row stride ldkv -- so q,k,v may be column slices of one
  * [T, (nq+2nkv) d] buffer.  Cross-segment score tiles are never computed.
- * The backward needs ob_varlen_attn_bwd_workspace_bytes() bytes of scratch (holds
- * Delta_i = sum_d dO_i O_i, [nq, T] fp32).  dk/dv are summed over the nq/nkv query heads of a
- * group inside one workgroup (no atomics: results are bitwise reproducible). */
+ * The backward needs ob_varlen_attn_bwd_workspace_bytes() bytes of scratch: Delta_i = sum_d dO_i O_i
+ * ([nq, T] fp32) and, when nq > nkv, one fp32 dK and dV partial per query head of a group, which
+ * a second kernel sums in head order (no atomics: results are bitwise reproducible). */
 int ob_varlen_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
                        int ldq, int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d,
                        float scale, int mask, int dtype, void *hip_stream);
-size_t ob_varlen_attn_bwd_workspace_bytes(int total_tokens, int nq);
+size_t ob_varlen_attn_bwd_workspace_bytes(int total_tokens, int nq, int nkv, int d);
 int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const void *o,
                        const float *lse, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
                        const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,

@@ -74,7 +74,7 @@ _SIGNATURES = {
     "ob_prof_begin": (_I, [_I]),
     "ob_prof_end": (_I, [C.POINTER(C.c_double), _i64p, C.POINTER(C.c_double), _I]),
     "ob_varlen_attn_fwd": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _SEG, _I, _I, _I, _F, _I, _I, _P]),
-    "ob_varlen_attn_bwd_workspace_bytes": (_Z, [_I, _I]),
+    "ob_varlen_attn_bwd_workspace_bytes": (_Z, [_I, _I, _I, _I]),
     "ob_varlen_attn_bwd": (_I, [_P] * 9 + [_I, _I, _I, _SEG, _I, _I, _I, _F, _I, _I, _P, _Z, _P]),
     "ob_block_saved_bytes": (_Z, [_DESC, _I]),
     "ob_block_workspace_bytes": (_Z, [_DESC, _I]),
@@ -170,8 +170,8 @@ def ob_varlen_attn_fwd(q, k, v, o, lse, ldq, ldkv, ldo, seg: Segments, nq, nkv, 
                                   C.byref(seg.c), nq, nkv, d, scale, mask, dtype, _stream(stream)))
 
 
-def ob_varlen_attn_bwd_workspace_bytes(total_tokens, nq) -> int:
-    return lib.ob_varlen_attn_bwd_workspace_bytes(total_tokens, nq)
+def ob_varlen_attn_bwd_workspace_bytes(total_tokens, nq, nkv, d) -> int:
+    return lib.ob_varlen_attn_bwd_workspace_bytes(total_tokens, nq, nkv, d)
 
 
 def ob_varlen_attn_bwd(d_o, q, k, v, o, lse, dq, dk, dv, ldq, ldkv, ldo, seg: Segments, nq, nkv,

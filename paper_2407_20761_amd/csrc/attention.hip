@@ -123,20 +123,42 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
     return o;
 }
 
-// which segment-aligned tile (of `tile_rows` rows) is blockIdx.x
+// Which segment-aligned tile (of `tile_rows` rows) is blockIdx.x: tiles are numbered segment by
+// segment.  Thread j looks at segment j (256 segments per round), an inclusive scan over the
+// workgroup gives each segment's first tile number, and the thread whose range holds blockIdx.x
+// publishes the answer -- one global-memory round trip instead of a serial walk over cu.
 struct TileInfo { int seg_start, seg_end, row0; };
 __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, int n_seg, int tile_rows,
-                                              int *sh) {
-    if (threadIdx.x == 0) {
-        int acc = 0, j = 0, a = 0, b = 0, loc = 0;
-        for (; j < n_seg; ++j) {
+                                              int *sh /* >= 8 ints */) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid == 0) sh[2] = -1;
+    int base = 0;  // tiles in the segments of earlier rounds
+    for (int j0 = 0; j0 < n_seg; j0 += 256) {
+        const int j = j0 + tid;
+        int a = 0, b = 0, nt = 0;
+        if (j < n_seg) {
             a = cu[j];
             b = cu[j + 1];
-            const int nt = (b - a + tile_rows - 1) / tile_rows;
-            if ((int)blockIdx.x < acc + nt) { loc = blockIdx.x - acc; break; }
-            acc += nt;
+            nt = (b - a + tile_rows - 1) / tile_rows;
         }
-        sh[0] = a; sh[1] = b; sh[2] = (j < n_seg) ? a + loc * tile_rows : -1;
+        int incl = nt;  // inclusive scan inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o);
+            if (lane >= o) incl += up;
+        }
+        __syncthreads();  // sh[4..7] free (previous round consumed)
+        if (lane == 63) sh[4 + wave] = incl;
+        __syncthreads();
+        int before = base;
+        for (int w = 0; w < wave; ++w) before += sh[4 + w];
+        const int first = before + incl - nt;  // number of this segment's first tile
+        if (nt > 0 && (int)blockIdx.x >= first && (int)blockIdx.x < first + nt) {
+            sh[0] = a;
+            sh[1] = b;
+            sh[2] = a + ((int)blockIdx.x - first) * tile_rows;
+        }
+        base += sh[4] + sh[5] + sh[6] + sh[7];
     }
     __syncthreads();
     TileInfo t;
@@ -149,6 +171,16 @@ __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, in
 // ------------------------------------------------------------------------------------------------
 // forward:  S^T = K Q^T,  online softmax per lane,  O^T += V^T P^T
 // ------------------------------------------------------------------------------------------------
+// LDS reads are issued one batch ahead of the MFMAs that consume them (explicit double buffers and
+// scheduling groups): left alone, the compiler emits read / wait / MFMA triples and every MFMA
+// pays a full LDS round trip.
+#define OB_SCHED_READS_THEN_MFMA(n_reads, n_mfma)                 \
+    do {                                                          \
+        __builtin_amdgcn_sched_group_barrier(0x100, (n_reads), 0); \
+        __builtin_amdgcn_sched_group_barrier(0x008, (n_mfma), 0);  \
+        __builtin_amdgcn_sched_barrier(0);                         \
+    } while (0)
+
 template <int D, bool CAUSAL>
 __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict__ ks,
                                          const unsigned char OB_LDS *__restrict__ vs, const Tile<D> &tl,
@@ -156,14 +188,38 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
                                          float &l_run, int kv0, int seg_end, int q_row, bool need_mask,
                                          float sl2) {
     const int lh = (threadIdx.x & 63) >> 5;
+    constexpr int HB = 2;                 // K fragments (D-steps) per batch
+    constexpr int R = D == 128 ? 3 : 2;   // batches in flight (ring depth)
+    constexpr int PER = (D / 16) / HB;    // batches per 32-row tile
+    constexpr int NB = 2 * PER;
+    constexpr int DT = D / 32;
     f32x16 acc_s[2];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_s[mt][r] = 0.f;
+    bf16x8 fa[R][HB], fb[2][DT];
 #pragma unroll
-        for (int t = 0; t < D / 16; ++t)
-            acc_s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tl.frag_row(ks, mt, t), qf[t], acc_s[mt], 0, 0, 0);
+    for (int b = 0; b < R - 1; ++b)
+#pragma unroll
+        for (int i = 0; i < HB; ++i) fa[b][i] = tl.frag_row(ks, b / PER, (b % PER) * HB + i);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {  // batch b: row tile b / PER, D-steps (b % PER) HB ..
+        constexpr int AHEAD = R - 1;
+        if (b + AHEAD < NB) {
+#pragma unroll
+            for (int i = 0; i < HB; ++i)
+                fa[(b + AHEAD) % R][i] = tl.frag_row(ks, (b + AHEAD) / PER, ((b + AHEAD) % PER) * HB + i);
+        } else if (b + AHEAD == NB) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) fb[0][dt] = tl.frag_tr(vs, dt, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < HB; ++i)
+            acc_s[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[b % R][i], qf[(b % PER) * HB + i], acc_s[b / PER], 0, 0, 0);
+        if (b + AHEAD < NB) OB_SCHED_READS_THEN_MFMA(HB, HB);
+        else if (b + AHEAD == NB) OB_SCHED_READS_THEN_MFMA(2 * DT, HB);
+        else OB_SCHED_READS_THEN_MFMA(0, HB);
     }
     float mx = NEG_BIG;
     if (need_mask) {
@@ -211,10 +267,15 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
     l_run += psum;
 #pragma unroll
     for (int u = 0; u < ST / 16; ++u) {
+        if (u + 1 < ST / 16) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) fb[(u + 1) & 1][dt] = tl.frag_tr(vs, dt, u + 1);
+        }
         const bf16x8 pb = pack8(acc_s[u >> 1], 8 * (u & 1));
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-            acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tl.frag_tr(vs, dt, u), pb, acc_o[dt], 0, 0, 0);
+        for (int dt = 0; dt < DT; ++dt)
+            acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u & 1][dt], pb, acc_o[dt], 0, 0, 0);
+        if (u + 1 < ST / 16) OB_SCHED_READS_THEN_MFMA(2 * DT, DT); else OB_SCHED_READS_THEN_MFMA(0, DT);
     }
 }
 
@@ -227,7 +288,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     __shared__ __attribute__((aligned(1024))) unsigned char v_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char k_s1[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char v_s1[Tile<D>::BYTES];
-    __shared__ int sh[4];
+    __shared__ int sh[8];
     const TileInfo ti = find_tile(cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
     const int head = blockIdx.y, kvh = head / group;
@@ -307,16 +368,45 @@ __device__ __forceinline__ void dq_tile(const unsigned char OB_LDS *__restrict__
                                         f32x16 (&acc_dq)[D / 32], float lse2, float dlt, int kv0, int seg_end,
                                         int q_row, bool need_mask, float sl2) {
     const int lh = (threadIdx.x & 63) >> 5;
+    constexpr int HB = D == 128 ? 1 : 2;  // D-steps per batch (a batch reads HB fragments of K and HB of V)
+    constexpr int R = D == 128 ? 4 : 2;   // batches in flight (ring depth)
+    constexpr int PER = (D / 16) / HB;    // batches per 32-row tile
+    constexpr int NB = 2 * PER;
+    constexpr int DT = D / 32;
     f32x16 acc_s[2], acc_dp[2];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_s[mt][r] = acc_dp[mt][r] = 0.f;
+    bf16x8 fk[R][HB], fv[R][HB], fb[2][DT];
 #pragma unroll
-        for (int t = 0; t < D / 16; ++t) {
-            acc_s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tl.frag_row(ks, mt, t), qf[t], acc_s[mt], 0, 0, 0);
-            acc_dp[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tl.frag_row(vs, mt, t), dof[t], acc_dp[mt], 0, 0, 0);
+    for (int b = 0; b < R - 1; ++b)
+#pragma unroll
+        for (int i = 0; i < HB; ++i) {
+            fk[b][i] = tl.frag_row(ks, b / PER, (b % PER) * HB + i);
+            fv[b][i] = tl.frag_row(vs, b / PER, (b % PER) * HB + i);
         }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {  // batch b: row tile b / PER, D-steps (b % PER) HB ..
+        constexpr int AHEAD = R - 1;
+        if (b + AHEAD < NB) {
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                fk[(b + AHEAD) % R][i] = tl.frag_row(ks, (b + AHEAD) / PER, ((b + AHEAD) % PER) * HB + i);
+                fv[(b + AHEAD) % R][i] = tl.frag_row(vs, (b + AHEAD) / PER, ((b + AHEAD) % PER) * HB + i);
+            }
+        } else if (b + AHEAD == NB) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) fb[0][dt] = tl.frag_tr(ks, dt, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < HB; ++i) {
+            acc_s[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[b % R][i], qf[(b % PER) * HB + i], acc_s[b / PER], 0, 0, 0);
+            acc_dp[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[b % R][i], dof[(b % PER) * HB + i], acc_dp[b / PER], 0, 0, 0);
+        }
+        if (b + AHEAD < NB) OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB);
+        else if (b + AHEAD == NB) OB_SCHED_READS_THEN_MFMA(2 * DT, 2 * HB);
+        else OB_SCHED_READS_THEN_MFMA(0, 2 * HB);
     }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -332,15 +422,20 @@ __device__ __forceinline__ void dq_tile(const unsigned char OB_LDS *__restrict__
         }
 #pragma unroll
     for (int u = 0; u < ST / 16; ++u) {
+        if (u + 1 < ST / 16) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) fb[(u + 1) & 1][dt] = tl.frag_tr(ks, dt, u + 1);
+        }
         const bf16x8 dsb = pack8(acc_s[u >> 1], 8 * (u & 1));
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-            acc_dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tl.frag_tr(ks, dt, u), dsb, acc_dq[dt], 0, 0, 0);
+        for (int dt = 0; dt < DT; ++dt)
+            acc_dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u & 1][dt], dsb, acc_dq[dt], 0, 0, 0);
+        if (u + 1 < ST / 16) OB_SCHED_READS_THEN_MFMA(2 * DT, DT); else OB_SCHED_READS_THEN_MFMA(0, DT);
     }
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse, const float *__restrict__ delta,
     __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo, const int32_t *__restrict__ cu, int n_seg,
@@ -349,7 +444,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     __shared__ __attribute__((aligned(1024))) unsigned char v_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char k_s1[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char v_s1[Tile<D>::BYTES];
-    __shared__ int sh[4];
+    __shared__ int sh[8];
     const TileInfo ti = find_tile(cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
     const int head = blockIdx.y, kvh = head / group;
@@ -434,24 +529,58 @@ __device__ __forceinline__ void dkv_tile(const unsigned char OB_LDS *__restrict_
                                          f32x16 (&acc_dv)[D / 32], int q0, int seg_end, int kv_row,
                                          bool need_mask, float sl2) {
     const int lh = (threadIdx.x & 63) >> 5;
+    constexpr int HB = D / 32;  // D-steps per batch (a batch reads HB fragments of Q and HB of dO)
+    constexpr int NB = 2 * (D / 16) / HB;
+    constexpr int PER = NB / 2;
+    constexpr int DT = D / 32;
     f32x16 acc_s[2], acc_dp[2];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt) {
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_s[mt][r] = acc_dp[mt][r] = 0.f;
+    bf16x8 fq[2][HB], fd[2][HB], tq_f[2][DT], td_f[2][DT];
+    // row statistics of the 64 query rows: each lane needs 4 consecutive rows per 8-row group
+    f32x4 l4[2][4], d4[2][4];
 #pragma unroll
-        for (int t = 0; t < D / 16; ++t) {
-            acc_s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq.frag_row(qs, mt, t), kf[t], acc_s[mt], 0, 0, 0);
-            acc_dp[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td.frag_row(dos, mt, t), vf[t], acc_dp[mt], 0, 0, 0);
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            l4[mt][g] = *(const f32x4 OB_LDS *)(lse_s + mt * 32 + 8 * g + 4 * lh);
+            d4[mt][g] = *(const f32x4 OB_LDS *)(dlt_s + mt * 32 + 8 * g + 4 * lh);
         }
+#pragma unroll
+    for (int i = 0; i < HB; ++i) {
+        fq[0][i] = tq.frag_row(qs, 0, i);
+        fd[0][i] = td.frag_row(dos, 0, i);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        if (b + 1 < NB) {
+#pragma unroll
+            for (int i = 0; i < HB; ++i) {
+                fq[(b + 1) & 1][i] = tq.frag_row(qs, (b + 1) / PER, ((b + 1) % PER) * HB + i);
+                fd[(b + 1) & 1][i] = td.frag_row(dos, (b + 1) / PER, ((b + 1) % PER) * HB + i);
+            }
+        } else {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                td_f[0][dt] = td.frag_tr(dos, dt, 0);
+                tq_f[0][dt] = tq.frag_tr(qs, dt, 0);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < HB; ++i) {
+            acc_s[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[b & 1][i], kf[(b % PER) * HB + i], acc_s[b / PER], 0, 0, 0);
+            acc_dp[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[b & 1][i], vf[(b % PER) * HB + i], acc_dp[b / PER], 0, 0, 0);
+        }
+        if (b + 1 < NB) OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB); else OB_SCHED_READS_THEN_MFMA(4 * DT, 2 * HB);
     }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             const int qi = mt * 32 + 8 * g + 4 * lh;  // 4 consecutive query rows
-            const f32x4 l4 = *(const f32x4 OB_LDS *)(lse_s + qi);
-            const f32x4 d4 = *(const f32x4 OB_LDS *)(dlt_s + qi);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int r = 4 * g + e;
@@ -460,20 +589,28 @@ __device__ __forceinline__ void dkv_tile(const unsigned char OB_LDS *__restrict_
                     const int qr = q0 + qi + e;
                     ok = qr < seg_end && (!CAUSAL || kv_row <= qr);
                 }
-                const float p = ok ? fast_exp2(acc_s[mt][r] * sl2 - l4[e] * LOG2E) : 0.f;
+                const float p = ok ? fast_exp2(acc_s[mt][r] * sl2 - l4[mt][g][e] * LOG2E) : 0.f;
                 acc_s[mt][r] = p;
-                acc_dp[mt][r] = p * (acc_dp[mt][r] - d4[e]);
+                acc_dp[mt][r] = p * (acc_dp[mt][r] - d4[mt][g][e]);
             }
         }
 #pragma unroll
     for (int u = 0; u < ST / 16; ++u) {
+        if (u + 1 < ST / 16) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                td_f[(u + 1) & 1][dt] = td.frag_tr(dos, dt, u + 1);
+                tq_f[(u + 1) & 1][dt] = tq.frag_tr(qs, dt, u + 1);
+            }
+        }
         const bf16x8 pb = pack8(acc_s[u >> 1], 8 * (u & 1));
         const bf16x8 dsb = pack8(acc_dp[u >> 1], 8 * (u & 1));
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-            acc_dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td.frag_tr(dos, dt, u), pb, acc_dv[dt], 0, 0, 0);
-            acc_dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq.frag_tr(qs, dt, u), dsb, acc_dk[dt], 0, 0, 0);
+        for (int dt = 0; dt < DT; ++dt) {
+            acc_dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td_f[u & 1][dt], pb, acc_dv[dt], 0, 0, 0);
+            acc_dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq_f[u & 1][dt], dsb, acc_dk[dt], 0, 0, 0);
         }
+        if (u + 1 < ST / 16) OB_SCHED_READS_THEN_MFMA(4 * DT, 2 * DT); else OB_SCHED_READS_THEN_MFMA(0, 2 * DT);
     }
 }
 
@@ -493,7 +630,8 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse, const float *__restrict__ delta,
-    __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int ldq, int ldkv, int ldo,
+    __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, float *__restrict__ part_dk,
+    float *__restrict__ part_dv, int nkv, int ldq, int ldkv, int ldo,
     const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale) {
     __shared__ __attribute__((aligned(1024))) unsigned char q_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char do_s0[Tile<D>::BYTES];
@@ -503,10 +641,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     __shared__ __attribute__((aligned(256))) float dlt_s0[ST];
     __shared__ __attribute__((aligned(256))) float lse_s1[ST];
     __shared__ __attribute__((aligned(256))) float dlt_s1[ST];
-    __shared__ int sh[4];
+    __shared__ int sh[8];
     const TileInfo ti = find_tile(cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
-    const int kvh = blockIdx.y;
+    const int head = blockIdx.y, kvh = head / group;
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int kv_row = min(ti.row0 + wave * 32 + lx, ti.seg_end - 1);
@@ -538,13 +676,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
 
     // causal: query rows before this workgroup's first key row see none of its keys
     const int q_begin = CAUSAL ? ti.seg_start + ((ti.row0 - ti.seg_start) / ST) * ST : ti.seg_start;
-    const int tiles_per_head = (ti.seg_end - q_begin + ST - 1) / ST;
-    const int n_iter = group * tiles_per_head;
+    const int n_iter = (ti.seg_end - q_begin + ST - 1) / ST;
     const long q_total = (long)T * ldq * 2, do_total = (long)T * ldo * 2;
 #define OB_ISSUE_DKV(it, stage)                                                                          \
     do {                                                                                                 \
-        const int hd_ = kvh * group + (it) / tiles_per_head;                                             \
-        const int q0_ = q_begin + ((it) % tiles_per_head) * ST;                                          \
+        const int hd_ = head;                                                                            \
+        const int q0_ = q_begin + (it) * ST;                                                             \
         const long qo_ = (long)q0_ * ldq * 2 + (long)hd_ * D * 2;                                        \
         const long do_ = (long)q0_ * ldo * 2 + (long)hd_ * D * 2;                                        \
         tq.issue((const unsigned char *)q + qo_, q_total - qo_, qs##stage, wave);                        \
@@ -554,7 +691,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     } while (0)
     OB_ISSUE_DKV(0, 0);
     for (int it = 0; it < n_iter; ++it) {
-        const int q0 = q_begin + (it % tiles_per_head) * ST;
+        const int q0 = q_begin + it * ST;
         __builtin_amdgcn_s_waitcnt(WAIT_VM0);
         __syncthreads();
         if (it + 1 < n_iter) {
@@ -572,20 +709,63 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     }
 #undef OB_ISSUE_DKV
     if (!kv_live) return;
+    if (group == 1) {
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+        for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            bf16x4 ok_, ov_;
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 ok_, ov_;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                ok_[e] = (__bf16)(acc_dk[dt][4 * g + e] * scale);
-                ov_[e] = (__bf16)acc_dv[dt][4 * g + e];
+                for (int e = 0; e < 4; ++e) {
+                    ok_[e] = (__bf16)(acc_dk[dt][4 * g + e] * scale);
+                    ov_[e] = (__bf16)acc_dv[dt][4 * g + e];
+                }
+                const size_t off = (size_t)kv_row * ldkv + kvh * D + dt * 32 + g * 8 + lh * 4;
+                *(bf16x4 *)(dk + off) = ok_;
+                *(bf16x4 *)(dv + off) = ov_;
             }
-            const size_t off = (size_t)kv_row * ldkv + kvh * D + dt * 32 + g * 8 + lh * 4;
-            *(bf16x4 *)(dk + off) = ok_;
-            *(bf16x4 *)(dv + off) = ov_;
-        }
+    } else {
+        // one fp32 partial per query head of the group, summed in fixed order by the reduce kernel
+        const size_t pbase = ((size_t)(head % group) * T + kv_row) * ((size_t)nkv * D) + (size_t)kvh * D;
+#pragma unroll
+        for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 pk, pv;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    pk[e] = acc_dk[dt][4 * g + e] * scale;
+                    pv[e] = acc_dv[dt][4 * g + e];
+                }
+                const size_t off = pbase + dt * 32 + g * 8 + lh * 4;
+                *(f32x4 *)(part_dk + off) = pk;
+                *(f32x4 *)(part_dv + off) = pv;
+            }
+    }
+}
+
+// dk / dv = sum over the group's query heads of the fp32 partials, in head order
+__global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(const float *__restrict__ part_dk,
+                                                              const float *__restrict__ part_dv,
+                                                              __bf16 *__restrict__ dk, __bf16 *__restrict__ dv,
+                                                              int T, int width, int ldkv, int group) {
+    const int per_row = width / 4;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)T * per_row) return;
+    const long row = i / per_row;
+    const int c = (int)(i % per_row) * 4;
+    f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < group; ++g) {
+        const size_t off = ((size_t)g * T + row) * width + c;
+        const f32x4 a = *(const f32x4 *)(part_dk + off), b = *(const f32x4 *)(part_dv + off);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { sk[e] += a[e]; sv[e] += b[e]; }
+    }
+    bf16x4 ok_, ov_;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { ok_[e] = (__bf16)sk[e]; ov_[e] = (__bf16)sv[e]; }
+    *(bf16x4 *)(dk + (size_t)row * ldkv + c) = ok_;
+    *(bf16x4 *)(dv + (size_t)row * ldkv + c) = ov_;
 }
 
 // algorithmic forward FLOPs: 4 nq d sum_seg A(s), A = s^2 or s (s + 1) / 2 (causal)
@@ -616,8 +796,8 @@ int count_tiles(const ob_segments *seg, int tile_rows) {
                                                       int, int, int, const int32_t *, int, int, int, float);  \
     template __global__ void attn_bwd_dkv_kernel<D, C>(const __bf16 *, const __bf16 *, const __bf16 *,        \
                                                        const __bf16 *, const float *, const float *,          \
-                                                       __bf16 *, __bf16 *, int, int, int, const int32_t *,    \
-                                                       int, int, int, float);
+                                                       __bf16 *, __bf16 *, float *, float *, int, int, int,   \
+                                                       int, const int32_t *, int, int, int, float);
 OB_ATTN_INSTANCES(64, true)
 OB_ATTN_INSTANCES(64, false)
 OB_ATTN_INSTANCES(128, true)
@@ -650,12 +830,14 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
 }
 
 void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse,
-                     const float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
-                     const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
+                     const float *delta, void *dq, void *dk, void *dv, float *part, int ldq, int ldkv,
+                     int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
                      hipStream_t s) {
     const bool causal = mask == OB_MASK_SEG_CAUSAL;
     const int tiles = count_tiles(seg, QT);
-    const dim3 grid_q(tiles, nq), grid_kv(tiles, nkv);
+    const int T = seg->total_tokens, group = nq / nkv;
+    const dim3 grid_q(tiles, nq);
+    float *part_dk = part, *part_dv = part ? part + (size_t)group * T * nkv * d : nullptr;
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
         OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, (const __bf16 *)d_o, (const __bf16 *)q,
@@ -663,9 +845,19 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
                          seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
     }
     ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
-    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_kv, (const __bf16 *)d_o, (const __bf16 *)q,
-                     (const __bf16 *)k, (const __bf16 *)v, lse, delta, (__bf16 *)dk, (__bf16 *)dv, ldq,
-                     ldkv, ldo, seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
+    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_q, (const __bf16 *)d_o, (const __bf16 *)q,
+                     (const __bf16 *)k, (const __bf16 *)v, lse, delta, (__bf16 *)dk, (__bf16 *)dv, part_dk,
+                     part_dv, nkv, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, T, group, scale);
+    if (group > 1) {
+        const long quads = (long)T * (nkv * d / 4);
+        hipLaunchKernelGGL(attn_dkv_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
+                           part_dk, part_dv, (__bf16 *)dk, (__bf16 *)dv, T, nkv * d, ldkv, group);
+    }
+}
+
+// fp32 scratch of the backward behind Delta: one dK and one dV partial per query head of a group
+size_t attn_bwd_partial_bytes(int T, int nq, int nkv, int d) {
+    return nq == nkv ? 0 : (size_t)2 * (nq / nkv) * T * nkv * d * 4;
 }
 
 }  // namespace ob

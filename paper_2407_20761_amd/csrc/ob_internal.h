@@ -64,9 +64,11 @@ void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out
 void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int ldq,
                      int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale,
                      int mask, hipStream_t s);
+// part: attn_bwd_partial_bytes() bytes of fp32 scratch (unused, may be null, when nq == nkv)
 void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse,
-                     const float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
-                     const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
+                     const float *delta, void *dq, void *dk, void *dv, float *part, int ldq, int ldkv,
+                     int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
                      hipStream_t s);
+size_t attn_bwd_partial_bytes(int T, int nq, int nkv, int d);
 
 }  // namespace ob

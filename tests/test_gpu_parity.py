@@ -86,7 +86,7 @@ def test_varlen_attention_fwd_bwd(lens, nq, nkv, d, mask):
     assert rel_err(to_np(o).reshape(T, nq, d), o_ref) < TOL
     assert np.abs(to_np(lse) - lse_ref).max() < 2e-2
     dqkv = torch.full((T, Dq), float("nan"), dtype=torch.bfloat16, device="cuda")
-    ws = bytes_buf(ob.ob_varlen_attn_bwd_workspace_bytes(T, nq))
+    ws = bytes_buf(ob.ob_varlen_attn_bwd_workspace_bytes(T, nq, nkv, d))
     dod = to_dev(d_o.reshape(T, -1))
     ob.ob_varlen_attn_bwd(dod, qd, kd, vd, o, lse, dqkv[:, :nq * d], dqkv[:, nq * d:(nq + nkv) * d],
                           dqkv[:, (nq + nkv) * d:], Dq, Dq, nq * d, seg, nq, nkv, d, scale, mask, ws)
