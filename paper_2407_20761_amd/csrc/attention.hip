@@ -181,12 +181,11 @@ __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, in
         __builtin_amdgcn_sched_barrier(0);                         \
     } while (0)
 
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool MASK>
 __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict__ ks,
                                          const unsigned char OB_LDS *__restrict__ vs, const Tile<D> &tl,
                                          const bf16x8 (&qf)[D / 16], f32x16 (&acc_o)[D / 32], float &m_run,
-                                         float &l_run, int kv0, int seg_end, int q_row, bool need_mask,
-                                         float sl2) {
+                                         float &l_run, int kv0, int seg_end, int q_row, float sl2) {
     const int lh = (threadIdx.x & 63) >> 5;
     constexpr int HB = 2;                 // K fragments (D-steps) per batch
     constexpr int R = D == 128 ? 3 : 2;   // batches in flight (ring depth)
@@ -222,7 +221,7 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
         else OB_SCHED_READS_THEN_MFMA(0, HB);
     }
     float mx = NEG_BIG;
-    if (need_mask) {
+    if (MASK) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -296,8 +295,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q_row = min(ti.row0 + wave * 32 + lx, ti.seg_end - 1);
     const bool q_live = ti.row0 + wave * 32 + lx < ti.seg_end;
-    const int wave_q_first = ti.row0 + wave * 32;
-    const int wave_q_last = min(wave_q_first + 31, ti.seg_end - 1);
+    const int wave_q_last = min(ti.row0 + wave * 32 + 31, ti.seg_end - 1);
     const float sl2 = scale * LOG2E;
 
     Tile<D> tl;
@@ -326,22 +324,30 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
         tl.issue(kbase + off, kv_bytes - off, ks0, wave);
         tl.issue(vbase + off, kv_bytes - off, vs0, wave);
     }
-    for (int j = 0; j < n_tiles; ++j) {
-        const int kv0 = ti.seg_start + j * ST;
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-        __syncthreads();
-        if (j + 1 < n_tiles) {
-            const long off = (long)(kv0 + ST) * ldkv * 2;
-            tl.issue(kbase + off, kv_bytes - off, (j & 1) ? ks0 : ks1, wave);
-            tl.issue(vbase + off, kv_bytes - off, (j & 1) ? vs0 : vs1, wave);
-        }
-        if (CAUSAL && kv0 > wave_q_last) continue;
-        const bool need_mask = kv0 + ST > ti.seg_end || (CAUSAL && kv0 + ST - 1 > wave_q_first);
-        if (j & 1)
-            fwd_tile<D, CAUSAL>(ks1, vs1, tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row, need_mask, sl2);
-        else
-            fwd_tile<D, CAUSAL>(ks0, vs0, tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row, need_mask, sl2);
+    // Tiles before the workgroup's first row (causal) or before the ragged end need no mask; they
+    // run in a loop of their own whose body is a single straight path (with several paths per
+    // iteration the register allocator shuffles the accumulators between homes every iteration).
+    const int n_main = CAUSAL ? (ti.row0 - ti.seg_start) / ST : (ti.seg_end - ti.seg_start) / ST;
+    int j = 0;
+#define OB_FWD_ITER(MASKED)                                                                              \
+    {                                                                                                    \
+        const int kv0 = ti.seg_start + j * ST;                                                           \
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                            \
+        __syncthreads();                                                                                 \
+        if (j + 1 < n_tiles) {                                                                           \
+            const long off = (long)(kv0 + ST) * ldkv * 2;                                                \
+            tl.issue(kbase + off, kv_bytes - off, (j & 1) ? ks0 : ks1, wave);                            \
+            tl.issue(vbase + off, kv_bytes - off, (j & 1) ? vs0 : vs1, wave);                            \
+        }                                                                                                \
+        const unsigned char OB_LDS *const ks = (j & 1) ? ks1 : ks0, *const vs = (j & 1) ? vs1 : vs0;     \
+        if (!(MASKED))                                                                                   \
+            fwd_tile<D, CAUSAL, false>(ks, vs, tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row, sl2); \
+        else if (!(CAUSAL && kv0 > wave_q_last))                                                         \
+            fwd_tile<D, CAUSAL, true>(ks, vs, tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row, sl2); \
     }
+    for (; j < n_main; ++j) OB_FWD_ITER(false)
+    for (; j < n_tiles; ++j) OB_FWD_ITER(true)
+#undef OB_FWD_ITER
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (!q_live) return;
     const float inv = 1.0f / l_tot;
@@ -361,12 +367,12 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 // backward, part 1: dQ.  Same ownership as the forward; P is rebuilt from the saved log-sum-exp.
 //   S^T = K Q^T,  P = exp(scale S - lse),  dP^T = V dO^T,  dS^T = P (dP^T - Delta),  dQ^T += K^T dS^T
 // ------------------------------------------------------------------------------------------------
-template <int D, bool CAUSAL>
+template <int D, bool CAUSAL, bool MASK>
 __device__ __forceinline__ void dq_tile(const unsigned char OB_LDS *__restrict__ ks,
                                         const unsigned char OB_LDS *__restrict__ vs, const Tile<D> &tl,
                                         const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16],
                                         f32x16 (&acc_dq)[D / 32], float lse2, float dlt, int kv0, int seg_end,
-                                        int q_row, bool need_mask, float sl2) {
+                                        int q_row, float sl2) {
     const int lh = (threadIdx.x & 63) >> 5;
     constexpr int HB = D == 128 ? 1 : 2;  // D-steps per batch (a batch reads HB fragments of K and HB of V)
     constexpr int R = D == 128 ? 4 : 2;   // batches in flight (ring depth)
@@ -413,7 +419,7 @@ __device__ __forceinline__ void dq_tile(const unsigned char OB_LDS *__restrict__
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             bool ok = true;
-            if (need_mask) {
+            if (MASK) {
                 const int kv = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                 ok = kv < seg_end && (!CAUSAL || kv <= q_row);
             }
@@ -437,7 +443,7 @@ __device__ __forceinline__ void dq_tile(const unsigned char OB_LDS *__restrict__
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
-    const __bf16 *__restrict__ v, const float *__restrict__ lse, const float *__restrict__ delta,
+    const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo, const int32_t *__restrict__ cu, int n_seg,
     int T, int group, float scale) {
     __shared__ __attribute__((aligned(1024))) unsigned char k_s0[Tile<D>::BYTES];
@@ -452,8 +458,7 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q_row = min(ti.row0 + wave * 32 + lx, ti.seg_end - 1);
     const bool q_live = ti.row0 + wave * 32 + lx < ti.seg_end;
-    const int wave_q_first = ti.row0 + wave * 32;
-    const int wave_q_last = min(wave_q_first + 31, ti.seg_end - 1);
+    const int wave_q_last = min(ti.row0 + wave * 32 + 31, ti.seg_end - 1);
     const float sl2 = scale * LOG2E;
 
     Tile<D> tl;
@@ -468,7 +473,7 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
         qf[t] = *(const bf16x8 *)(q + (size_t)q_row * ldq + head * D + 16 * t + 8 * lh);
         dof[t] = *(const bf16x8 *)(d_o + (size_t)q_row * ldo + head * D + 16 * t + 8 * lh);
     }
-    const float lse2 = lse[(size_t)head * T + q_row] * LOG2E;
+    const float lse2 = lse2_all[(size_t)head * T + q_row];
     const float dlt = delta[(size_t)head * T + q_row];
     f32x16 acc_dq[D / 32];
 #pragma unroll
@@ -485,22 +490,27 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
         tl.issue(kbase + off, kv_bytes - off, ks0, wave);
         tl.issue(vbase + off, kv_bytes - off, vs0, wave);
     }
-    for (int j = 0; j < n_tiles; ++j) {
-        const int kv0 = ti.seg_start + j * ST;
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-        __syncthreads();
-        if (j + 1 < n_tiles) {
-            const long off = (long)(kv0 + ST) * ldkv * 2;
-            tl.issue(kbase + off, kv_bytes - off, (j & 1) ? ks0 : ks1, wave);
-            tl.issue(vbase + off, kv_bytes - off, (j & 1) ? vs0 : vs1, wave);
-        }
-        if (CAUSAL && kv0 > wave_q_last) continue;
-        const bool need_mask = kv0 + ST > ti.seg_end || (CAUSAL && kv0 + ST - 1 > wave_q_first);
-        if (j & 1)
-            dq_tile<D, CAUSAL>(ks1, vs1, tl, qf, dof, acc_dq, lse2, dlt, kv0, ti.seg_end, q_row, need_mask, sl2);
-        else
-            dq_tile<D, CAUSAL>(ks0, vs0, tl, qf, dof, acc_dq, lse2, dlt, kv0, ti.seg_end, q_row, need_mask, sl2);
+    const int n_main = CAUSAL ? (ti.row0 - ti.seg_start) / ST : (ti.seg_end - ti.seg_start) / ST;
+    int j = 0;
+#define OB_DQ_ITER(MASKED)                                                                                   \
+    {                                                                                                        \
+        const int kv0 = ti.seg_start + j * ST;                                                               \
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                                \
+        __syncthreads();                                                                                     \
+        if (j + 1 < n_tiles) {                                                                               \
+            const long off = (long)(kv0 + ST) * ldkv * 2;                                                    \
+            tl.issue(kbase + off, kv_bytes - off, (j & 1) ? ks0 : ks1, wave);                                \
+            tl.issue(vbase + off, kv_bytes - off, (j & 1) ? vs0 : vs1, wave);                                \
+        }                                                                                                    \
+        const unsigned char OB_LDS *const ks = (j & 1) ? ks1 : ks0, *const vs = (j & 1) ? vs1 : vs0;         \
+        if (!(MASKED))                                                                                       \
+            dq_tile<D, CAUSAL, false>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv0, ti.seg_end, q_row, sl2);   \
+        else if (!(CAUSAL && kv0 > wave_q_last))                                                             \
+            dq_tile<D, CAUSAL, true>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv0, ti.seg_end, q_row, sl2);    \
     }
+    for (; j < n_main; ++j) OB_DQ_ITER(false)
+    for (; j < n_tiles; ++j) OB_DQ_ITER(true)
+#undef OB_DQ_ITER
     if (!q_live) return;
 #pragma unroll
     for (int dt = 0; dt < D / 32; ++dt)
@@ -516,10 +526,46 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
 // ------------------------------------------------------------------------------------------------
 // backward, part 2: dK, dV.  A wave owns 32 key rows of one KV head and streams, for every query
 // head of the group, the segment's query rows (from the diagonal on when causal):
-//   S = Q K^T,  P = exp(scale S - lse),  dV^T += dO^T P,  dP = dO V^T,  dS = P (dP - Delta),
+//   S = Q K^T,  P = 2^(scale log2(e) S - lse2),  dV^T += dO^T P,  dP = dO V^T,  dS = P (dP - Delta),
 //   dK^T += Q^T dS.   The sum over the group's query heads happens in the accumulators.
 // ------------------------------------------------------------------------------------------------
-template <int D, bool CAUSAL>
+// probabilities and score gradients of 32 query rows (one 32x32 accumulator pair), packed as the
+// second operands of the two 16-row contraction steps that consume them
+template <bool CAUSAL, bool MASK>
+__device__ __forceinline__ void dkv_softmax_half(const f32x16 &s, const f32x16 &dp, const f32x4 (&l4)[4],
+                                                 const f32x4 (&d4)[4], int q_first, int seg_end, int kv_row,
+                                                 float sl2, bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) {
+    const int lh = (threadIdx.x & 63) >> 5;
+    f32x16 p, ds;
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int r = 4 * g + e;
+            bool ok = true;
+            if (MASK) {
+                const int qr = q_first + 8 * g + 4 * lh + e;
+                ok = qr < seg_end && (!CAUSAL || kv_row <= qr);
+            }
+            p[r] = ok ? fast_exp2(s[r] * sl2 - l4[g][e]) : 0.f;
+            ds[r] = p[r] * (dp[r] - d4[g][e]);
+        }
+    pb[0] = pack8(p, 0);
+    pb[1] = pack8(p, 8);
+    dsb[0] = pack8(ds, 0);
+    dsb[1] = pack8(ds, 8);
+}
+
+// n x (1 MFMA, nv VALU, nt transcendental): the element-wise work of one half tile is spread under
+// the MFMAs of the next (a wavefront running alone on its SIMD has no other wave to hide it)
+#define OB_SCHED_MFMA_VALU(n, nv, nt)                              \
+    _Pragma("unroll") for (int i_ = 0; i_ < (n); ++i_) {           \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         \
+        __builtin_amdgcn_sched_group_barrier(0x002, (nv), 0);      \
+        __builtin_amdgcn_sched_group_barrier(0x400, (nt), 0);      \
+    }
+
+template <int D, bool CAUSAL, bool MASK>
 __device__ __forceinline__ void dkv_tile(const unsigned char OB_LDS *__restrict__ qs,
                                          const unsigned char OB_LDS *__restrict__ dos,
                                          const float OB_LDS *__restrict__ lse_s,
@@ -527,40 +573,57 @@ __device__ __forceinline__ void dkv_tile(const unsigned char OB_LDS *__restrict_
                                          const Tile<D> &td, const bf16x8 (&kf)[D / 16],
                                          const bf16x8 (&vf)[D / 16], f32x16 (&acc_dk)[D / 32],
                                          f32x16 (&acc_dv)[D / 32], int q0, int seg_end, int kv_row,
-                                         bool need_mask, float sl2) {
+                                         float sl2) {
     const int lh = (threadIdx.x & 63) >> 5;
     constexpr int HB = D / 32;  // D-steps per batch (a batch reads HB fragments of Q and HB of dO)
     constexpr int NB = 2 * (D / 16) / HB;
-    constexpr int PER = NB / 2;
+    constexpr int PER = NB / 2;  // batches per 32-row half
     constexpr int DT = D / 32;
+    constexpr int NV = 96 / (4 * HB), NT = 16 / (4 * HB);  // element-wise work of a half per MFMA of the next
+    static_assert(PER == 2 && DT == HB, "the phase schedule below assumes two batches per half");
     f32x16 acc_s[2], acc_dp[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_s[mt][r] = acc_dp[mt][r] = 0.f;
     bf16x8 fq[2][HB], fd[2][HB], tq_f[2][DT], td_f[2][DT];
-    // row statistics of the 64 query rows: each lane needs 4 consecutive rows per 8-row group
-    f32x4 l4[2][4], d4[2][4];
+    bf16x8 pb[2][2], dsb[2][2];
+    // row statistics of 32 query rows: each lane needs 4 consecutive rows per 8-row group
+    f32x4 l4[4], d4[4];
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            l4[mt][g] = *(const f32x4 OB_LDS *)(lse_s + mt * 32 + 8 * g + 4 * lh);
-            d4[mt][g] = *(const f32x4 OB_LDS *)(dlt_s + mt * 32 + 8 * g + 4 * lh);
-        }
+    for (int g = 0; g < 4; ++g) {
+        l4[g] = *(const f32x4 OB_LDS *)(lse_s + 8 * g + 4 * lh);
+        d4[g] = *(const f32x4 OB_LDS *)(dlt_s + 8 * g + 4 * lh);
+    }
 #pragma unroll
     for (int i = 0; i < HB; ++i) {
         fq[0][i] = tq.frag_row(qs, 0, i);
         fd[0][i] = td.frag_row(dos, 0, i);
     }
     __builtin_amdgcn_sched_barrier(0);
+    // phase A: S and dP of query rows 0..31
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
+    for (int b = 0; b < PER; ++b) {
+#pragma unroll
+        for (int i = 0; i < HB; ++i) {
+            fq[(b + 1) & 1][i] = tq.frag_row(qs, (b + 1) / PER, ((b + 1) % PER) * HB + i);
+            fd[(b + 1) & 1][i] = td.frag_row(dos, (b + 1) / PER, ((b + 1) % PER) * HB + i);
+        }
+#pragma unroll
+        for (int i = 0; i < HB; ++i) {
+            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[b & 1][i], kf[b * HB + i], acc_s[0], 0, 0, 0);
+            acc_dp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[b & 1][i], vf[b * HB + i], acc_dp[0], 0, 0, 0);
+        }
+        OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB);
+    }
+    // phase B: S and dP of rows 32..63, with the element-wise work of rows 0..31 underneath
+#pragma unroll
+    for (int b = PER; b < NB; ++b) {
         if (b + 1 < NB) {
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
-                fq[(b + 1) & 1][i] = tq.frag_row(qs, (b + 1) / PER, ((b + 1) % PER) * HB + i);
-                fd[(b + 1) & 1][i] = td.frag_row(dos, (b + 1) / PER, ((b + 1) % PER) * HB + i);
+                fq[(b + 1) & 1][i] = tq.frag_row(qs, 1, ((b + 1) % PER) * HB + i);
+                fd[(b + 1) & 1][i] = td.frag_row(dos, 1, ((b + 1) % PER) * HB + i);
             }
         } else {
 #pragma unroll
@@ -571,46 +634,57 @@ __device__ __forceinline__ void dkv_tile(const unsigned char OB_LDS *__restrict_
         }
 #pragma unroll
         for (int i = 0; i < HB; ++i) {
-            acc_s[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[b & 1][i], kf[(b % PER) * HB + i], acc_s[b / PER], 0, 0, 0);
-            acc_dp[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[b & 1][i], vf[(b % PER) * HB + i], acc_dp[b / PER], 0, 0, 0);
+            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[b & 1][i], kf[(b % PER) * HB + i], acc_s[1], 0, 0, 0);
+            acc_dp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[b & 1][i], vf[(b % PER) * HB + i], acc_dp[1], 0, 0, 0);
         }
-        if (b + 1 < NB) OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB); else OB_SCHED_READS_THEN_MFMA(4 * DT, 2 * HB);
+    }
+    dkv_softmax_half<CAUSAL, MASK>(acc_s[0], acc_dp[0], l4, d4, q0, seg_end, kv_row, sl2, pb[0], dsb[0]);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * HB, 0);
+    OB_SCHED_MFMA_VALU(2 * HB, NV, NT)
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 * DT, 0);
+    OB_SCHED_MFMA_VALU(2 * HB, NV, NT)
+    __builtin_amdgcn_sched_barrier(0);
+    // phase C: dV and dK from rows 0..31, with the element-wise work of rows 32..63 underneath
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        l4[g] = *(const f32x4 OB_LDS *)(lse_s + 32 + 8 * g + 4 * lh);
+        d4[g] = *(const f32x4 OB_LDS *)(dlt_s + 32 + 8 * g + 4 * lh);
     }
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int qi = mt * 32 + 8 * g + 4 * lh;  // 4 consecutive query rows
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int r = 4 * g + e;
-                bool ok = true;
-                if (need_mask) {
-                    const int qr = q0 + qi + e;
-                    ok = qr < seg_end && (!CAUSAL || kv_row <= qr);
-                }
-                const float p = ok ? fast_exp2(acc_s[mt][r] * sl2 - l4[mt][g][e] * LOG2E) : 0.f;
-                acc_s[mt][r] = p;
-                acc_dp[mt][r] = p * (acc_dp[mt][r] - d4[mt][g][e]);
-            }
+        for (int dt = 0; dt < DT; ++dt) {
+            td_f[(u + 1) & 1][dt] = td.frag_tr(dos, dt, u + 1);
+            tq_f[(u + 1) & 1][dt] = tq.frag_tr(qs, dt, u + 1);
         }
 #pragma unroll
-    for (int u = 0; u < ST / 16; ++u) {
-        if (u + 1 < ST / 16) {
+        for (int dt = 0; dt < DT; ++dt) {
+            acc_dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td_f[u & 1][dt], pb[0][u], acc_dv[dt], 0, 0, 0);
+            acc_dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq_f[u & 1][dt], dsb[0][u], acc_dk[dt], 0, 0, 0);
+        }
+    }
+    dkv_softmax_half<CAUSAL, MASK>(acc_s[1], acc_dp[1], l4, d4, q0 + 32, seg_end, kv_row, sl2, pb[1], dsb[1]);
+    __builtin_amdgcn_sched_group_barrier(0x100, 8 + 4 * DT, 0);
+    OB_SCHED_MFMA_VALU(2 * DT, NV, NT)
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 * DT, 0);
+    OB_SCHED_MFMA_VALU(2 * DT, NV, NT)
+    __builtin_amdgcn_sched_barrier(0);
+    // phase D: dV and dK from rows 32..63
+#pragma unroll
+    for (int u = 2; u < 4; ++u) {
+        if (u + 1 < 4) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 td_f[(u + 1) & 1][dt] = td.frag_tr(dos, dt, u + 1);
                 tq_f[(u + 1) & 1][dt] = tq.frag_tr(qs, dt, u + 1);
             }
         }
-        const bf16x8 pb = pack8(acc_s[u >> 1], 8 * (u & 1));
-        const bf16x8 dsb = pack8(acc_dp[u >> 1], 8 * (u & 1));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            acc_dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td_f[u & 1][dt], pb, acc_dv[dt], 0, 0, 0);
-            acc_dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq_f[u & 1][dt], dsb, acc_dk[dt], 0, 0, 0);
+            acc_dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td_f[u & 1][dt], pb[1][u - 2], acc_dv[dt], 0, 0, 0);
+            acc_dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq_f[u & 1][dt], dsb[1][u - 2], acc_dk[dt], 0, 0, 0);
         }
-        if (u + 1 < ST / 16) OB_SCHED_READS_THEN_MFMA(4 * DT, 2 * DT); else OB_SCHED_READS_THEN_MFMA(0, 2 * DT);
+        if (u + 1 < 4) OB_SCHED_READS_THEN_MFMA(4 * DT, 2 * DT); else OB_SCHED_READS_THEN_MFMA(0, 2 * DT);
     }
 }
 
@@ -629,7 +703,7 @@ __device__ __forceinline__ void issue_row_stats(const float *base, long floats_l
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
-    const __bf16 *__restrict__ v, const float *__restrict__ lse, const float *__restrict__ delta,
+    const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, float *__restrict__ part_dk,
     float *__restrict__ part_dv, int nkv, int ldq, int ldkv, int ldo,
     const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale) {
@@ -686,27 +760,36 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
         const long do_ = (long)q0_ * ldo * 2 + (long)hd_ * D * 2;                                        \
         tq.issue((const unsigned char *)q + qo_, q_total - qo_, qs##stage, wave);                        \
         td.issue((const unsigned char *)d_o + do_, do_total - do_, dos##stage, wave);                    \
-        if (wave == 0) issue_row_stats(lse + (size_t)hd_ * T + q0_, (long)T - q0_, lses##stage, lane);   \
+        if (wave == 0) issue_row_stats(lse2_all + (size_t)hd_ * T + q0_, (long)T - q0_, lses##stage, lane);   \
         if (wave == 1) issue_row_stats(delta + (size_t)hd_ * T + q0_, (long)T - q0_, dlts##stage, lane); \
     } while (0)
     OB_ISSUE_DKV(0, 0);
-    for (int it = 0; it < n_iter; ++it) {
-        const int q0 = q_begin + it * ST;
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
-        __syncthreads();
-        if (it + 1 < n_iter) {
-            if (it & 1) OB_ISSUE_DKV(it + 1, 0); else OB_ISSUE_DKV(it + 1, 1);
-        }
-        // a 64-row query tile entirely before this wave's keys contributes nothing
-        if (CAUSAL && q0 + ST - 1 < wave_kv_first) continue;
-        const bool need_mask = q0 + ST > ti.seg_end || (CAUSAL && q0 < wave_kv_first + 31);
-        if (it & 1)
-            dkv_tile<D, CAUSAL>(qs1, dos1, lses1, dlts1, tq, td, kf, vf, acc_dk, acc_dv, q0, ti.seg_end,
-                                kv_row, need_mask, sl2);
-        else
-            dkv_tile<D, CAUSAL>(qs0, dos0, lses0, dlts0, tq, td, kf, vf, acc_dk, acc_dv, q0, ti.seg_end,
-                                kv_row, need_mask, sl2);
+    // causal: only the first two query tiles touch some wave's diagonal; either way only the last
+    // tile can be ragged.  The tiles in between run mask-free in a single-path loop.
+    const int n_head = CAUSAL ? min(2, n_iter) : 0;
+    const int n_mid_end = max(n_head, n_iter - (((ti.seg_end - q_begin) % ST) ? 1 : 0));
+    int it = 0;
+#define OB_DKV_ITER(MASKED)                                                                                \
+    {                                                                                                      \
+        const int q0 = q_begin + it * ST;                                                                  \
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                              \
+        __syncthreads();                                                                                   \
+        if (it + 1 < n_iter) {                                                                             \
+            if (it & 1) OB_ISSUE_DKV(it + 1, 0); else OB_ISSUE_DKV(it + 1, 1);                             \
+        }                                                                                                  \
+        const unsigned char OB_LDS *const qs = (it & 1) ? qs1 : qs0, *const dos = (it & 1) ? dos1 : dos0;  \
+        const float OB_LDS *const lses = (it & 1) ? lses1 : lses0, *const dlts = (it & 1) ? dlts1 : dlts0; \
+        if (!(MASKED))                                                                                     \
+            dkv_tile<D, CAUSAL, false>(qs, dos, lses, dlts, tq, td, kf, vf, acc_dk, acc_dv, q0, ti.seg_end, \
+                                       kv_row, sl2);                                                       \
+        else if (!(CAUSAL && q0 + ST - 1 < wave_kv_first)) /* tile entirely before this wave's keys */     \
+            dkv_tile<D, CAUSAL, true>(qs, dos, lses, dlts, tq, td, kf, vf, acc_dk, acc_dv, q0, ti.seg_end,  \
+                                      kv_row, sl2);                                                        \
     }
+    for (; it < n_head; ++it) OB_DKV_ITER(true)
+    for (; it < n_mid_end; ++it) OB_DKV_ITER(false)
+    for (; it < n_iter; ++it) OB_DKV_ITER(true)
+#undef OB_DKV_ITER
 #undef OB_ISSUE_DKV
     if (!kv_live) return;
     if (group == 1) {
@@ -829,7 +912,7 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
                      nq / nkv, scale);
 }
 
-void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse,
+void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse2,
                      const float *delta, void *dq, void *dk, void *dv, float *part, int ldq, int ldkv,
                      int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
                      hipStream_t s) {
@@ -841,12 +924,12 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
         OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, (const __bf16 *)d_o, (const __bf16 *)q,
-                         (const __bf16 *)k, (const __bf16 *)v, lse, delta, (__bf16 *)dq, ldq, ldkv, ldo,
+                         (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
                          seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
     }
     ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
     OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_q, (const __bf16 *)d_o, (const __bf16 *)q,
-                     (const __bf16 *)k, (const __bf16 *)v, lse, delta, (__bf16 *)dk, (__bf16 *)dv, part_dk,
+                     (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dk, (__bf16 *)dv, part_dk,
                      part_dv, nkv, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, T, group, scale);
     if (group > 1) {
         const long quads = (long)T * (nkv * d / 4);

@@ -327,10 +327,13 @@ __global__ __launch_bounds__(256) void act_bwd_kernel(const __bf16 *__restrict__
 }
 
 // delta[head][t] = sum_d dO[t, head, d] * O[t, head, d]; 8 lanes (d = 64) or 16 lanes (d = 128)
-// share one (t, head) row.
+// share one (t, head) row.  The same pass rewrites the row's log-sum-exp in base-2 units
+// (lse2 = lse * log2 e), the form the backward kernels feed to the hardware's 2^x.
 __global__ __launch_bounds__(256) void attn_delta_kernel(const __bf16 *__restrict__ d_o,
                                                          const __bf16 *__restrict__ o, int ldo,
-                                                         float *__restrict__ delta, int T, int nq,
+                                                         const float *__restrict__ lse,
+                                                         float *__restrict__ delta,
+                                                         float *__restrict__ lse2, int T, int nq,
                                                          int d) {
     const int lanes = d / 8;
     const long gid = (long)blockIdx.x * 256 + threadIdx.x;
@@ -349,7 +352,10 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(const __bf16 *__restric
         for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)b[e];
     }
     for (int off = lanes >> 1; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-    if (live && part == 0) delta[(size_t)head * T + t] = s;
+    if (live && part == 0) {
+        delta[(size_t)head * T + t] = s;
+        lse2[(size_t)head * T + t] = lse[(size_t)head * T + t] * 1.4426950408889634f;
+    }
 }
 
 __global__ __launch_bounds__(256) void mask_kernel(const int32_t *__restrict__ cu, int n_seg, int T,
@@ -435,12 +441,12 @@ void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T,
                            (const __bf16 *)up, (__bf16 *)dup, n_vec, F);
 }
 
-void launch_attn_delta(const void *d_o, const void *o, int ldo, float *delta, int T, int nq, int d,
-                       hipStream_t s) {
-    ProfScope prof(K_ATTN_DELTA, s, 4.0 * T * nq * d);
+void launch_attn_delta(const void *d_o, const void *o, int ldo, const float *lse, float *delta,
+                       float *lse2, int T, int nq, int d, hipStream_t s) {
+    ProfScope prof(K_ATTN_DELTA, s, 4.0 * T * nq * d + 12.0 * T * nq);
     const long threads = (long)T * nq * (d / 8);
     hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
-                       (const __bf16 *)d_o, (const __bf16 *)o, ldo, delta, T, nq, d);
+                       (const __bf16 *)d_o, (const __bf16 *)o, ldo, lse, delta, lse2, T, nq, d);
 }
 
 void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out, hipStream_t s) {

@@ -56,8 +56,9 @@ void launch_rotary(void *qkv, int ld, int T, int n_heads_rot, int d, const int32
 void launch_act_fwd(int mlp, const void *up, void *act, int T, int F, hipStream_t s);
 void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T, int F,
                     hipStream_t s);
-void launch_attn_delta(const void *d_o, const void *o, int ldo, float *delta, int T, int nq, int d,
-                       hipStream_t s);
+// delta and lse2 (= lse * log2 e): [nq][T] floats each
+void launch_attn_delta(const void *d_o, const void *o, int ldo, const float *lse, float *delta,
+                       float *lse2, int T, int nq, int d, hipStream_t s);
 void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out, hipStream_t s);
 
 // ---- attention (attention.hip) ---------------------------------------------------------------
@@ -65,7 +66,7 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
                      int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale,
                      int mask, hipStream_t s);
 // part: attn_bwd_partial_bytes() bytes of fp32 scratch (unused, may be null, when nq == nkv)
-void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse,
+void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse2,
                      const float *delta, void *dq, void *dk, void *dv, float *part, int ldq, int ldkv,
                      int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
                      hipStream_t s);
