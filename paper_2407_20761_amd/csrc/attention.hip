@@ -131,12 +131,13 @@ struct TileInfo { int seg_start, seg_end, row0; };
 __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, int n_seg, int tile_rows,
                                               int *sh /* >= 8 ints */) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool scans = tid < 256;  // waves past the fourth only take part in the barriers
     if (tid == 0) sh[2] = -1;
     int base = 0;  // tiles in the segments of earlier rounds
     for (int j0 = 0; j0 < n_seg; j0 += 256) {
         const int j = j0 + tid;
         int a = 0, b = 0, nt = 0;
-        if (j < n_seg) {
+        if (scans && j < n_seg) {
             a = cu[j];
             b = cu[j + 1];
             nt = (b - a + tile_rows - 1) / tile_rows;
@@ -148,12 +149,12 @@ __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, in
             if (lane >= o) incl += up;
         }
         __syncthreads();  // sh[4..7] free (previous round consumed)
-        if (lane == 63) sh[4 + wave] = incl;
+        if (scans && lane == 63) sh[4 + wave] = incl;
         __syncthreads();
         int before = base;
-        for (int w = 0; w < wave; ++w) before += sh[4 + w];
+        for (int w = 0; w < (wave & 3); ++w) before += sh[4 + w];
         const int first = before + incl - nt;  // number of this segment's first tile
-        if (nt > 0 && (int)blockIdx.x >= first && (int)blockIdx.x < first + nt) {
+        if (scans && nt > 0 && (int)blockIdx.x >= first && (int)blockIdx.x < first + nt) {
             sh[0] = a;
             sh[1] = b;
             sh[2] = a + ((int)blockIdx.x - first) * tile_rows;
@@ -524,167 +525,111 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward, part 2: dK, dV.  A wave owns 32 key rows of one KV head and streams, for every query
-// head of the group, the segment's query rows (from the diagonal on when causal):
-//   S = Q K^T,  P = 2^(scale log2(e) S - lse2),  dV^T += dO^T P,  dP = dO V^T,  dS = P (dP - Delta),
-//   dK^T += Q^T dS.   The sum over the group's query heads happens in the accumulators.
+// backward, part 2: dK, dV.  A workgroup owns 128 key rows of one head and streams the segment's
+// 64-row query tiles (from the diagonal on when causal).  Its eight wavefronts form four pairs, one
+// pair per 32 key rows, and the two waves of a pair split the four products between them:
+//   role P (waves 0-3):  S = Q K^T,  P = 2^(scale log2(e) S - lse2),  dV^T += dO^T P
+//   role G (waves 4-7):  dP = dO V^T,  dS = P (dP - Delta),           dK^T += Q^T dS
+// P travels from the first to the second through LDS in the packed operand layout both use.  Each
+// wave keeps half of the state a single wave would need (so two fit on a SIMD and one's MFMAs hide
+// the other's element-wise work and LDS waits), and no product is computed twice.  Seen from the
+// code the two roles differ only in which operands they pick: both run "row-fragment tile x held
+// rows -> 32x32 scores", then "transposed tile x packed scores -> output".
 // ------------------------------------------------------------------------------------------------
-// probabilities and score gradients of 32 query rows (one 32x32 accumulator pair), packed as the
-// second operands of the two 16-row contraction steps that consume them
-template <bool CAUSAL, bool MASK>
-__device__ __forceinline__ void dkv_softmax_half(const f32x16 &s, const f32x16 &dp, const f32x4 (&l4)[4],
-                                                 const f32x4 (&d4)[4], int q_first, int seg_end, int kv_row,
-                                                 float sl2, bf16x8 (&pb)[2], bf16x8 (&dsb)[2]) {
-    const int lh = (threadIdx.x & 63) >> 5;
-    f32x16 p, ds;
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int r = 4 * g + e;
-            bool ok = true;
-            if (MASK) {
-                const int qr = q_first + 8 * g + 4 * lh + e;
-                ok = qr < seg_end && (!CAUSAL || kv_row <= qr);
-            }
-            p[r] = ok ? fast_exp2(s[r] * sl2 - l4[g][e]) : 0.f;
-            ds[r] = p[r] * (dp[r] - d4[g][e]);
-        }
-    pb[0] = pack8(p, 0);
-    pb[1] = pack8(p, 8);
-    dsb[0] = pack8(ds, 0);
-    dsb[1] = pack8(ds, 8);
-}
-
-// n x (1 MFMA, nv VALU, nt transcendental): the element-wise work of one half tile is spread under
-// the MFMAs of the next (a wavefront running alone on its SIMD has no other wave to hide it)
-#define OB_SCHED_MFMA_VALU(n, nv, nt)                              \
-    _Pragma("unroll") for (int i_ = 0; i_ < (n); ++i_) {           \
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         \
-        __builtin_amdgcn_sched_group_barrier(0x002, (nv), 0);      \
-        __builtin_amdgcn_sched_group_barrier(0x400, (nt), 0);      \
-    }
-
-template <int D, bool CAUSAL, bool MASK>
-__device__ __forceinline__ void dkv_tile(const unsigned char OB_LDS *__restrict__ qs,
-                                         const unsigned char OB_LDS *__restrict__ dos,
-                                         const float OB_LDS *__restrict__ lse_s,
-                                         const float OB_LDS *__restrict__ dlt_s, const Tile<D> &tq,
-                                         const Tile<D> &td, const bf16x8 (&kf)[D / 16],
-                                         const bf16x8 (&vf)[D / 16], f32x16 (&acc_dk)[D / 32],
-                                         f32x16 (&acc_dv)[D / 32], int q0, int seg_end, int kv_row,
-                                         float sl2) {
-    const int lh = (threadIdx.x & 63) >> 5;
-    constexpr int HB = D / 32;  // D-steps per batch (a batch reads HB fragments of Q and HB of dO)
-    constexpr int NB = 2 * (D / 16) / HB;
-    constexpr int PER = NB / 2;  // batches per 32-row half
-    constexpr int DT = D / 32;
-    constexpr int NV = 96 / (4 * HB), NT = 16 / (4 * HB);  // element-wise work of a half per MFMA of the next
-    static_assert(PER == 2 && DT == HB, "the phase schedule below assumes two batches per half");
-    f32x16 acc_s[2], acc_dp[2];
+// scores of a 64-row streamed tile against the 32 held rows: acc[mt] = rows 32 mt .. of the tile
+template <int D>
+__device__ __forceinline__ void dkv_scores(const unsigned char OB_LDS *__restrict__ tile, const Tile<D> &tl,
+                                           const bf16x8 (&held)[D / 16], f32x16 (&acc)[2]) {
+    constexpr int HB = D / 32, NB = 2 * (D / 16) / HB, PER = NB / 2;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_s[mt][r] = acc_dp[mt][r] = 0.f;
-    bf16x8 fq[2][HB], fd[2][HB], tq_f[2][DT], td_f[2][DT];
-    bf16x8 pb[2][2], dsb[2][2];
-    // row statistics of 32 query rows: each lane needs 4 consecutive rows per 8-row group
-    f32x4 l4[4], d4[4];
+        for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
+    bf16x8 fr[2][HB];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        l4[g] = *(const f32x4 OB_LDS *)(lse_s + 8 * g + 4 * lh);
-        d4[g] = *(const f32x4 OB_LDS *)(dlt_s + 8 * g + 4 * lh);
-    }
-#pragma unroll
-    for (int i = 0; i < HB; ++i) {
-        fq[0][i] = tq.frag_row(qs, 0, i);
-        fd[0][i] = td.frag_row(dos, 0, i);
-    }
+    for (int i = 0; i < HB; ++i) fr[0][i] = tl.frag_row(tile, 0, i);
     __builtin_amdgcn_sched_barrier(0);
-    // phase A: S and dP of query rows 0..31
 #pragma unroll
-    for (int b = 0; b < PER; ++b) {
-#pragma unroll
-        for (int i = 0; i < HB; ++i) {
-            fq[(b + 1) & 1][i] = tq.frag_row(qs, (b + 1) / PER, ((b + 1) % PER) * HB + i);
-            fd[(b + 1) & 1][i] = td.frag_row(dos, (b + 1) / PER, ((b + 1) % PER) * HB + i);
-        }
-#pragma unroll
-        for (int i = 0; i < HB; ++i) {
-            acc_s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[b & 1][i], kf[b * HB + i], acc_s[0], 0, 0, 0);
-            acc_dp[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[b & 1][i], vf[b * HB + i], acc_dp[0], 0, 0, 0);
-        }
-        OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB);
-    }
-    // phase B: S and dP of rows 32..63, with the element-wise work of rows 0..31 underneath
-#pragma unroll
-    for (int b = PER; b < NB; ++b) {
+    for (int b = 0; b < NB; ++b) {
         if (b + 1 < NB) {
 #pragma unroll
-            for (int i = 0; i < HB; ++i) {
-                fq[(b + 1) & 1][i] = tq.frag_row(qs, 1, ((b + 1) % PER) * HB + i);
-                fd[(b + 1) & 1][i] = td.frag_row(dos, 1, ((b + 1) % PER) * HB + i);
-            }
-        } else {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                td_f[0][dt] = td.frag_tr(dos, dt, 0);
-                tq_f[0][dt] = tq.frag_tr(qs, dt, 0);
-            }
+            for (int i = 0; i < HB; ++i)
+                fr[(b + 1) & 1][i] = tl.frag_row(tile, (b + 1) / PER, ((b + 1) % PER) * HB + i);
         }
 #pragma unroll
-        for (int i = 0; i < HB; ++i) {
-            acc_s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fq[b & 1][i], kf[(b % PER) * HB + i], acc_s[1], 0, 0, 0);
-            acc_dp[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fd[b & 1][i], vf[(b % PER) * HB + i], acc_dp[1], 0, 0, 0);
-        }
+        for (int i = 0; i < HB; ++i)
+            acc[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[b & 1][i], held[(b % PER) * HB + i], acc[b / PER], 0, 0, 0);
+        if (b + 1 < NB) OB_SCHED_READS_THEN_MFMA(HB, HB); else OB_SCHED_READS_THEN_MFMA(0, HB);
     }
-    dkv_softmax_half<CAUSAL, MASK>(acc_s[0], acc_dp[0], l4, d4, q0, seg_end, kv_row, sl2, pb[0], dsb[0]);
-    __builtin_amdgcn_sched_group_barrier(0x100, 2 * HB, 0);
-    OB_SCHED_MFMA_VALU(2 * HB, NV, NT)
-    __builtin_amdgcn_sched_group_barrier(0x100, 4 * DT, 0);
-    OB_SCHED_MFMA_VALU(2 * HB, NV, NT)
+}
+
+// role P: probabilities of the 64 x 32 score tile, packed as the second operands of the four
+// 16-row contraction steps (pk[mt][h] serves step 2 mt + h)
+template <bool CAUSAL, bool MASK>
+__device__ __forceinline__ void dkv_probs(const f32x16 (&s)[2], const float OB_LDS *__restrict__ lse2_s,
+                                          int q0, int seg_end, int kv_row, float sl2, bf16x8 (&pk)[2][2]) {
+    const int lh = (threadIdx.x & 63) >> 5;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        f32x16 p;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 l4 = *(const f32x4 OB_LDS *)(lse2_s + mt * 32 + 8 * g + 4 * lh);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                bool ok = true;
+                if (MASK) {
+                    const int qr = q0 + mt * 32 + 8 * g + 4 * lh + e;
+                    ok = qr < seg_end && (!CAUSAL || kv_row <= qr);
+                }
+                p[4 * g + e] = ok ? fast_exp2(s[mt][4 * g + e] * sl2 - l4[e]) : 0.f;
+            }
+        }
+        pk[mt][0] = pack8(p, 0);
+        pk[mt][1] = pack8(p, 8);
+    }
+}
+
+// role G: dS = P (dP - Delta), in place of the packed probabilities
+__device__ __forceinline__ void dkv_dscores(const f32x16 (&dp)[2], const float OB_LDS *__restrict__ dlt_s,
+                                            bf16x8 (&pk)[2][2]) {
+    const int lh = (threadIdx.x & 63) >> 5;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        f32x16 ds;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 d4 = *(const f32x4 OB_LDS *)(dlt_s + mt * 32 + 8 * g + 4 * lh);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int r = 4 * g + e;
+                ds[r] = (float)pk[mt][r >> 3][r & 7] * (dp[mt][r] - d4[e]);
+            }
+        }
+        pk[mt][0] = pack8(ds, 0);
+        pk[mt][1] = pack8(ds, 8);
+    }
+}
+
+// out^T += tile^T x packed scores, contracting over the tile's 64 rows
+template <int D>
+__device__ __forceinline__ void dkv_outputs(const unsigned char OB_LDS *__restrict__ tile, const Tile<D> &tl,
+                                            const bf16x8 (&pk)[2][2], f32x16 (&acc_out)[D / 32]) {
+    constexpr int DT = D / 32;
+    bf16x8 tf[2][DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) tf[0][dt] = tl.frag_tr(tile, dt, 0);
     __builtin_amdgcn_sched_barrier(0);
-    // phase C: dV and dK from rows 0..31, with the element-wise work of rows 32..63 underneath
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        l4[g] = *(const f32x4 OB_LDS *)(lse_s + 32 + 8 * g + 4 * lh);
-        d4[g] = *(const f32x4 OB_LDS *)(dlt_s + 32 + 8 * g + 4 * lh);
-    }
+    for (int u = 0; u < ST / 16; ++u) {
+        if (u + 1 < ST / 16) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            td_f[(u + 1) & 1][dt] = td.frag_tr(dos, dt, u + 1);
-            tq_f[(u + 1) & 1][dt] = tq.frag_tr(qs, dt, u + 1);
+            for (int dt = 0; dt < DT; ++dt) tf[(u + 1) & 1][dt] = tl.frag_tr(tile, dt, u + 1);
         }
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            acc_dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td_f[u & 1][dt], pb[0][u], acc_dv[dt], 0, 0, 0);
-            acc_dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq_f[u & 1][dt], dsb[0][u], acc_dk[dt], 0, 0, 0);
-        }
-    }
-    dkv_softmax_half<CAUSAL, MASK>(acc_s[1], acc_dp[1], l4, d4, q0 + 32, seg_end, kv_row, sl2, pb[1], dsb[1]);
-    __builtin_amdgcn_sched_group_barrier(0x100, 8 + 4 * DT, 0);
-    OB_SCHED_MFMA_VALU(2 * DT, NV, NT)
-    __builtin_amdgcn_sched_group_barrier(0x100, 4 * DT, 0);
-    OB_SCHED_MFMA_VALU(2 * DT, NV, NT)
-    __builtin_amdgcn_sched_barrier(0);
-    // phase D: dV and dK from rows 32..63
-#pragma unroll
-    for (int u = 2; u < 4; ++u) {
-        if (u + 1 < 4) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                td_f[(u + 1) & 1][dt] = td.frag_tr(dos, dt, u + 1);
-                tq_f[(u + 1) & 1][dt] = tq.frag_tr(qs, dt, u + 1);
-            }
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            acc_dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(td_f[u & 1][dt], pb[1][u - 2], acc_dv[dt], 0, 0, 0);
-            acc_dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq_f[u & 1][dt], dsb[1][u - 2], acc_dk[dt], 0, 0, 0);
-        }
-        if (u + 1 < 4) OB_SCHED_READS_THEN_MFMA(4 * DT, 2 * DT); else OB_SCHED_READS_THEN_MFMA(0, 2 * DT);
+        for (int dt = 0; dt < DT; ++dt)
+            acc_out[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf[u & 1][dt], pk[u >> 1][u & 1], acc_out[dt], 0, 0, 0);
+        if (u + 1 < ST / 16) OB_SCHED_READS_THEN_MFMA(2 * DT, DT); else OB_SCHED_READS_THEN_MFMA(0, DT);
     }
 }
 
@@ -701,7 +646,7 @@ __device__ __forceinline__ void issue_row_stats(const float *base, long floats_l
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
+__global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, float *__restrict__ part_dk,
@@ -711,6 +656,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     __shared__ __attribute__((aligned(1024))) unsigned char do_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char q_s1[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char do_s1[Tile<D>::BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char p_s[4 * 4096];  // per pair: 4 x 64 lanes x 16 B
     __shared__ __attribute__((aligned(256))) float lse_s0[ST];
     __shared__ __attribute__((aligned(256))) float dlt_s0[ST];
     __shared__ __attribute__((aligned(256))) float lse_s1[ST];
@@ -721,70 +667,85 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
     const int head = blockIdx.y, kvh = head / group;
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int kv_row = min(ti.row0 + wave * 32 + lx, ti.seg_end - 1);
-    const bool kv_live = ti.row0 + wave * 32 + lx < ti.seg_end;
-    const int wave_kv_first = ti.row0 + wave * 32;
+    const int pair = wave & 3;
+    const bool role_g = wave >= 4;  // false: S, P, dV;  true: dP, dS, dK
+    const int kv_row = min(ti.row0 + pair * 32 + lx, ti.seg_end - 1);
+    const bool kv_live = ti.row0 + pair * 32 + lx < ti.seg_end;
+    const int pair_kv_first = ti.row0 + pair * 32;
     const float sl2 = scale * LOG2E;
+    constexpr int KT = D / 16, DT = D / 32;
 
-    // q and d_o may have different row strides: two addressing sets
-    Tile<D> tq, td;
-    tq.init(ldq, wave, lane);
-    td.init(ldo, wave, lane);
+    // the wave copies the tile it reads row fragments from: Q (role P) or dO (role G)
+    Tile<D> tl;
+    tl.init(role_g ? ldo : ldq, pair, lane);
+    const unsigned char *const own_base = role_g ? (const unsigned char *)d_o : (const unsigned char *)q;
+    const long own_ld2 = (role_g ? (long)ldo : (long)ldq) * 2;
+    const long own_total = (long)T * own_ld2;
 
-    bf16x8 kf[D / 16], vf[D / 16];
+    // held rows: K (role P) or V (role G)
+    bf16x8 kvf[KT];
+    {
+        const __bf16 *src = (role_g ? v : k) + (size_t)kv_row * ldkv + kvh * D + 8 * lh;
 #pragma unroll
-    for (int t = 0; t < D / 16; ++t) {
-        kf[t] = *(const bf16x8 *)(k + (size_t)kv_row * ldkv + kvh * D + 16 * t + 8 * lh);
-        vf[t] = *(const bf16x8 *)(v + (size_t)kv_row * ldkv + kvh * D + 16 * t + 8 * lh);
+        for (int t = 0; t < KT; ++t) kvf[t] = *(const bf16x8 *)(src + 16 * t);
     }
-    f32x16 acc_dk[D / 32], acc_dv[D / 32];
+    f32x16 acc_out[DT];  // dV^T (role P) or dK^T (role G)
 #pragma unroll
-    for (int i = 0; i < D / 32; ++i)
+    for (int i = 0; i < DT; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_dk[i][r] = acc_dv[i][r] = 0.f;
+        for (int r = 0; r < 16; ++r) acc_out[i][r] = 0.f;
 
     unsigned char OB_LDS *const qs0 = (unsigned char OB_LDS *)q_s0, *const qs1 = (unsigned char OB_LDS *)q_s1;
     unsigned char OB_LDS *const dos0 = (unsigned char OB_LDS *)do_s0, *const dos1 = (unsigned char OB_LDS *)do_s1;
     float OB_LDS *const lses0 = (float OB_LDS *)lse_s0, *const lses1 = (float OB_LDS *)lse_s1;
     float OB_LDS *const dlts0 = (float OB_LDS *)dlt_s0, *const dlts1 = (float OB_LDS *)dlt_s1;
+    unsigned char OB_LDS *const p_mine = (unsigned char OB_LDS *)p_s + pair * 4096 + lane * 16;
 
     // causal: query rows before this workgroup's first key row see none of its keys
     const int q_begin = CAUSAL ? ti.seg_start + ((ti.row0 - ti.seg_start) / ST) * ST : ti.seg_start;
     const int n_iter = (ti.seg_end - q_begin + ST - 1) / ST;
-    const long q_total = (long)T * ldq * 2, do_total = (long)T * ldo * 2;
-#define OB_ISSUE_DKV(it, stage)                                                                          \
-    do {                                                                                                 \
-        const int hd_ = head;                                                                            \
-        const int q0_ = q_begin + (it) * ST;                                                             \
-        const long qo_ = (long)q0_ * ldq * 2 + (long)hd_ * D * 2;                                        \
-        const long do_ = (long)q0_ * ldo * 2 + (long)hd_ * D * 2;                                        \
-        tq.issue((const unsigned char *)q + qo_, q_total - qo_, qs##stage, wave);                        \
-        td.issue((const unsigned char *)d_o + do_, do_total - do_, dos##stage, wave);                    \
-        if (wave == 0) issue_row_stats(lse2_all + (size_t)hd_ * T + q0_, (long)T - q0_, lses##stage, lane);   \
-        if (wave == 1) issue_row_stats(delta + (size_t)hd_ * T + q0_, (long)T - q0_, dlts##stage, lane); \
+#define OB_ISSUE_DKV(it_, stage_)                                                                             \
+    do {                                                                                                      \
+        const int q0_ = q_begin + (it_) * ST;                                                                 \
+        const long off_ = (long)q0_ * own_ld2 + (long)head * D * 2;                                           \
+        tl.issue(own_base + off_, own_total - off_, role_g ? dos##stage_ : qs##stage_, pair);                 \
+        if (wave == 0) issue_row_stats(lse2_all + (size_t)head * T + q0_, (long)T - q0_, lses##stage_, lane); \
+        if (wave == 4) issue_row_stats(delta + (size_t)head * T + q0_, (long)T - q0_, dlts##stage_, lane);    \
     } while (0)
     OB_ISSUE_DKV(0, 0);
-    // causal: only the first two query tiles touch some wave's diagonal; either way only the last
+    // causal: only the first two query tiles touch some pair's diagonal; either way only the last
     // tile can be ragged.  The tiles in between run mask-free in a single-path loop.
     const int n_head = CAUSAL ? min(2, n_iter) : 0;
     const int n_mid_end = max(n_head, n_iter - (((ti.seg_end - q_begin) % ST) ? 1 : 0));
     int it = 0;
-#define OB_DKV_ITER(MASKED)                                                                                \
-    {                                                                                                      \
-        const int q0 = q_begin + it * ST;                                                                  \
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                              \
-        __syncthreads();                                                                                   \
-        if (it + 1 < n_iter) {                                                                             \
-            if (it & 1) OB_ISSUE_DKV(it + 1, 0); else OB_ISSUE_DKV(it + 1, 1);                             \
-        }                                                                                                  \
-        const unsigned char OB_LDS *const qs = (it & 1) ? qs1 : qs0, *const dos = (it & 1) ? dos1 : dos0;  \
-        const float OB_LDS *const lses = (it & 1) ? lses1 : lses0, *const dlts = (it & 1) ? dlts1 : dlts0; \
-        if (!(MASKED))                                                                                     \
-            dkv_tile<D, CAUSAL, false>(qs, dos, lses, dlts, tq, td, kf, vf, acc_dk, acc_dv, q0, ti.seg_end, \
-                                       kv_row, sl2);                                                       \
-        else if (!(CAUSAL && q0 + ST - 1 < wave_kv_first)) /* tile entirely before this wave's keys */     \
-            dkv_tile<D, CAUSAL, true>(qs, dos, lses, dlts, tq, td, kf, vf, acc_dk, acc_dv, q0, ti.seg_end,  \
-                                      kv_row, sl2);                                                        \
+#define OB_DKV_ITER(MASKED)                                                                                  \
+    {                                                                                                        \
+        const int q0 = q_begin + it * ST;                                                                    \
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                                \
+        __syncthreads();                                                                                     \
+        if (it + 1 < n_iter) {                                                                               \
+            if (it & 1) OB_ISSUE_DKV(it + 1, 0); else OB_ISSUE_DKV(it + 1, 1);                               \
+        }                                                                                                    \
+        const unsigned char OB_LDS *const qs = (it & 1) ? qs1 : qs0, *const dos = (it & 1) ? dos1 : dos0;    \
+        const unsigned char OB_LDS *const row_tile = role_g ? dos : qs, *const tr_tile = role_g ? qs : dos;  \
+        const float OB_LDS *const stat = role_g ? ((it & 1) ? dlts1 : dlts0) : ((it & 1) ? lses1 : lses0);   \
+        /* a masked tile entirely before this pair's keys contributes nothing (but keeps the barriers) */    \
+        const bool live = !((MASKED) && CAUSAL && q0 + ST - 1 < pair_kv_first);                              \
+        f32x16 acc_x[2];                                                                                     \
+        bf16x8 pk[2][2];                                                                                     \
+        if (live) dkv_scores<D>(row_tile, tl, kvf, acc_x);                                                   \
+        if (live && !role_g) {                                                                               \
+            dkv_probs<CAUSAL, MASKED>(acc_x, stat, q0, ti.seg_end, kv_row, sl2, pk);                         \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                 \
+                *(bf16x8 OB_LDS *)(p_mine + i_ * 1024) = pk[i_ >> 1][i_ & 1];                                \
+        }                                                                                                    \
+        __syncthreads();                                                                                     \
+        if (live && role_g) {                                                                                \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                 \
+                pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + i_ * 1024);                          \
+            dkv_dscores(acc_x, stat, pk);                                                                    \
+        }                                                                                                    \
+        if (live) dkv_outputs<D>(tr_tile, tl, pk, acc_out);                                                  \
     }
     for (; it < n_head; ++it) OB_DKV_ITER(true)
     for (; it < n_mid_end; ++it) OB_DKV_ITER(false)
@@ -792,37 +753,30 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(
 #undef OB_DKV_ITER
 #undef OB_ISSUE_DKV
     if (!kv_live) return;
+    const float out_scale = role_g ? scale : 1.0f;
     if (group == 1) {
+        __bf16 *const dst = role_g ? dk : dv;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                bf16x4 ok_, ov_;
+                bf16x4 ov;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    ok_[e] = (__bf16)(acc_dk[dt][4 * g + e] * scale);
-                    ov_[e] = (__bf16)acc_dv[dt][4 * g + e];
-                }
-                const size_t off = (size_t)kv_row * ldkv + kvh * D + dt * 32 + g * 8 + lh * 4;
-                *(bf16x4 *)(dk + off) = ok_;
-                *(bf16x4 *)(dv + off) = ov_;
+                for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc_out[dt][4 * g + e] * out_scale);
+                *(bf16x4 *)(dst + (size_t)kv_row * ldkv + kvh * D + dt * 32 + g * 8 + lh * 4) = ov;
             }
     } else {
         // one fp32 partial per query head of the group, summed in fixed order by the reduce kernel
+        float *const dst = role_g ? part_dk : part_dv;
         const size_t pbase = ((size_t)(head % group) * T + kv_row) * ((size_t)nkv * D) + (size_t)kvh * D;
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                f32x4 pk, pv;
+                f32x4 pv;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    pk[e] = acc_dk[dt][4 * g + e] * scale;
-                    pv[e] = acc_dv[dt][4 * g + e];
-                }
-                const size_t off = pbase + dt * 32 + g * 8 + lh * 4;
-                *(f32x4 *)(part_dk + off) = pk;
-                *(f32x4 *)(part_dv + off) = pv;
+                for (int e = 0; e < 4; ++e) pv[e] = acc_out[dt][4 * g + e] * out_scale;
+                *(f32x4 *)(dst + pbase + dt * 32 + g * 8 + lh * 4) = pv;
             }
     }
 }
@@ -889,16 +843,16 @@ OB_ATTN_INSTANCES(128, false)
 
 }  // namespace
 
-#define OB_ATTN_DISPATCH(KERNEL, GRID, ...)                                                        \
+#define OB_ATTN_DISPATCH(KERNEL, GRID, THREADS, ...)                                                      \
     do {                                                                                           \
         if (d == 64 && causal)                                                                     \
-            hipLaunchKernelGGL((KERNEL<64, true>), GRID, dim3(256), 0, s, __VA_ARGS__);            \
+            hipLaunchKernelGGL((KERNEL<64, true>), GRID, dim3(THREADS), 0, s, __VA_ARGS__);            \
         else if (d == 64)                                                                          \
-            hipLaunchKernelGGL((KERNEL<64, false>), GRID, dim3(256), 0, s, __VA_ARGS__);           \
+            hipLaunchKernelGGL((KERNEL<64, false>), GRID, dim3(THREADS), 0, s, __VA_ARGS__);           \
         else if (causal)                                                                           \
-            hipLaunchKernelGGL((KERNEL<128, true>), GRID, dim3(256), 0, s, __VA_ARGS__);           \
+            hipLaunchKernelGGL((KERNEL<128, true>), GRID, dim3(THREADS), 0, s, __VA_ARGS__);           \
         else                                                                                       \
-            hipLaunchKernelGGL((KERNEL<128, false>), GRID, dim3(256), 0, s, __VA_ARGS__);          \
+            hipLaunchKernelGGL((KERNEL<128, false>), GRID, dim3(THREADS), 0, s, __VA_ARGS__);          \
     } while (0)
 
 void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int ldq,
@@ -907,7 +861,7 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
     const bool causal = mask == OB_MASK_SEG_CAUSAL;
     ProfScope prof(K_ATTN_FWD, s, attn_flops(seg, nq, d, causal));
     const dim3 grid(count_tiles(seg, QT), nq);
-    OB_ATTN_DISPATCH(attn_fwd_kernel, grid, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
+    OB_ATTN_DISPATCH(attn_fwd_kernel, grid, 256, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
                      (__bf16 *)o, lse, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, seg->total_tokens,
                      nq / nkv, scale);
 }
@@ -923,12 +877,12 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     float *part_dk = part, *part_dv = part ? part + (size_t)group * T * nkv * d : nullptr;
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
-        OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, (const __bf16 *)d_o, (const __bf16 *)q,
+        OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 256, (const __bf16 *)d_o, (const __bf16 *)q,
                          (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
                          seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
     }
     ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
-    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_q, (const __bf16 *)d_o, (const __bf16 *)q,
+    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_q, 512, (const __bf16 *)d_o, (const __bf16 *)q,
                      (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dk, (__bf16 *)dv, part_dk,
                      part_dv, nkv, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, T, group, scale);
     if (group > 1) {
