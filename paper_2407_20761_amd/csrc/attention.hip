@@ -221,6 +221,7 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
         else if (b + AHEAD == NB) OB_SCHED_READS_THEN_MFMA(2 * DT, HB);
         else OB_SCHED_READS_THEN_MFMA(0, HB);
     }
+    // the running maximum is kept on the raw scores; the softmax scale rides in the exponent's FMA
     float mx = NEG_BIG;
     if (MASK) {
 #pragma unroll
@@ -229,7 +230,7 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
             for (int r = 0; r < 16; ++r) {
                 const int kv = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                 const bool ok = kv < seg_end && (!CAUSAL || kv <= q_row);
-                const float s = ok ? acc_s[mt][r] * sl2 : NEG_BIG;
+                const float s = ok ? acc_s[mt][r] : NEG_BIG;
                 acc_s[mt][r] = s;
                 mx = fmaxf(mx, s);
             }
@@ -237,26 +238,23 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float s = acc_s[mt][r] * sl2;
-                acc_s[mt][r] = s;
-                mx = fmaxf(mx, s);
-            }
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[mt][r]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     const float m_new = fmaxf(m_run, mx);
+    const float c = m_new * sl2;
     float psum = 0.f;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(acc_s[mt][r] - m_new);
+            const float p = fast_exp2(acc_s[mt][r] * sl2 - c);
             acc_s[mt][r] = p;
             psum += p;
         }
     // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
     if (__any(m_new > m_run)) {
-        const float alpha = fast_exp2(m_run - m_new);
+        const float alpha = fast_exp2((m_run - m_new) * sl2);
         l_run *= alpha;
 #pragma unroll
         for (int i = 0; i < D / 32; ++i)
@@ -330,24 +328,34 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     // iteration the register allocator shuffles the accumulators between homes every iteration).
     const int n_main = CAUSAL ? (ti.row0 - ti.seg_start) / ST : (ti.seg_end - ti.seg_start) / ST;
     int j = 0;
-#define OB_FWD_ITER(MASKED)                                                                              \
+#define OB_FWD_ITER(MASKED, KS, VS, KS_NEXT, VS_NEXT)                                                     \
     {                                                                                                    \
         const int kv0 = ti.seg_start + j * ST;                                                           \
         __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                            \
         __syncthreads();                                                                                 \
         if (j + 1 < n_tiles) {                                                                           \
             const long off = (long)(kv0 + ST) * ldkv * 2;                                                \
-            tl.issue(kbase + off, kv_bytes - off, (j & 1) ? ks0 : ks1, wave);                            \
-            tl.issue(vbase + off, kv_bytes - off, (j & 1) ? vs0 : vs1, wave);                            \
+            tl.issue(kbase + off, kv_bytes - off, (KS_NEXT), wave);                                      \
+            tl.issue(vbase + off, kv_bytes - off, (VS_NEXT), wave);                                      \
         }                                                                                                \
-        const unsigned char OB_LDS *const ks = (j & 1) ? ks1 : ks0, *const vs = (j & 1) ? vs1 : vs0;     \
         if (!(MASKED))                                                                                   \
-            fwd_tile<D, CAUSAL, false>(ks, vs, tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row, sl2); \
+            fwd_tile<D, CAUSAL, false>((KS), (VS), tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row,  \
+                                       sl2);                                                             \
         else if (!(CAUSAL && kv0 > wave_q_last))                                                         \
-            fwd_tile<D, CAUSAL, true>(ks, vs, tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row, sl2); \
+            fwd_tile<D, CAUSAL, true>((KS), (VS), tl, qf, acc_o, m_run, l_run, kv0, ti.seg_end, q_row,   \
+                                      sl2);                                                              \
+        ++j;                                                                                             \
     }
-    for (; j < n_main; ++j) OB_FWD_ITER(false)
-    for (; j < n_tiles; ++j) OB_FWD_ITER(true)
+    // two tiles per trip: the stage buffers are then compile-time constants and every LDS address is
+    // a register plus an immediate offset
+    while (j + 1 < n_main) {
+        OB_FWD_ITER(false, ks0, vs0, ks1, vs1)
+        OB_FWD_ITER(false, ks1, vs1, ks0, vs0)
+    }
+#define OB_FWD_ANY(MASKED) OB_FWD_ITER(MASKED, (j & 1) ? ks1 : ks0, (j & 1) ? vs1 : vs0, (j & 1) ? ks0 : ks1, (j & 1) ? vs0 : vs1)
+    while (j < n_main) OB_FWD_ANY(false)
+    while (j < n_tiles) OB_FWD_ANY(true)
+#undef OB_FWD_ANY
 #undef OB_FWD_ITER
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     if (!q_live) return;
@@ -361,112 +369,110 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
             for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc_o[dt][4 * g + e] * inv);
             *(bf16x4 *)(o + (size_t)q_row * ldo + head * D + dt * 32 + g * 8 + lh * 4) = ov;
         }
-    if (lh == 0) lse[(size_t)head * T + q_row] = (m_run + __builtin_amdgcn_logf(l_tot)) * LN2;
+    if (lh == 0) lse[(size_t)head * T + q_row] = (m_run * sl2 + __builtin_amdgcn_logf(l_tot)) * LN2;
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward, part 1: dQ.  Same ownership as the forward; P is rebuilt from the saved log-sum-exp.
-//   S^T = K Q^T,  P = exp(scale S - lse),  dP^T = V dO^T,  dS^T = P (dP^T - Delta),  dQ^T += K^T dS^T
+// backward, part 1: dQ.  A workgroup owns 128 query rows of one head and streams the segment's
+// 64-row key/value tiles (up to the diagonal when causal); P is rebuilt from the saved
+// log-sum-exp.  Eight wavefronts form four pairs, one pair per 32 query rows; the two waves of a
+// pair each take one 32-row half of every streamed tile through all three products
+//   S^T = K Q^T,  P = 2^(scale log2(e) S - lse2),  dP^T = V dO^T,  dS^T = P (dP^T - Delta),
+//   dQ^T += K^T dS^T
+// and keep their own dQ partial, which the pair adds once at the end through LDS.  Half the
+// per-wave state of a single-wave design, so two waves fit on a SIMD and hide each other's
+// element-wise work and LDS waits.
 // ------------------------------------------------------------------------------------------------
 template <int D, bool CAUSAL, bool MASK>
-__device__ __forceinline__ void dq_tile(const unsigned char OB_LDS *__restrict__ ks,
+__device__ __forceinline__ void dq_half(const unsigned char OB_LDS *__restrict__ ks,
                                         const unsigned char OB_LDS *__restrict__ vs, const Tile<D> &tl,
                                         const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16],
-                                        f32x16 (&acc_dq)[D / 32], float lse2, float dlt, int kv0, int seg_end,
-                                        int q_row, float sl2) {
+                                        f32x16 (&acc_dq)[D / 32], float lse2, float dlt, int kv_first,
+                                        int seg_end, int q_row, float sl2) {
+    // ks / vs point at this wave's 32-row half of the K / V tile; kv_first is its first key row
     const int lh = (threadIdx.x & 63) >> 5;
-    constexpr int HB = D == 128 ? 1 : 2;  // D-steps per batch (a batch reads HB fragments of K and HB of V)
-    constexpr int R = D == 128 ? 4 : 2;   // batches in flight (ring depth)
-    constexpr int PER = (D / 16) / HB;    // batches per 32-row tile
-    constexpr int NB = 2 * PER;
+    constexpr int HB = 2;             // D-steps per batch (a batch reads HB fragments of K and HB of V)
+    constexpr int NB = (D / 16) / HB;
     constexpr int DT = D / 32;
-    f32x16 acc_s[2], acc_dp[2];
+    f32x16 acc_s, acc_dp;
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int r = 0; r < 16; ++r) acc_s[r] = acc_dp[r] = 0.f;
+    bf16x8 fk[2][HB], fv[2][HB], fb[2][DT];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc_s[mt][r] = acc_dp[mt][r] = 0.f;
-    bf16x8 fk[R][HB], fv[R][HB], fb[2][DT];
+    for (int i = 0; i < HB; ++i) {
+        fk[0][i] = tl.frag_row(ks, 0, i);
+        fv[0][i] = tl.frag_row(vs, 0, i);
+    }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int b = 0; b < R - 1; ++b)
-#pragma unroll
-        for (int i = 0; i < HB; ++i) {
-            fk[b][i] = tl.frag_row(ks, b / PER, (b % PER) * HB + i);
-            fv[b][i] = tl.frag_row(vs, b / PER, (b % PER) * HB + i);
-        }
-#pragma unroll
-    for (int b = 0; b < NB; ++b) {  // batch b: row tile b / PER, D-steps (b % PER) HB ..
-        constexpr int AHEAD = R - 1;
-        if (b + AHEAD < NB) {
+    for (int b = 0; b < NB; ++b) {
+        if (b + 1 < NB) {
 #pragma unroll
             for (int i = 0; i < HB; ++i) {
-                fk[(b + AHEAD) % R][i] = tl.frag_row(ks, (b + AHEAD) / PER, ((b + AHEAD) % PER) * HB + i);
-                fv[(b + AHEAD) % R][i] = tl.frag_row(vs, (b + AHEAD) / PER, ((b + AHEAD) % PER) * HB + i);
+                fk[(b + 1) & 1][i] = tl.frag_row(ks, 0, (b + 1) * HB + i);
+                fv[(b + 1) & 1][i] = tl.frag_row(vs, 0, (b + 1) * HB + i);
             }
-        } else if (b + AHEAD == NB) {
+        } else {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) fb[0][dt] = tl.frag_tr(ks, dt, 0);
         }
 #pragma unroll
         for (int i = 0; i < HB; ++i) {
-            acc_s[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[b % R][i], qf[(b % PER) * HB + i], acc_s[b / PER], 0, 0, 0);
-            acc_dp[b / PER] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[b % R][i], dof[(b % PER) * HB + i], acc_dp[b / PER], 0, 0, 0);
+            acc_s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fk[b & 1][i], qf[b * HB + i], acc_s, 0, 0, 0);
+            acc_dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fv[b & 1][i], dof[b * HB + i], acc_dp, 0, 0, 0);
         }
-        if (b + AHEAD < NB) OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB);
-        else if (b + AHEAD == NB) OB_SCHED_READS_THEN_MFMA(2 * DT, 2 * HB);
-        else OB_SCHED_READS_THEN_MFMA(0, 2 * HB);
+        if (b + 1 < NB) OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB); else OB_SCHED_READS_THEN_MFMA(2 * DT, 2 * HB);
     }
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            bool ok = true;
-            if (MASK) {
-                const int kv = kv0 + mt * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                ok = kv < seg_end && (!CAUSAL || kv <= q_row);
-            }
-            const float p = ok ? fast_exp2(acc_s[mt][r] * sl2 - lse2) : 0.f;
-            acc_s[mt][r] = p * (acc_dp[mt][r] - dlt);
+    for (int r = 0; r < 16; ++r) {
+        bool ok = true;
+        if (MASK) {
+            const int kv = kv_first + 8 * (r >> 2) + 4 * lh + (r & 3);
+            ok = kv < seg_end && (!CAUSAL || kv <= q_row);
         }
+        const float p = ok ? fast_exp2(acc_s[r] * sl2 - lse2) : 0.f;
+        acc_s[r] = p * (acc_dp[r] - dlt);
+    }
 #pragma unroll
-    for (int u = 0; u < ST / 16; ++u) {
-        if (u + 1 < ST / 16) {
+    for (int h = 0; h < 2; ++h) {
+        if (h == 0) {
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) fb[(u + 1) & 1][dt] = tl.frag_tr(ks, dt, u + 1);
+            for (int dt = 0; dt < DT; ++dt) fb[1][dt] = tl.frag_tr(ks, dt, 1);
         }
-        const bf16x8 dsb = pack8(acc_s[u >> 1], 8 * (u & 1));
+        const bf16x8 dsb = pack8(acc_s, 8 * h);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-            acc_dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u & 1][dt], dsb, acc_dq[dt], 0, 0, 0);
-        if (u + 1 < ST / 16) OB_SCHED_READS_THEN_MFMA(2 * DT, DT); else OB_SCHED_READS_THEN_MFMA(0, DT);
+            acc_dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[h][dt], dsb, acc_dq[dt], 0, 0, 0);
+        if (h == 0) OB_SCHED_READS_THEN_MFMA(2 * DT, DT); else OB_SCHED_READS_THEN_MFMA(0, DT);
     }
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(512) void attn_bwd_dq_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo, const int32_t *__restrict__ cu, int n_seg,
     int T, int group, float scale) {
-    __shared__ __attribute__((aligned(1024))) unsigned char k_s0[Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char v_s0[Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char k_s1[Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char v_s1[Tile<D>::BYTES];
+    // stages 0 / 1 of the K and V tiles; after the last tile the same bytes carry the dQ partials
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * Tile<D>::BYTES];
     __shared__ int sh[8];
     const TileInfo ti = find_tile(cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
     const int head = blockIdx.y, kvh = head / group;
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int q_row = min(ti.row0 + wave * 32 + lx, ti.seg_end - 1);
-    const bool q_live = ti.row0 + wave * 32 + lx < ti.seg_end;
-    const int wave_q_last = min(ti.row0 + wave * 32 + 31, ti.seg_end - 1);
+    const int pair = wave & 3, half = wave >> 2;
+    const int q_row = min(ti.row0 + pair * 32 + lx, ti.seg_end - 1);
+    const bool q_live = ti.row0 + pair * 32 + lx < ti.seg_end;
+    const int pair_q_last = min(ti.row0 + pair * 32 + 31, ti.seg_end - 1);
     const float sl2 = scale * LOG2E;
+    constexpr int BYTES = Tile<D>::BYTES, DT = D / 32;
 
+    // waves 0-3 copy the K tiles, waves 4-7 the V tiles
     Tile<D> tl;
-    tl.init(ldkv, wave, lane);
-    const unsigned char *kbase = (const unsigned char *)(k + kvh * D);
-    const unsigned char *vbase = (const unsigned char *)(v + kvh * D);
-    const long kv_bytes = (long)T * ldkv * 2 - (long)kvh * D * 2;
+    tl.init(ldkv, pair, lane);
+    const unsigned char *const own_base = (const unsigned char *)((half ? v : k) + kvh * D);
+    const long own_bytes = (long)T * ldkv * 2 - (long)kvh * D * 2;
 
     bf16x8 qf[D / 16], dof[D / 16];
 #pragma unroll
@@ -476,50 +482,72 @@ __global__ __launch_bounds__(256, D == 128 ? 1 : 2) void attn_bwd_dq_kernel(
     }
     const float lse2 = lse2_all[(size_t)head * T + q_row];
     const float dlt = delta[(size_t)head * T + q_row];
-    f32x16 acc_dq[D / 32];
+    f32x16 acc_dq[DT];
 #pragma unroll
-    for (int i = 0; i < D / 32; ++i)
+    for (int i = 0; i < DT; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_dq[i][r] = 0.f;
 
     const int kv_end = CAUSAL ? min(ti.seg_end, ti.row0 + QT) : ti.seg_end;
     const int n_tiles = (kv_end - ti.seg_start + ST - 1) / ST;
-    unsigned char OB_LDS *const ks0 = (unsigned char OB_LDS *)k_s0, *const ks1 = (unsigned char OB_LDS *)k_s1;
-    unsigned char OB_LDS *const vs0 = (unsigned char OB_LDS *)v_s0, *const vs1 = (unsigned char OB_LDS *)v_s1;
+    unsigned char OB_LDS *const sm = (unsigned char OB_LDS *)smem;  // [stage][K | V][BYTES]
     {
         const long off = (long)ti.seg_start * ldkv * 2;
-        tl.issue(kbase + off, kv_bytes - off, ks0, wave);
-        tl.issue(vbase + off, kv_bytes - off, vs0, wave);
+        tl.issue(own_base + off, own_bytes - off, sm + half * BYTES, pair);
     }
     const int n_main = CAUSAL ? (ti.row0 - ti.seg_start) / ST : (ti.seg_end - ti.seg_start) / ST;
     int j = 0;
-#define OB_DQ_ITER(MASKED)                                                                                   \
-    {                                                                                                        \
-        const int kv0 = ti.seg_start + j * ST;                                                               \
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                                \
-        __syncthreads();                                                                                     \
-        if (j + 1 < n_tiles) {                                                                               \
-            const long off = (long)(kv0 + ST) * ldkv * 2;                                                    \
-            tl.issue(kbase + off, kv_bytes - off, (j & 1) ? ks0 : ks1, wave);                                \
-            tl.issue(vbase + off, kv_bytes - off, (j & 1) ? vs0 : vs1, wave);                                \
-        }                                                                                                    \
-        const unsigned char OB_LDS *const ks = (j & 1) ? ks1 : ks0, *const vs = (j & 1) ? vs1 : vs0;         \
-        if (!(MASKED))                                                                                       \
-            dq_tile<D, CAUSAL, false>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv0, ti.seg_end, q_row, sl2);   \
-        else if (!(CAUSAL && kv0 > wave_q_last))                                                             \
-            dq_tile<D, CAUSAL, true>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv0, ti.seg_end, q_row, sl2);    \
+#define OB_DQ_ITER(MASKED, STAGE)                                                                            \
+    {                                                                                                       \
+        const int kv0 = ti.seg_start + j * ST;                                                              \
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                               \
+        __syncthreads();                                                                                    \
+        if (j + 1 < n_tiles) {                                                                              \
+            const long off = (long)(kv0 + ST) * ldkv * 2;                                                   \
+            tl.issue(own_base + off, own_bytes - off, sm + (1 - (STAGE)) * 2 * BYTES + half * BYTES, pair); \
+        }                                                                                                   \
+        const unsigned char OB_LDS *const ks = sm + (STAGE) * 2 * BYTES + half * 32 * Tile<D>::RB;          \
+        const unsigned char OB_LDS *const vs = ks + BYTES;                                                  \
+        const int kv_first = kv0 + half * 32;                                                               \
+        if (!(MASKED))                                                                                      \
+            dq_half<D, CAUSAL, false>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv_first, ti.seg_end, q_row,   \
+                                      sl2);                                                                 \
+        else if (kv_first < ti.seg_end && !(CAUSAL && kv_first > pair_q_last))                              \
+            dq_half<D, CAUSAL, true>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv_first, ti.seg_end, q_row,    \
+                                     sl2);                                                                  \
+        ++j;                                                                                                \
     }
-    for (; j < n_main; ++j) OB_DQ_ITER(false)
-    for (; j < n_tiles; ++j) OB_DQ_ITER(true)
+    while (j + 1 < n_main) {  // two tiles per trip: the stage is a compile-time constant
+        OB_DQ_ITER(false, 0)
+        OB_DQ_ITER(false, 1)
+    }
+    while (j < n_main) OB_DQ_ITER(false, j & 1)
+    while (j < n_tiles) OB_DQ_ITER(true, j & 1)
 #undef OB_DQ_ITER
-    if (!q_live) return;
+    // the pair's second wave hands its partial over: [pair][register quad][lane] 16-byte slots
+    __syncthreads();  // every wave is done reading the tiles
+    f32x4 OB_LDS *const slot = (f32x4 OB_LDS *)sm + (size_t)pair * (DT * 4 * 64) + lane;
+    if (half) {
 #pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 t4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t4[e] = acc_dq[dt][4 * g + e];
+                slot[(dt * 4 + g) * 64] = t4;
+            }
+    }
+    __syncthreads();
+    if (half || !q_live) return;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
+            const f32x4 t4 = slot[(dt * 4 + g) * 64];
             bf16x4 ov;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc_dq[dt][4 * g + e] * scale);
+            for (int e = 0; e < 4; ++e) ov[e] = (__bf16)((acc_dq[dt][4 * g + e] + t4[e]) * scale);
             *(bf16x4 *)(dq + (size_t)q_row * ldq + head * D + dt * 32 + g * 8 + lh * 4) = ov;
         }
 }
@@ -718,38 +746,49 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     const int n_head = CAUSAL ? min(2, n_iter) : 0;
     const int n_mid_end = max(n_head, n_iter - (((ti.seg_end - q_begin) % ST) ? 1 : 0));
     int it = 0;
-#define OB_DKV_ITER(MASKED)                                                                                  \
-    {                                                                                                        \
-        const int q0 = q_begin + it * ST;                                                                    \
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                                \
-        __syncthreads();                                                                                     \
-        if (it + 1 < n_iter) {                                                                               \
-            if (it & 1) OB_ISSUE_DKV(it + 1, 0); else OB_ISSUE_DKV(it + 1, 1);                               \
-        }                                                                                                    \
-        const unsigned char OB_LDS *const qs = (it & 1) ? qs1 : qs0, *const dos = (it & 1) ? dos1 : dos0;    \
-        const unsigned char OB_LDS *const row_tile = role_g ? dos : qs, *const tr_tile = role_g ? qs : dos;  \
-        const float OB_LDS *const stat = role_g ? ((it & 1) ? dlts1 : dlts0) : ((it & 1) ? lses1 : lses0);   \
-        /* a masked tile entirely before this pair's keys contributes nothing (but keeps the barriers) */    \
-        const bool live = !((MASKED) && CAUSAL && q0 + ST - 1 < pair_kv_first);                              \
-        f32x16 acc_x[2];                                                                                     \
-        bf16x8 pk[2][2];                                                                                     \
-        if (live) dkv_scores<D>(row_tile, tl, kvf, acc_x);                                                   \
-        if (live && !role_g) {                                                                               \
-            dkv_probs<CAUSAL, MASKED>(acc_x, stat, q0, ti.seg_end, kv_row, sl2, pk);                         \
-            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                 \
-                *(bf16x8 OB_LDS *)(p_mine + i_ * 1024) = pk[i_ >> 1][i_ & 1];                                \
-        }                                                                                                    \
-        __syncthreads();                                                                                     \
-        if (live && role_g) {                                                                                \
-            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                 \
-                pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + i_ * 1024);                          \
-            dkv_dscores(acc_x, stat, pk);                                                                    \
-        }                                                                                                    \
-        if (live) dkv_outputs<D>(tr_tile, tl, pk, acc_out);                                                  \
+#define OB_DKV_ITER(MASKED, QS, DOS, LSES, DLTS, ISSUE_NEXT)                                                 \
+    {                                                                                                       \
+        const int q0 = q_begin + it * ST;                                                                   \
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                               \
+        __syncthreads();                                                                                    \
+        if (it + 1 < n_iter) { ISSUE_NEXT; }                                                                \
+        const unsigned char OB_LDS *const row_tile = role_g ? (DOS) : (QS);                                 \
+        const unsigned char OB_LDS *const tr_tile = role_g ? (QS) : (DOS);                                  \
+        const float OB_LDS *const stat = role_g ? (DLTS) : (LSES);                                          \
+        /* a masked tile entirely before this pair's keys contributes nothing (but keeps the barriers) */   \
+        const bool live = !((MASKED) && CAUSAL && q0 + ST - 1 < pair_kv_first);                             \
+        f32x16 acc_x[2];                                                                                    \
+        bf16x8 pk[2][2];                                                                                    \
+        if (live) dkv_scores<D>(row_tile, tl, kvf, acc_x);                                                  \
+        if (live && !role_g) {                                                                              \
+            dkv_probs<CAUSAL, MASKED>(acc_x, stat, q0, ti.seg_end, kv_row, sl2, pk);                        \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                \
+                *(bf16x8 OB_LDS *)(p_mine + i_ * 1024) = pk[i_ >> 1][i_ & 1];                               \
+        }                                                                                                   \
+        __syncthreads();                                                                                    \
+        if (live && role_g) {                                                                               \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                \
+                pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + i_ * 1024);                         \
+            dkv_dscores(acc_x, stat, pk);                                                                   \
+        }                                                                                                   \
+        if (live) dkv_outputs<D>(tr_tile, tl, pk, acc_out);                                                 \
+        ++it;                                                                                               \
     }
-    for (; it < n_head; ++it) OB_DKV_ITER(true)
-    for (; it < n_mid_end; ++it) OB_DKV_ITER(false)
-    for (; it < n_iter; ++it) OB_DKV_ITER(true)
+#define OB_DKV_STAGE0(MASKED) OB_DKV_ITER(MASKED, qs0, dos0, lses0, dlts0, OB_ISSUE_DKV(it + 1, 1))
+#define OB_DKV_STAGE1(MASKED) OB_DKV_ITER(MASKED, qs1, dos1, lses1, dlts1, OB_ISSUE_DKV(it + 1, 0))
+#define OB_DKV_ANY(MASKED)                                                                                 \
+    OB_DKV_ITER(MASKED, (it & 1) ? qs1 : qs0, (it & 1) ? dos1 : dos0, (it & 1) ? lses1 : lses0,             \
+                (it & 1) ? dlts1 : dlts0, if (it & 1) OB_ISSUE_DKV(it + 1, 0); else OB_ISSUE_DKV(it + 1, 1))
+    while (it < n_head) OB_DKV_ANY(true)
+    while (it + 1 < n_mid_end) {  // it is even here: two tiles per trip with constant stage buffers
+        OB_DKV_STAGE0(false)
+        OB_DKV_STAGE1(false)
+    }
+    while (it < n_mid_end) OB_DKV_ANY(false)
+    while (it < n_iter) OB_DKV_ANY(true)
+#undef OB_DKV_ANY
+#undef OB_DKV_STAGE1
+#undef OB_DKV_STAGE0
 #undef OB_DKV_ITER
 #undef OB_ISSUE_DKV
     if (!kv_live) return;
@@ -877,7 +916,7 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     float *part_dk = part, *part_dv = part ? part + (size_t)group * T * nkv * d : nullptr;
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
-        OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 256, (const __bf16 *)d_o, (const __bf16 *)q,
+        OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 512, (const __bf16 *)d_o, (const __bf16 *)q,
                          (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
                          seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
     }
