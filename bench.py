@@ -41,6 +41,19 @@ def step_flops(shape, cu, n_blocks):
     return 3.0 * n_blocks * (T * gemm + 4.0 * nq * d * area)
 
 
+def measured_traffic(config, kernel):
+    """HBM bytes per launch of `kernel` on `config`, from the committed summary of two
+    rocprofv3 --pmc passes (profiles/hbm_traffic.txt); None when no summary covers this workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = dict(kv.split("=", 1) for kv in line.split() if "=" in kv)
+        if f.get("config") == str(config) and f.get("kernel") == kernel:
+            return float(f["fetch_bytes_per_launch"]) + float(f["write_bytes_per_launch"])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -50,6 +63,9 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--spread-batches", type=int, default=50)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="before the warm-up, copy this many MiB device-to-device three times: a "
+                         "kernel of known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -128,6 +144,14 @@ def main():
             g_in = g_out
         return cu
 
+    if args.calibrate_copy_mib > 0:
+        src = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         step(bal[i])
     torch.cuda.synchronize()
@@ -166,9 +190,18 @@ def main():
                          "frac": rate / (PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS)}
     gms, gcnt, gwork = prof["gemm"]
     g_ach = gwork / (gms * 1e-3) / 1e12
-    roofline = {"kernel": "gemm_nt_kernel (bf16 MFMA 32x32x16)", "bound": "mfma",
+    # compulsory HBM bytes of the 12 GEMMs of a block (operands once, result once, residual once)
+    T_avg = tokens / args.steps
+    Dq, HD, upF, F = shape.d_qkv, shape.n_q_heads * shape.head_dim, shape.up_rows, shape.mlp_dim
+    mnk = [(T_avg, Dq, H), (T_avg, H, HD), (T_avg, upF, H), (T_avg, H, F),      # forward
+           (T_avg, H, Dq), (T_avg, HD, H), (T_avg, H, upF), (T_avg, F, H),      # dgrad
+           (Dq, H, T_avg), (H, HD, T_avg), (upF, H, T_avg), (H, F, T_avg)]      # wgrad
+    alg_bytes = sum(2.0 * (m * k + n * k + m * n) for m, n, k in mnk) + 2 * 2.0 * T_avg * H
+    roofline = {"kernel": "gemm_kernel (bf16 MFMA 32x32x16; NT, NN and TN instances)", "bound": "mfma",
                 "achieved": g_ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": g_ach / PEAK_BF16_TFLOPS, "traffic": None,
+                "frac": g_ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config, "gemm"),
+                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
+                "algorithmic_bytes_per_launch": alg_bytes / 12.0,
                 "avg_launch_us": 1e3 * gms / gcnt, "launches": gcnt,
                 "flops_per_launch_avg": gwork / gcnt,
                 "share_of_step_time": gms / (prof_elapsed * 1e3)}
