@@ -17,6 +17,9 @@
  *     void*; NULL = the default stream).
  *   - Tensors are dense row-major.  Activations [T, H]; weights [out_features, in_features];
  *     bf16 storage (OB_BF16) with fp32 accumulation; row statistics and log-sum-exp are fp32.
+ *     OB_FP32 selects the debug path of the attention and block entry points: every tensor
+ *     (activations, weights, gradients, saved members) is fp32 and every product is a plain
+ *     fp32 FMA loop: slow, no MFMA, meant for checking against the oracle at 1e-4.
  *   - Every call validates its arguments on the host first and returns a non-zero ob_status
  *     WITHOUT launching anything when validation fails.  ob_last_error() gives the text.
  *   - Feature dimensions (hidden, mlp_dim, head_dim * heads) must be multiples of 64; head_dim
@@ -36,7 +39,7 @@ typedef enum {
     OB_OK = 0,
     OB_EINVAL = 1,       /* null pointer, non-positive size, inconsistent head counts ...      */
     OB_ESEGMENTS = 2,    /* cu_seqlens not starting at 0, not strictly increasing, wrong total  */
-    OB_EUNSUPPORTED = 3, /* head_dim not in {64,128}, dimension not a multiple of 64, fp32 path */
+    OB_EUNSUPPORTED = 3, /* head_dim not in {64,128}, dimension not a multiple of 64             */
     OB_EWORKSPACE = 4,   /* workspace / saved buffer smaller than the query functions report    */
     OB_EHIP = 5          /* a HIP launch failed; text in ob_last_error()                         */
 } ob_status;

@@ -84,7 +84,7 @@ int validate_attn(const ob_segments *seg, int nq, int nkv, int d, int ldq, int l
     if (nq < 1 || nkv < 1 || nq % nkv != 0)
         return fail(OB_EINVAL, "%s: n_q_heads %d must be a positive multiple of n_kv_heads %d", who, nq, nkv);
     if (d != 64 && d != 128) return fail(OB_EUNSUPPORTED, "%s: head_dim %d not in {64, 128}", who, d);
-    if (dtype != OB_BF16) return fail(OB_EUNSUPPORTED, "%s: only the bf16 path is built", who);
+    if (dtype != OB_BF16 && dtype != OB_FP32) return fail(OB_EINVAL, "%s: unknown dtype %d", who, dtype);
     if (mask != OB_MASK_SEG_BIDIR && mask != OB_MASK_SEG_CAUSAL) return fail(OB_EINVAL, "%s: unknown mask kind %d", who, mask);
     if (ldq < nq * d || ldo < nq * d || ldkv < nkv * d || ldq % 8 || ldkv % 8 || ldo % 8)
         return fail(OB_EINVAL, "%s: row strides must cover the heads and be multiples of 8 elements", who);
@@ -93,7 +93,7 @@ int validate_attn(const ob_segments *seg, int nq, int nkv, int d, int ldq, int l
 
 int validate_desc(const ob_block_desc *dsc, const char *who) {
     if (!dsc) return fail(OB_EINVAL, "%s: desc is null", who);
-    if (dsc->dtype != OB_BF16) return fail(OB_EUNSUPPORTED, "%s: only the bf16 path is built", who);
+    if (dsc->dtype != OB_BF16 && dsc->dtype != OB_FP32) return fail(OB_EINVAL, "%s: unknown dtype %d", who, dsc->dtype);
     if (dsc->hidden < 64 || dsc->mlp_dim < 64 || dsc->n_q_heads < 1 || dsc->n_kv_heads < 1)
         return fail(OB_EINVAL, "%s: non-positive dimension", who);
     if (dsc->n_q_heads % dsc->n_kv_heads)
@@ -220,7 +220,10 @@ extern "C" int ob_varlen_attn_fwd(const void *q, const void *k, const void *v, v
                                   int d, float scale, int mask, int dtype, void *hip_stream) {
     if (!q || !k || !v || !o || !lse) return fail(OB_EINVAL, "ob_varlen_attn_fwd: null tensor pointer");
     if (int rc = validate_attn(seg, nq, nkv, d, ldq, ldkv, ldo, mask, dtype, "ob_varlen_attn_fwd")) return rc;
-    launch_attn_fwd(q, k, v, o, lse, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, (hipStream_t)hip_stream);
+    if (dtype == OB_FP32)
+        f32::attn_fwd(q, k, v, o, lse, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, (hipStream_t)hip_stream);
+    else
+        launch_attn_fwd(q, k, v, o, lse, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, (hipStream_t)hip_stream);
     return check_launch("ob_varlen_attn_fwd");
 }
 
@@ -240,6 +243,10 @@ extern "C" int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k,
     if (!ws || ws_bytes < ob_varlen_attn_bwd_workspace_bytes(seg->total_tokens, nq, nkv, d))
         return fail(OB_EWORKSPACE, "ob_varlen_attn_bwd: workspace too small (%zu bytes given)", ws_bytes);
     hipStream_t s = (hipStream_t)hip_stream;
+    if (dtype == OB_FP32) {
+        f32::attn_bwd(d_o, q, k, v, o, lse, dq, dk, dv, (float *)ws, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, s);
+        return check_launch("ob_varlen_attn_bwd");
+    }
     const size_t rows = align_up((size_t)seg->total_tokens * nq * 4, 256);
     float *delta = (float *)ws, *lse2 = (float *)((unsigned char *)ws + rows);
     float *part = (float *)((unsigned char *)ws + 2 * rows);
@@ -250,17 +257,24 @@ extern "C" int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k,
 
 extern "C" size_t ob_block_saved_bytes(const ob_block_desc *desc, int total_tokens) {
     if (validate_desc(desc, "ob_block_saved_bytes") || total_tokens < 1 || total_tokens > MAX_TOKENS) return 0;
+    if (desc->dtype == OB_FP32) return f32::saved_layout(desc, total_tokens).total;
     return saved_layout(dims_of(desc, total_tokens)).total;
 }
 
 extern "C" size_t ob_block_workspace_bytes(const ob_block_desc *desc, int total_tokens) {
     if (validate_desc(desc, "ob_block_workspace_bytes") || total_tokens < 1 || total_tokens > MAX_TOKENS) return 0;
+    if (desc->dtype == OB_FP32) return f32::work_layout(desc, total_tokens).total;
     return work_layout(dims_of(desc, total_tokens)).total;
 }
 
 extern "C" size_t ob_block_saved_offset(const ob_block_desc *desc, int total_tokens, const char *name) {
     if (!name || validate_desc(desc, "ob_block_saved_offset") || total_tokens < 1) return (size_t)-1;
-    const Saved s = saved_layout(dims_of(desc, total_tokens));
+    Saved s = saved_layout(dims_of(desc, total_tokens));
+    if (desc->dtype == OB_FP32) {
+        const f32::SavedF32 f = f32::saved_layout(desc, total_tokens);
+        s.h1 = f.h1; s.qkv = f.qkv; s.o = f.o; s.lse = f.lse; s.x1 = f.x1; s.h2 = f.h2; s.up = f.up; s.act = f.act;
+        s.stat1 = f.stat1; s.stat2 = f.stat2;
+    }
     const struct { const char *n; size_t o; } tab[] = {
         {"h1", s.h1}, {"qkv", s.qkv}, {"o", s.o}, {"lse", s.lse}, {"x1", s.x1}, {"h2", s.h2},
         {"up", s.up}, {"act", s.act}, {"stat1", s.stat1}, {"stat2", s.stat2}};
@@ -294,6 +308,10 @@ extern "C" int ob_block_fwd(const ob_block_desc *desc, const ob_block_weights *w
     if (!x || !y) return fail(OB_EINVAL, "ob_block_fwd: x / y is null");
     if (int rc = validate_block(desc, w, seg, saved, saved_bytes, ws, ws_bytes, "ob_block_fwd")) return rc;
     hipStream_t s = (hipStream_t)hip_stream;
+    if (desc->dtype == OB_FP32) {
+        f32::block_fwd(desc, w, x, y, saved, seg, s);
+        return check_launch("ob_block_fwd");
+    }
     const Dims m = dims_of(desc, seg->total_tokens);
     const Saved sv = saved_layout(m);
     const bool bias = desc->has_bias != 0;
@@ -332,6 +350,10 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
     if (beta && (!g->n1_b || !g->n2_b)) return fail(OB_EINVAL, "ob_block_bwd: a beta gradient pointer is null");
 
     hipStream_t s = (hipStream_t)hip_stream;
+    if (desc->dtype == OB_FP32) {
+        f32::block_bwd(desc, w, g, accumulate_wgrad ? 1 : 0, x, dy, dx, saved, seg, ws, s);
+        return check_launch("ob_block_bwd");
+    }
     const Dims m = dims_of(desc, seg->total_tokens);
     const Saved sv = saved_layout(m);
     const Work wk = work_layout(m);

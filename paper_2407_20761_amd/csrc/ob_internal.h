@@ -72,4 +72,23 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
                      hipStream_t s);
 size_t attn_bwd_partial_bytes(int T, int nq, int nkv, int d);
 
+// ---- fp32 debug path (debug_fp32.hip): every tensor fp32, plain FMA kernels --------------------
+namespace f32 {
+struct SavedF32 { size_t h1, qkv, o, lse, x1, h2, up, act, stat1, stat2, total; };
+struct WorkF32 { size_t dact, dup, dh, dx1, d_o, dqkv, delta, total; };
+SavedF32 saved_layout(const ob_block_desc *dsc, int T);
+WorkF32 work_layout(const ob_block_desc *dsc, int T);
+void attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int ldq, int ldkv, int ldo,
+              const ob_segments *seg, int nq, int nkv, int d, float scale, int mask, hipStream_t s);
+// delta: nq * T floats of scratch
+void attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const void *o, const float *lse,
+              void *dq, void *dk, void *dv, float *delta, int ldq, int ldkv, int ldo, const ob_segments *seg, int nq,
+              int nkv, int d, float scale, int mask, hipStream_t s);
+void block_fwd(const ob_block_desc *dsc, const ob_block_weights *w, const void *x, void *y, void *saved,
+               const ob_segments *seg, hipStream_t s);
+void block_bwd(const ob_block_desc *dsc, const ob_block_weights *w, const ob_block_grads *g, int accumulate,
+               const void *x, const void *dy, void *dx, const void *saved, const ob_segments *seg, void *ws,
+               hipStream_t s);
+}  // namespace f32
+
 }  // namespace ob

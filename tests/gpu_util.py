@@ -9,9 +9,9 @@ import synth_inputs as si
 DEV = "cuda"
 
 
-def to_dev(a):
-    """bf16-representable float32 numpy -> bf16 device tensor (exact)."""
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(torch.bfloat16)
+def to_dev(a, dtype=torch.bfloat16):
+    """bf16-representable float32 numpy -> bf16 (or fp32) device tensor (exact)."""
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV).to(dtype)
 
 
 def to_np(t):
@@ -31,10 +31,10 @@ def saved_view(desc, T, saved, name, shape, dtype=torch.bfloat16):
 class BlockRun:
     """One block's device state: weights, grads, saved, workspace."""
 
-    def __init__(self, shape, w_np, T):
+    def __init__(self, shape, w_np, T, dtype=torch.bfloat16):
         self.shape, self.T = shape, T
-        self.desc = ob.make_desc(shape)
-        self.w = {n: to_dev(a) for n, a in w_np.items()}
+        self.desc = ob.make_desc(shape, ob.OB_BF16 if dtype == torch.bfloat16 else ob.OB_FP32)
+        self.w = {n: to_dev(a, dtype) for n, a in w_np.items()}
         self.g = {n: torch.zeros_like(t) for n, t in self.w.items()}
         self.saved = bytes_buf(ob.ob_block_saved_bytes(self.desc, T))
         self.ws = bytes_buf(ob.ob_block_workspace_bytes(self.desc, T))
@@ -50,11 +50,11 @@ class BlockRun:
         return dx
 
 
-def run_block(shape, w_np, x_np, dy_np, cu):
+def run_block(shape, w_np, x_np, dy_np, cu, dtype=torch.bfloat16):
     T = x_np.shape[0]
     seg = ob.Segments(cu)
-    run = BlockRun(shape, w_np, T)
-    x, dy = to_dev(x_np), to_dev(dy_np)
+    run = BlockRun(shape, w_np, T, dtype)
+    x, dy = to_dev(x_np, dtype), to_dev(dy_np, dtype)
     y = run.fwd(x, seg)
     dx = run.bwd(x, dy, seg)
     torch.cuda.synchronize()

@@ -1,8 +1,8 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
 
 Tolerance: max|err| / max|ref| <= 2e-2 per tensor for the bf16 path (the benchmark contract's
-bound; bf16 has 8 mantissa bits, every stored intermediate costs up to 2^-9 relative).  Segment
-offsets and masks are compared bit for bit.
+bound; bf16 has 8 mantissa bits, every stored intermediate costs up to 2^-9 relative) and <= 1e-4
+for the fp32 debug path.  Segment offsets and masks are compared bit for bit.
 """
 import numpy as np
 import pytest
@@ -16,6 +16,7 @@ from oracle import packer as orc_pack
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
+TOL_FP32 = 1e-4
 
 if torch.cuda.is_available():
     from gpu_util import BlockRun, bytes_buf, run_block, saved_view, to_dev, to_np
@@ -121,13 +122,14 @@ def test_mask_and_offsets_bit_exact(mask):
 
 # ---- whole block ----------------------------------------------------------------------------
 
-def _check_block(shape, cu, seed, intermediates=True):
+def _check_block(shape, cu, seed, intermediates=True, dtype=None, tol=TOL):
+    dtype = dtype or torch.bfloat16
     T = int(cu[-1])
     w = si.block_weights(shape, seed=seed)
     x, dy = si.activations(T, shape.hidden, seed=seed)
     y_ref, cache = orc.block_fwd(shape, w, x, cu)
     dx_ref, g_ref, _ = orc.block_bwd(shape, w, cache, dy, cu)
-    run, y, dx, g = run_block(shape, w, x, dy, cu)
+    run, y, dx, g = run_block(shape, w, x, dy, cu, dtype)
     errs = {"y": rel_err(y, y_ref), "dx": rel_err(dx, dx_ref)}
     for n in g_ref:
         errs["d" + n] = rel_err(g[n], g_ref[n])
@@ -140,10 +142,10 @@ def _check_block(shape, cu, seed, intermediates=True):
                  "h2": (cache["h2"], (T, shape.hidden)), "up": (cache["up"], (T, shape.up_rows)),
                  "act": (cache["act"], (T, shape.mlp_dim))}
         for n, (ref, shp) in views.items():
-            errs["saved." + n] = rel_err(to_np(saved_view(run.desc, T, run.saved, n, shp)), ref)
+            errs["saved." + n] = rel_err(to_np(saved_view(run.desc, T, run.saved, n, shp, dtype)), ref)
     _say("  " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()))
     assert set(g_ref) == set(w)
-    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    bad = {k: v for k, v in errs.items() if not v <= tol}
     assert not bad, bad
     return run
 
@@ -174,6 +176,54 @@ def test_block_small_variants(variant):
         lens = [1025, 130]
     _say(f"block {variant}: lens={lens}")
     _check_block(shape, si.lengths_to_cu(lens), seed=3)
+
+
+# ---- fp32 debug path: same entry points, dtype = OB_FP32, tolerance 1e-4 ----------------------
+
+@pytest.mark.parametrize("lens,nq,nkv,d,mask", ATTN_CASES[:3] + [([257, 130], 3, 3, 128, orc.MASK_BIDIR)])
+def test_fp32_debug_attention(lens, nq, nkv, d, mask):
+    _say(f"fp32 attention lens={lens} nq={nq} nkv={nkv} d={d} mask={mask}")
+    cu = si.lengths_to_cu(lens)
+    T = int(cu[-1])
+    q, k, v, d_o = si.qkv_tensors(T, nq, nkv, d, seed=len(lens) + d)
+    scale = 1.0 / np.sqrt(d)
+    o_ref, lse_ref = orc.attention_fwd(*(a.astype(np.float64) for a in (q, k, v)), cu, mask, scale)
+    dq_ref, dk_ref, dv_ref = orc.attention_bwd(*(a.astype(np.float64) for a in (d_o, q, k, v)),
+                                               cu, mask, scale)
+    f32 = torch.float32
+    qd, kd, vd = (to_dev(a.reshape(T, -1), f32) for a in (q, k, v))
+    o = torch.empty((T, nq * d), dtype=f32, device="cuda")
+    lse = torch.empty((nq, T), dtype=f32, device="cuda")
+    seg = ob.Segments(cu)
+    ob.ob_varlen_attn_fwd(qd, kd, vd, o, lse, nq * d, nkv * d, nq * d, seg, nq, nkv, d, scale, mask,
+                          dtype=ob.OB_FP32)
+    assert rel_err(to_np(o).reshape(T, nq, d), o_ref) < TOL_FP32
+    assert np.abs(to_np(lse) - lse_ref).max() < 1e-4
+    dq, dk, dv = (torch.full_like(t, float("nan")) for t in (qd, kd, vd))
+    ws = bytes_buf(ob.ob_varlen_attn_bwd_workspace_bytes(T, nq, nkv, d))
+    ob.ob_varlen_attn_bwd(to_dev(d_o.reshape(T, -1), f32), qd, kd, vd, o, lse, dq, dk, dv, nq * d, nkv * d,
+                          nq * d, seg, nq, nkv, d, scale, mask, ws, dtype=ob.OB_FP32)
+    assert rel_err(to_np(dq).reshape(T, nq, d), dq_ref) < TOL_FP32
+    assert rel_err(to_np(dk).reshape(T, nkv, d), dk_ref) < TOL_FP32
+    assert rel_err(to_np(dv).reshape(T, nkv, d), dv_ref) < TOL_FP32
+
+
+@pytest.mark.parametrize("variant", ["config1", "llm-like", "vit-d128-rms"])
+def test_fp32_debug_block(variant):
+    if variant == "config1":
+        shape, lens = si.CONFIGS[1], si.tiny_segment_lengths(seed=0)
+    elif variant == "llm-like":
+        shape = si.small_shape(hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, mlp_dim=320,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
+                               use_rotary=True, has_bias=False, norm_eps=1e-6)
+        lens = [300, 1, 140, 259]
+    else:
+        shape = si.small_shape(hidden=384, n_q_heads=3, n_kv_heads=3, head_dim=128, mlp_dim=1536,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_GELU, mask=si.MASK_BIDIR,
+                               use_rotary=False, has_bias=False, norm_eps=1e-6)
+        lens = [513, 130]
+    _say(f"fp32 block {variant}: lens={list(lens)}")
+    _check_block(shape, si.lengths_to_cu(lens), seed=3, dtype=torch.float32, tol=TOL_FP32)
 
 
 def _subset_cu(cfg, max_tokens, seed=0):

@@ -101,7 +101,7 @@ def test_attention_argument_validation():
     assert _attn_status(_seg([0, 5, 9], max_seqlen=3)) == ob.OB_ESEGMENTS
     assert _attn_status(good, nq=4, nkv=3) == ob.OB_EINVAL
     assert _attn_status(good, d=96) == ob.OB_EUNSUPPORTED
-    assert _attn_status(good, dtype=ob.OB_FP32) == ob.OB_EUNSUPPORTED
+    assert _attn_status(good, dtype=7) == ob.OB_EINVAL
     assert _attn_status(good, mask=7) == ob.OB_EINVAL
     assert _attn_status(good, ldq=100) == ob.OB_EINVAL
     assert _attn_status(_seg([0, 5, 9], fake_dev=False)) == ob.OB_EINVAL  # cu_dev null
@@ -123,6 +123,12 @@ def test_block_argument_validation_and_sizes():
             ("h1", "qkv", "o", "lse", "x1", "h2", "up", "act", "stat1", "stat2")]
     assert offs == sorted(offs) and offs[0] == 0 and all(o % 256 == 0 for o in offs)
     assert ob.ob_block_saved_offset(desc, T, "nope") == C.c_size_t(-1).value
+    # the fp32 debug path stores the same members with four-byte elements
+    d32 = ob.make_desc(shape, dtype=ob.OB_FP32)
+    sb32 = ob.ob_block_saved_bytes(d32, T)
+    lower32 = T * (4 * 256 + 768 + 1024 + 1024) * 4 + 4 * T * 4 + 2 * T * 2 * 4
+    assert lower32 <= sb32 <= lower32 + 10 * 256 and ob.ob_block_workspace_bytes(d32, T) > 0
+    assert ob.ob_block_saved_offset(d32, T, "qkv") == (T * 256 * 4 + 255) // 256 * 256
 
     p = C.c_void_p(0x1000)
     w = ob.ob_block_weights(*[0x1000] * 12)
@@ -140,7 +146,7 @@ def test_block_argument_validation_and_sizes():
     w_missing.b_qkv = None
     assert fwd(desc, w_=w_missing) == ob.OB_EINVAL            # has_bias but no bias pointer
     for field, val, status in (("head_dim", 96, ob.OB_EUNSUPPORTED), ("hidden", 250, ob.OB_EUNSUPPORTED),
-                               ("n_kv_heads", 3, ob.OB_EINVAL), ("dtype", ob.OB_FP32, ob.OB_EUNSUPPORTED),
+                               ("n_kv_heads", 3, ob.OB_EINVAL), ("dtype", 7, ob.OB_EINVAL),
                                ("norm", 5, ob.OB_EINVAL), ("hidden", 16384, ob.OB_EUNSUPPORTED)):
         d2 = ob.make_desc(shape)
         setattr(d2, field, val)
