@@ -206,6 +206,41 @@ def main():
                 "flops_per_launch_avg": gwork / gcnt,
                 "share_of_step_time": gms / (prof_elapsed * 1e3)}
 
+    # ---- re-computation (Sec. 4.3): every block replays its forward; one saved buffer serves all --
+    def step_recompute(group):
+        cu = cu_of(group)
+        seg = ob.Segments(cu, device=dev)
+        T = int(cu[-1])
+        for i in range(L):
+            ob.ob_block_fwd(desc, weights[i], acts[i][:T], acts[i + 1][:T], saved[0], seg, ws, stream)
+        g_in = dy[:T]
+        for i in reversed(range(L)):
+            g_out = gbuf[i & 1][:T]
+            ob.ob_block_bwd(desc, weights[i], grads[i], ob.OB_BWD_RECOMPUTE, acts[i][:T], g_in, g_out,
+                            saved[0], seg, ws, stream)
+            g_in = g_out
+
+    n_rc = min(3, args.steps)
+    step_recompute(timed[0])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for g in timed[:n_rc]:
+        step_recompute(g)
+    torch.cuda.synchronize()
+    rc_ms = (time.perf_counter() - t0) * 1e3 / n_rc
+    base_ms = ms_per_step
+    per_block = ob.ob_block_saved_bytes(desc, Tmax)
+    free_now, total_mem = torch.cuda.mem_get_info()
+    m_r = free_now + (L - 1) * per_block           # what would be free with re-computation everywhere
+    fwd_ms_block = max(rc_ms - base_ms, 0.0) / L   # replay cost of one block
+    kinds = (0, 1, 0.0, L, per_block, fwd_ms_block) if shape.kind == "llm" else (L, per_block, fwd_ms_block, 0, 1, 0.0)
+    keep_v, keep_t = ob.ob_recompute_plan(m_r, *kinds)
+    recompute = {"ms_per_step_all_blocks_recomputed": rc_ms, "ms_per_step_none_recomputed": base_ms,
+                 "replay_ms_per_block": fwd_ms_block, "saved_bytes_per_block": int(per_block),
+                 "bytes_freed_by_recomputing_all": int((L - 1) * per_block),
+                 "free_bytes_with_all_recomputed": int(m_r), "hbm_bytes": int(total_mem),
+                 "blocks_that_may_skip_recomputation": int(keep_v + keep_t), "n_blocks": L}
+
     # ---- step-time spread: balanced vs random grouping ----------------------------------------
     spread = None
     if n_spread > 0:
@@ -284,7 +319,8 @@ def main():
         "ms_per_step_with_event_profiling": prof_elapsed * 1e3 / args.steps,
         "packer": {"ms": packer_ms, "samples": int(len(tiles)), "groups": len(groups),
                    "leftover": int(len(leftover)), "groups_per_iter": [int(a) for a in per_iter]},
-        "roofline": roofline, "kernels": kernels, "spread": spread, "cpu_baseline": cpu,
+        "roofline": roofline, "kernels": kernels, "spread": spread, "recompute": recompute,
+        "cpu_baseline": cpu,
         "context": PAPER_CONTEXT,
     }
     print(json.dumps(out))

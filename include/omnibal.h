@@ -120,15 +120,21 @@ int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k, const void
 /* ---- one transformer block (steps a1..a9 / b9..b1) -------------------------------------------
  * ob_block_fwd:  y = Block(x); keeps in `saved` (ob_block_saved_bytes) what the backward needs.
  * ob_block_bwd:  given dy, the same x, weights and `saved`, writes dx and every weight gradient
- * (bf16, after fp32 accumulation; accumulate_wgrad != 0 adds into the existing gradient buffers
- * instead of overwriting them).  x/y and dy/dx may not alias each other or `saved`/`ws`. */
+ * (bf16, after fp32 accumulation).  `flags` is a bit set:
+ *   OB_BWD_ACCUMULATE  add into the existing gradient buffers instead of overwriting them;
+ *   OB_BWD_RECOMPUTE   re-computation (Sec. 4.3): `saved` need not hold this block's forward data
+ *                      (one buffer may serve every block); the forward is replayed from x into it
+ *                      first (every step but the last GEMM), then the backward runs as usual, so
+ *                      the results are bit-identical to the non-recomputed ones.
+ * x/y and dy/dx may not alias each other or `saved`/`ws`. */
+enum { OB_BWD_ACCUMULATE = 1, OB_BWD_RECOMPUTE = 2 };
 size_t ob_block_saved_bytes(const ob_block_desc *desc, int total_tokens);
 size_t ob_block_workspace_bytes(const ob_block_desc *desc, int total_tokens);
 int ob_block_fwd(const ob_block_desc *desc, const ob_block_weights *w, const void *x, void *y,
                  void *saved, size_t saved_bytes, const ob_segments *seg, void *ws, size_t ws_bytes,
                  void *hip_stream);
 int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w, const ob_block_grads *g,
-                 int accumulate_wgrad, const void *x, const void *dy, void *dx, const void *saved,
+                 int flags, const void *x, const void *dy, void *dx, void *saved,
                  size_t saved_bytes, const ob_segments *seg, void *ws, size_t ws_bytes,
                  void *hip_stream);
 
@@ -172,6 +178,16 @@ int ob_pack_isf(const int32_t *n_img, const int32_t *n_tok, int64_t n_samples, i
 int ob_pack_random(int64_t n_samples, int64_t B, uint64_t seed, int64_t *group_offsets,
                    int64_t *n_groups, int64_t *sample_ids, int64_t *leftover_ids,
                    int64_t *n_leftover);
+/* Sec. 5.4, method 2 (Length-Group): samples sorted by token count (ties by id), cut into runs of
+ * B, the mini-batches then put in a seeded random order.  Method 3 (Device-Group): the random
+ * arm's mini-batches ordered by their token totals, so consecutive mini-batches (the ones a step
+ * hands to its devices) are close in size.  Outputs as for ob_pack_random. */
+int ob_pack_length_group(const int32_t *n_tok, int64_t n_samples, int64_t B, uint64_t seed,
+                         int64_t *group_offsets, int64_t *n_groups, int64_t *sample_ids,
+                         int64_t *leftover_ids, int64_t *n_leftover);
+int ob_pack_device_group(const int32_t *n_tok, int64_t n_samples, int64_t B, uint64_t seed,
+                         int64_t *group_offsets, int64_t *n_groups, int64_t *sample_ids,
+                         int64_t *leftover_ids, int64_t *n_leftover);
 /* Segment offsets of one packed mini-batch: one segment per sample (LLM) / per tile (ViT). */
 int ob_build_cu_seqlens_llm(const int64_t *group_ids, int64_t n, const int32_t *n_tok,
                             int32_t *cu_out, int32_t *max_seqlen_out);
@@ -179,6 +195,35 @@ int ob_build_cu_seqlens_vit(int64_t n_tiles, int32_t tile_len, int32_t *cu_out);
 /* Eq. 1 and Eq. 2 (same form): sum_i (max - v_i) / (max * n). */
 double ob_pad_ratio(const int64_t *tokens_per_sample, int64_t n);
 double ob_dist_ratio(const int64_t *tokens_per_minibatch, int64_t n);
+
+
+/* ---- host side: adaptive re-computation, Step 4 (Sec. 4.3) -----------------------------------
+ * With re-computation on everywhere a stage has free_bytes (M_r) left; keeping the activations of
+ * one ViT / LLM layer costs saved_bytes_vit / saved_bytes_llm (M_v / M_t, e.g.
+ * ob_block_saved_bytes) and saves that layer's forward replay (fwd_ms_*).  Returns the counts of
+ * layers that may skip re-computation: the pair that saves the most replay time within the budget
+ * (ties: fewer bytes, then fewer ViT layers).  Each failed trial run of the caller adds one to
+ * extra_recompute: one more kept layer is given up, the kind with the larger footprint first. */
+int ob_recompute_plan(int64_t free_bytes, int n_vit, int64_t saved_bytes_vit, double fwd_ms_vit,
+                      int n_llm, int64_t saved_bytes_llm, double fwd_ms_llm, int extra_recompute,
+                      int *keep_vit, int *keep_llm);
+
+/* ---- host side: balanced model partitioning (Sec. 4.2) ---------------------------------------
+ * Layers are numbered 1..L, the pipeline has N stages, a partition is P = (P1 < ... < P(N-1)) with
+ * P0 = 1 and PN = L + 1; stage i holds layers P(i-1) <= l < P(i).  fwd_ms[l-1] = profiled forward
+ * time of layer l, activ[l-1] = size of its output activation (the volume sent if a cut follows).
+ * ob_bmp_anchor: greedy anchor P+, cut i where the running time is closest to i/N of the total
+ * among positions that leave every stage a layer (ties: the earlier).  P_out[N-1].
+ * ob_bmp_search: every partition within radius r of the anchor that is valid (n_candidates of
+ * them; 27 for r = 1, N = 4 when none falls off the ends), scored by
+ *   VAR(fwd_time) + comm_weight * SUM(comm)      (Eq. 4 + Eq. 5; the variance as printed, no 1/N)
+ * and the top_k lowest returned in ascending order (ties: lexicographic in P):
+ * cand_out[top_k][N-1], score_out[top_k], n_returned = min(top_k, n_candidates).  Timing the
+ * returned candidates and picking the fastest (Eq. 3) is the caller's step. */
+int ob_bmp_anchor(const double *fwd_ms, int L, int N, int *P_out);
+int ob_bmp_search(const double *fwd_ms, const double *activ, int L, int N, int r, double comm_weight,
+                  int top_k, int *cand_out, double *score_out, int64_t *n_candidates,
+                  int *n_returned);
 
 #ifdef __cplusplus
 }

@@ -118,6 +118,26 @@ def random_groups(n_samples, B, seed):
     return groups, sorted(perm[n_full * B:])
 
 
+def length_groups(n_tok, B, seed):
+    """Sec. 5.4 method 2 (Length-Group), reading: sort by token count (ties by id), cut into runs of
+    B, then put the mini-batches in a random order; the last partial run is left over."""
+    n = len(n_tok)
+    order = sorted(range(n), key=lambda i: (int(n_tok[i]), i))
+    n_full = n // B
+    batch_order = randperm(n_full, seed)
+    groups = [order[b * B:(b + 1) * B] for b in batch_order]
+    return groups, sorted(order[n_full * B:])
+
+
+def device_groups(n_tok, B, seed):
+    """Sec. 5.4 method 3 (Device-Group), reading: the random arm's mini-batches ordered by their
+    token totals (ties keep the random order)."""
+    groups, left = random_groups(len(n_tok), B, seed)
+    totals = [sum(int(n_tok[i]) for i in g) for g in groups]
+    idx = sorted(range(len(groups)), key=lambda g: (totals[g], g))
+    return [groups[g] for g in idx], left
+
+
 def choose_qv(n_img, n_tok, Qt):
     """Sec. 5.2: Qv from the dataset's image-to-token ratio at the token budget Qt."""
     return max(1, int(math.floor(Qt * sum(int(a) for a in n_img)

@@ -21,6 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libomnibal.so")
 
 OB_OK, OB_EINVAL, OB_ESEGMENTS, OB_EUNSUPPORTED, OB_EWORKSPACE, OB_EHIP = range(6)
 OB_BF16, OB_FP32 = 0, 1
+OB_BWD_ACCUMULATE, OB_BWD_RECOMPUTE = 1, 2
 OB_MASK_SEG_BIDIR, OB_MASK_SEG_CAUSAL = 0, 1
 OB_LAYERNORM, OB_RMSNORM = 0, 1
 OB_GELU, OB_SWIGLU = 0, 1
@@ -90,6 +91,13 @@ _SIGNATURES = {
     "ob_pack_random": (_I, [C.c_int64, C.c_int64, C.c_uint64, _i64p, _i64p, _i64p, _i64p, _i64p]),
     "ob_build_cu_seqlens_llm": (_I, [_i64p, C.c_int64, _i32p, _i32p, _i32p]),
     "ob_build_cu_seqlens_vit": (_I, [C.c_int64, C.c_int32, _i32p]),
+    "ob_pack_length_group": (_I, [_i32p, C.c_int64, C.c_int64, C.c_uint64, _i64p, _i64p, _i64p, _i64p, _i64p]),
+    "ob_pack_device_group": (_I, [_i32p, C.c_int64, C.c_int64, C.c_uint64, _i64p, _i64p, _i64p, _i64p, _i64p]),
+    "ob_recompute_plan": (_I, [C.c_int64, _I, C.c_int64, C.c_double, _I, C.c_int64, C.c_double, _I,
+                               C.POINTER(C.c_int), C.POINTER(C.c_int)]),
+    "ob_bmp_anchor": (_I, [C.POINTER(C.c_double), _I, _I, C.POINTER(C.c_int)]),
+    "ob_bmp_search": (_I, [C.POINTER(C.c_double), C.POINTER(C.c_double), _I, _I, _I, C.c_double, _I,
+                           C.POINTER(C.c_int), C.POINTER(C.c_double), _i64p, C.POINTER(C.c_int)]),
     "ob_pad_ratio": (C.c_double, [_i64p, C.c_int64]),
     "ob_dist_ratio": (C.c_double, [_i64p, C.c_int64]),
 }
@@ -202,11 +210,12 @@ def ob_block_fwd(desc, weights: dict, x, y, saved, seg: Segments, ws, stream=Non
                             ws.numel() * ws.element_size(), _stream(stream)))
 
 
-def ob_block_bwd(desc, weights: dict, grads: dict, accumulate_wgrad, x, dy, dx, saved,
+def ob_block_bwd(desc, weights: dict, grads: dict, flags, x, dy, dx, saved,
                  seg: Segments, ws, stream=None):
+    """flags: bit set of OB_BWD_ACCUMULATE / OB_BWD_RECOMPUTE (False / True = 0 / accumulate)"""
     w = _weights_struct(ob_block_weights, weights)
     g = _weights_struct(ob_block_grads, grads)
-    _check(lib.ob_block_bwd(C.byref(desc), C.byref(w), C.byref(g), int(accumulate_wgrad), _ptr(x),
+    _check(lib.ob_block_bwd(C.byref(desc), C.byref(w), C.byref(g), int(flags), _ptr(x),
                             _ptr(dy), _ptr(dx), _ptr(saved), saved.numel() * saved.element_size(),
                             C.byref(seg.c), _ptr(ws), ws.numel() * ws.element_size(),
                             _stream(stream)))
@@ -256,6 +265,56 @@ def ob_pack_random(n_samples, B, seed=0):
                               ids.ctypes.data_as(_i64p), left.ctypes.data_as(_i64p), C.byref(nl)))
     groups = [ids[offs[g]:offs[g + 1]].copy() for g in range(ng.value)]
     return groups, left[:nl.value].copy()
+
+
+def _pack_by_size(fn, n_tok, B, seed):
+    n_tok = np.ascontiguousarray(n_tok, dtype=np.int32)
+    n = len(n_tok)
+    offs, ids, left = np.zeros(n + 1, np.int64), np.zeros(max(n, 1), np.int64), np.zeros(max(n, 1), np.int64)
+    ng, nl = C.c_int64(0), C.c_int64(0)
+    _check(fn(n_tok.ctypes.data_as(_i32p), n, int(B), int(seed), offs.ctypes.data_as(_i64p), C.byref(ng),
+              ids.ctypes.data_as(_i64p), left.ctypes.data_as(_i64p), C.byref(nl)))
+    return [ids[offs[g]:offs[g + 1]].copy() for g in range(ng.value)], left[:nl.value].copy()
+
+
+def ob_pack_length_group(n_tok, B, seed=0):
+    return _pack_by_size(lib.ob_pack_length_group, n_tok, B, seed)
+
+
+def ob_pack_device_group(n_tok, B, seed=0):
+    return _pack_by_size(lib.ob_pack_device_group, n_tok, B, seed)
+
+
+def ob_recompute_plan(free_bytes, n_vit, bytes_vit, ms_vit, n_llm, bytes_llm, ms_llm, extra_recompute=0):
+    kv, kt = C.c_int(0), C.c_int(0)
+    _check(lib.ob_recompute_plan(int(free_bytes), int(n_vit), int(bytes_vit), float(ms_vit), int(n_llm),
+                                 int(bytes_llm), float(ms_llm), int(extra_recompute), C.byref(kv), C.byref(kt)))
+    return kv.value, kt.value
+
+
+def _dbl(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def ob_bmp_anchor(fwd_ms, N):
+    f = _dbl(fwd_ms)
+    P = (C.c_int * max(int(N) - 1, 1))()
+    _check(lib.ob_bmp_anchor(f.ctypes.data_as(C.POINTER(C.c_double)), len(f), int(N), P))
+    return tuple(P[:int(N) - 1])
+
+
+def ob_bmp_search(fwd_ms, activ, N, r, comm_weight=1.0, top_k=10):
+    """([(score, P)] ascending, number of valid candidates)"""
+    f, a = _dbl(fwd_ms), _dbl(activ)
+    assert len(f) == len(a)
+    c = int(N) - 1
+    cand = (C.c_int * max(top_k * c, 1))()
+    score = (C.c_double * top_k)()
+    n_c, n_r = C.c_int64(0), C.c_int(0)
+    _check(lib.ob_bmp_search(f.ctypes.data_as(C.POINTER(C.c_double)), a.ctypes.data_as(C.POINTER(C.c_double)),
+                             len(f), int(N), int(r), float(comm_weight), int(top_k), cand, score,
+                             C.byref(n_c), C.byref(n_r)))
+    return [(score[k], tuple(cand[k * c:(k + 1) * c])) for k in range(n_r.value)], n_c.value
 
 
 def ob_build_cu_seqlens_llm(group_ids, n_tok):

@@ -302,16 +302,10 @@ static int validate_block(const ob_block_desc *desc, const ob_block_weights *w, 
     return OB_OK;
 }
 
-extern "C" int ob_block_fwd(const ob_block_desc *desc, const ob_block_weights *w, const void *x, void *y,
-                            void *saved, size_t saved_bytes, const ob_segments *seg, void *ws,
-                            size_t ws_bytes, void *hip_stream) {
-    if (!x || !y) return fail(OB_EINVAL, "ob_block_fwd: x / y is null");
-    if (int rc = validate_block(desc, w, seg, saved, saved_bytes, ws, ws_bytes, "ob_block_fwd")) return rc;
-    hipStream_t s = (hipStream_t)hip_stream;
-    if (desc->dtype == OB_FP32) {
-        f32::block_fwd(desc, w, x, y, saved, seg, s);
-        return check_launch("ob_block_fwd");
-    }
+// forward of one bf16 block into `saved`; y == nullptr: everything but the last GEMM (the replay
+// of the re-computation path, which has no use for the block output)
+static void block_fwd_bf16(const ob_block_desc *desc, const ob_block_weights *w, const void *x, void *y,
+                           void *saved, const ob_segments *seg, hipStream_t s) {
     const Dims m = dims_of(desc, seg->total_tokens);
     const Saved sv = saved_layout(m);
     const bool bias = desc->has_bias != 0;
@@ -331,15 +325,27 @@ extern "C" int ob_block_fwd(const ob_block_desc *desc, const ob_block_weights *w
     launch_norm_fwd(desc->norm, x1, w->n2_g, beta ? w->n2_b : nullptr, h2, (float *)at(saved, sv.stat2), m.T, m.H, desc->norm_eps, s);
     launch_gemm_nt(m.T, m.upF, m.H, h2, m.H, w->w_up, m.H, up, m.upF, bias ? w->b_up : nullptr, nullptr, 0, s);
     launch_act_fwd(desc->mlp, up, act, m.T, m.F, s);
-    launch_gemm_nt(m.T, m.H, m.F, act, m.F, w->w_down, m.F, y, m.H, bias ? w->b_down : nullptr, x1, m.H, s);
+    if (y) launch_gemm_nt(m.T, m.H, m.F, act, m.F, w->w_down, m.F, y, m.H, bias ? w->b_down : nullptr, x1, m.H, s);
+}
+
+extern "C" int ob_block_fwd(const ob_block_desc *desc, const ob_block_weights *w, const void *x, void *y,
+                            void *saved, size_t saved_bytes, const ob_segments *seg, void *ws,
+                            size_t ws_bytes, void *hip_stream) {
+    if (!x || !y) return fail(OB_EINVAL, "ob_block_fwd: x / y is null");
+    if (int rc = validate_block(desc, w, seg, saved, saved_bytes, ws, ws_bytes, "ob_block_fwd")) return rc;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (desc->dtype == OB_FP32) f32::block_fwd(desc, w, x, y, saved, seg, s);
+    else block_fwd_bf16(desc, w, x, y, saved, seg, s);
     return check_launch("ob_block_fwd");
 }
 
 extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w, const ob_block_grads *g,
-                            int accumulate_wgrad, const void *x, const void *dy, void *dx,
-                            const void *saved, size_t saved_bytes, const ob_segments *seg, void *ws,
+                            int flags, const void *x, const void *dy, void *dx,
+                            void *saved, size_t saved_bytes, const ob_segments *seg, void *ws,
                             size_t ws_bytes, void *hip_stream) {
     if (!x || !dy || !dx) return fail(OB_EINVAL, "ob_block_bwd: x / dy / dx is null");
+    if (flags & ~(OB_BWD_ACCUMULATE | OB_BWD_RECOMPUTE)) return fail(OB_EINVAL, "ob_block_bwd: unknown flag bits %d", flags);
+    const int accumulate_wgrad = flags & OB_BWD_ACCUMULATE;
     if (int rc = validate_block(desc, w, seg, saved, saved_bytes, ws, ws_bytes, "ob_block_bwd")) return rc;
     if (!g) return fail(OB_EINVAL, "ob_block_bwd: grads is null");
     if (!g->n1_g || !g->w_qkv || !g->w_o || !g->n2_g || !g->w_up || !g->w_down)
@@ -351,9 +357,11 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
 
     hipStream_t s = (hipStream_t)hip_stream;
     if (desc->dtype == OB_FP32) {
+        if (flags & OB_BWD_RECOMPUTE) f32::block_fwd(desc, w, x, nullptr, saved, seg, s);
         f32::block_bwd(desc, w, g, accumulate_wgrad ? 1 : 0, x, dy, dx, saved, seg, ws, s);
         return check_launch("ob_block_bwd");
     }
+    if (flags & OB_BWD_RECOMPUTE) block_fwd_bf16(desc, w, x, nullptr, saved, seg, s);
     const Dims m = dims_of(desc, seg->total_tokens);
     const Saved sv = saved_layout(m);
     const Work wk = work_layout(m);

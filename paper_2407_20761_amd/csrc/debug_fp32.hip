@@ -407,7 +407,7 @@ void block_fwd(const ob_block_desc *dsc, const ob_block_weights *w, const void *
     gemm(0, T, upF, H, h2, OB_F(w->w_up), up, bias ? OB_F(w->b_up) : nullptr, nullptr, 0, s);
     hipLaunchKernelGGL(act_fwd_kernel, dim3(blocks_for((long)T * F)), dim3(256), 0, s, dsc->mlp == OB_SWIGLU ? 1 : 0, up,
                        act, (long)T * F, F);
-    gemm(0, T, H, F, act, OB_F(w->w_down), OB_FM(y), bias ? OB_F(w->b_down) : nullptr, x1, 0, s);
+    if (y) gemm(0, T, H, F, act, OB_F(w->w_down), OB_FM(y), bias ? OB_F(w->b_down) : nullptr, x1, 0, s);
 }
 
 void block_bwd(const ob_block_desc *dsc, const ob_block_weights *w, const ob_block_grads *g, int acc, const void *x,

@@ -137,6 +137,57 @@ extern "C" int ob_pack_random(int64_t n_samples, int64_t B, uint64_t seed, int64
     return OB_OK;
 }
 
+// Sec. 5.4, method 2 ("Length-Group"): samples of similar size share a mini-batch.  Reading: sort
+// by token count (ties by id), cut into consecutive runs of B, then shuffle the order of the
+// mini-batches so that the ones a step hands to its devices are unrelated in size.
+extern "C" int ob_pack_length_group(const int32_t *n_tok, int64_t n_samples, int64_t B, uint64_t seed,
+                                    int64_t *group_offsets, int64_t *n_groups, int64_t *sample_ids,
+                                    int64_t *leftover_ids, int64_t *n_leftover) {
+    if (!n_tok || !group_offsets || !n_groups || !sample_ids || !leftover_ids || !n_leftover)
+        return ob::fail(OB_EINVAL, "ob_pack_length_group: null pointer");
+    if (n_samples < 0 || B <= 0) return ob::fail(OB_EINVAL, "ob_pack_length_group: bad n_samples or B");
+    std::vector<int64_t> order((size_t)n_samples);
+    std::iota(order.begin(), order.end(), (int64_t)0);
+    std::stable_sort(order.begin(), order.end(), [&](int64_t a, int64_t b) { return n_tok[a] < n_tok[b]; });
+    const int64_t full = n_samples / B;
+    std::vector<int64_t> batch((size_t)full);
+    std::iota(batch.begin(), batch.end(), (int64_t)0);
+    shuffle(batch, seed);
+    group_offsets[0] = 0;
+    for (int64_t g = 0; g < full; ++g) {
+        for (int64_t p = 0; p < B; ++p) sample_ids[g * B + p] = order[(size_t)(batch[(size_t)g] * B + p)];
+        group_offsets[g + 1] = (g + 1) * B;
+    }
+    *n_groups = full;
+    std::vector<int64_t> rest(order.begin() + (size_t)(full * B), order.end());
+    std::sort(rest.begin(), rest.end());
+    std::copy(rest.begin(), rest.end(), leftover_ids);
+    *n_leftover = (int64_t)rest.size();
+    return OB_OK;
+}
+
+// Sec. 5.4, method 3 ("Device-Group"): the mini-batches one step hands to its devices are of
+// similar size.  Reading: the random arm's mini-batches, ordered by their token totals (ties keep
+// the random order), so that any run of consecutive mini-batches is close in size.
+extern "C" int ob_pack_device_group(const int32_t *n_tok, int64_t n_samples, int64_t B, uint64_t seed,
+                                    int64_t *group_offsets, int64_t *n_groups, int64_t *sample_ids,
+                                    int64_t *leftover_ids, int64_t *n_leftover) {
+    if (!n_tok) return ob::fail(OB_EINVAL, "ob_pack_device_group: null pointer");
+    if (int rc = ob_pack_random(n_samples, B, seed, group_offsets, n_groups, sample_ids, leftover_ids, n_leftover))
+        return rc;
+    const int64_t full = *n_groups;
+    std::vector<int64_t> total((size_t)full, 0), idx((size_t)full);
+    for (int64_t g = 0; g < full; ++g)
+        for (int64_t p = 0; p < B; ++p) total[(size_t)g] += n_tok[sample_ids[g * B + p]];
+    std::iota(idx.begin(), idx.end(), (int64_t)0);
+    std::stable_sort(idx.begin(), idx.end(), [&](int64_t a, int64_t b) { return total[(size_t)a] < total[(size_t)b]; });
+    std::vector<int64_t> out((size_t)(full * B));
+    for (int64_t g = 0; g < full; ++g)
+        for (int64_t p = 0; p < B; ++p) out[(size_t)(g * B + p)] = sample_ids[idx[(size_t)g] * B + p];
+    std::copy(out.begin(), out.end(), sample_ids);
+    return OB_OK;
+}
+
 extern "C" int ob_build_cu_seqlens_llm(const int64_t *group_ids, int64_t n, const int32_t *n_tok,
                                        int32_t *cu_out, int32_t *max_seqlen_out) {
     if (!group_ids || !n_tok || !cu_out) return ob::fail(OB_EINVAL, "ob_build_cu_seqlens_llm: null pointer");

@@ -178,6 +178,44 @@ def test_block_small_variants(variant):
     _check_block(shape, si.lengths_to_cu(lens), seed=3)
 
 
+# ---- re-computation (Sec. 4.3): backward replays the forward into a scratch `saved` -----------
+
+@pytest.mark.parametrize("variant", ["config1", "llm-like"])
+def test_block_bwd_with_recompute_is_bit_identical(variant):
+    if variant == "config1":
+        shape, lens = si.CONFIGS[1], si.tiny_segment_lengths(seed=0)
+    else:
+        shape = si.small_shape(hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, mlp_dim=320,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
+                               use_rotary=True, has_bias=False, norm_eps=1e-6)
+        lens = [300, 1, 140, 259]
+    cu = si.lengths_to_cu(lens)
+    T = int(cu[-1])
+    _say(f"recompute {variant}: T={T}")
+    w = si.block_weights(shape, seed=1)
+    x_np, dy_np = si.activations(T, shape.hidden, seed=1)
+    seg = ob.Segments(cu)
+    run = BlockRun(shape, w, T)
+    x, dy = to_dev(x_np), to_dev(dy_np)
+    run.fwd(x, seg)
+    dx_ref = run.bwd(x, dy, seg)
+    g_ref = {n: t.clone() for n, t in run.g.items()}
+    # poison the saved buffer (as if another block had used it), then let the backward replay
+    run.saved.fill_(0xFF)
+    for t in run.g.values():
+        t.zero_()
+    dx = torch.empty_like(x)
+    ob.ob_block_bwd(run.desc, run.w, run.g, ob.OB_BWD_RECOMPUTE, x, dy, dx, run.saved, seg, run.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dx.view(torch.int16), dx_ref.view(torch.int16))
+    for n in g_ref:
+        assert torch.equal(run.g[n].view(torch.int16), g_ref[n].view(torch.int16)), n
+    # and it still matches the oracle
+    y_ref, cache = orc.block_fwd(shape, w, x_np, cu)
+    dx_o, _, _ = orc.block_bwd(shape, w, cache, dy_np, cu)
+    assert rel_err(to_np(dx), dx_o) < TOL
+
+
 # ---- fp32 debug path: same entry points, dtype = OB_FP32, tolerance 1e-4 ----------------------
 
 @pytest.mark.parametrize("lens,nq,nkv,d,mask", ATTN_CASES[:3] + [([257, 130], 3, 3, 128, orc.MASK_BIDIR)])

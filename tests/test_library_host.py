@@ -169,3 +169,68 @@ def test_gemm_argument_validation():
     for layout in (0, 1, 2):                      # all three layouts run without scratch
         assert ob.ob_gemm_workspace_bytes(layout, 128, 64, 128) == 0
     assert ob.lib.ob_debug_materialize_mask(C.byref(_seg([0, 4]).c), 1, None, None) == ob.OB_EINVAL
+
+
+# ---- grouping arms, partition search and re-computation plan: library == oracle ----------------
+
+@pytest.mark.parametrize("seed", [0, 4])
+def test_size_grouping_arms_equal_oracle(seed):
+    tiles, tok = si.synthetic_dataset(1234, seed)
+    for B in (1, 6, 50):
+        g, left = ob.ob_pack_length_group(tok, B, seed)
+        G, Left = op.length_groups(tok, B, seed)
+        assert [a.tolist() for a in g] == G and left.tolist() == Left
+        g, left = ob.ob_pack_device_group(tok, B, seed)
+        G, Left = op.device_groups(tok, B, seed)
+        assert [a.tolist() for a in g] == G and left.tolist() == Left
+    with pytest.raises(RuntimeError):
+        ob.ob_pack_length_group(tok, 0, seed)
+
+
+def test_bmp_anchor_and_search_equal_oracle():
+    import random
+    from oracle import planner as pl
+    rng = random.Random(5)
+    assert ob.ob_bmp_anchor([1.0] * 20, 4) == (6, 11, 16)
+    ranked, n = ob.ob_bmp_search([1.0] * 20, [0.0] * 20, 4, 1, top_k=100)
+    assert n == 27 and len(ranked) == 27                      # Sec. 4.2: r = 1, N = 4
+    for _ in range(40):
+        N = rng.randint(1, 5)
+        L = rng.randint(N, 30)
+        # integer-valued times and volumes: every score is exact in double, so ranks must agree exactly
+        fwd = [float(rng.randint(1, 40)) for _ in range(L)]
+        activ = [float(rng.randint(0, 9)) for _ in range(L)]
+        r, w, k = rng.randint(0, 3), rng.choice([0.0, 1.0, 4.0]), rng.randint(1, 20)
+        assert ob.ob_bmp_anchor(fwd, N) == pl.anchor(fwd, N)
+        got, n_got = ob.ob_bmp_search(fwd, activ, N, r, w, k)
+        want, n_want = pl.search(fwd, activ, N, r, w, k)
+        assert n_got == n_want and got == want
+    # real-valued profile: same candidates, scores equal to rounding
+    fwd = [rng.uniform(0.5, 3.0) for _ in range(40)]
+    activ = [rng.uniform(0.0, 2.0) for _ in range(40)]
+    got, n_got = ob.ob_bmp_search(fwd, activ, 4, 2, 1.0, 125)
+    want, n_want = pl.search(fwd, activ, 4, 2, 1.0, 125)
+    assert n_got == n_want and sorted(P for _, P in got) == sorted(P for _, P in want)
+    assert all(abs(a - b) <= 1e-9 * max(1.0, abs(b)) for (a, _), (b, _) in zip(got, want))
+    for bad in (lambda: ob.ob_bmp_anchor([1.0, 2.0], 3), lambda: ob.ob_bmp_anchor([1.0, -2.0], 2),
+                lambda: ob.ob_bmp_search([1.0] * 60, [0.0] * 60, 30, 3)):
+        with pytest.raises(RuntimeError):
+            bad()
+
+
+def test_recompute_plan_equals_oracle():
+    import random
+    from oracle import planner as pl
+    rng = random.Random(2)
+    for _ in range(300):
+        nv, nt = rng.randint(0, 8), rng.randint(0, 8)
+        bv, bt = rng.randint(1, 30), rng.randint(1, 30)
+        mv, mt = rng.choice([0.0, 1.0, 1.5, 2.0, 3.0]), rng.choice([0.0, 1.0, 1.5, 2.0, 3.0])
+        free, e = rng.randint(0, 300), rng.randint(0, 3)
+        assert ob.ob_recompute_plan(free, nv, bv, mv, nt, bt, mt, e) == pl.recompute_plan(free, nv, bv, mv, nt, bt, mt, e)
+    # with the library's own byte counts: 8 config-3 blocks into 10 GiB
+    desc = ob.make_desc(si.CONFIGS[3])
+    per_block = ob.ob_block_saved_bytes(desc, 16384)
+    assert ob.ob_recompute_plan(10 << 30, 0, 1, 0.0, 8, per_block, 5.0) == (0, min(8, (10 << 30) // per_block))
+    with pytest.raises(RuntimeError):
+        ob.ob_recompute_plan(-1, 1, 1, 1.0, 1, 1, 1.0)

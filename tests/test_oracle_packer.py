@@ -142,3 +142,37 @@ def test_random_groups():
     G, left = op.random_groups(10, 3, 1)
     assert len(G) == 3 and all(len(g) == 3 for g in G) and len(left) == 1
     assert sorted([i for g in G for i in g] + left) == list(range(10))
+
+
+# ---- the other grouping arms of Sec. 5.4 (readings: see the oracle's docstrings) ---------------
+
+def test_length_groups_are_runs_of_the_sorted_order():
+    tiles, tok = si.synthetic_dataset(1000, 5)
+    B = 7
+    groups, left = op.length_groups(tok, B, seed=3)
+    assert len(groups) == 1000 // B and len(left) == 1000 % B
+    assert sorted(sum(groups, []) + left) == list(range(1000))
+    spans = sorted((min(int(tok[i]) for i in g), max(int(tok[i]) for i in g)) for g in groups)
+    assert all(spans[k][1] <= spans[k + 1][0] for k in range(len(spans) - 1))   # runs do not interleave
+    # similar sizes inside a mini-batch: far less padding than random mini-batches of the same size
+    rgroups, _ = op.random_groups(1000, B, seed=3)
+    pad = lambda gs: sum(op.pad_ratio([int(tok[i]) for i in g]) for g in gs) / len(gs)
+    assert pad(groups) < 0.25 * pad(rgroups)
+    # but the mini-batches of one step differ in size more than the random arm's do
+    step = lambda gs: [sum(int(tok[i]) for i in g) for g in gs[:8]]
+    assert op.dist_ratio(step(groups)) > op.dist_ratio(step(rgroups))
+
+
+def test_device_groups_reorder_the_random_arm_by_total():
+    tiles, tok = si.synthetic_dataset(1000, 6)
+    B = 5
+    groups, left = op.device_groups(tok, B, seed=9)
+    rgroups, rleft = op.random_groups(1000, B, seed=9)
+    assert sorted(map(tuple, groups)) == sorted(map(tuple, rgroups)) and left == rleft
+    totals = [sum(int(tok[i]) for i in g) for g in groups]
+    assert totals == sorted(totals)
+    # consecutive mini-batches (one step's devices) are close in size; padding inside is untouched
+    d = [op.dist_ratio(totals[k:k + 8]) for k in range(0, len(totals) - 8, 8)]
+    rt = [sum(int(tok[i]) for i in g) for g in rgroups]
+    rd = [op.dist_ratio(rt[k:k + 8]) for k in range(0, len(rt) - 8, 8)]
+    assert sum(d) / len(d) < 0.2 * sum(rd) / len(rd)
