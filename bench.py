@@ -54,6 +54,125 @@ def measured_traffic(config, kernel):
     return None
 
 
+def packer_report(seed, n_dev=8):
+    """Grouping arms of Sec. 5.4 and the ISF studies of Sec. 5.2 / App. G on the synthetic dataset.
+    A step hands n_dev consecutive mini-batches to its devices; DistRatio (Eq. 2) is averaged over
+    the steps, PadRatio (Eq. 1) over the mini-batches (what padding to the longest sample would
+    cost; the ISF arm runs packed, so its PadRatio is 0 by construction)."""
+    import paper_2407_20761_amd as ob
+    import synth_inputs as si
+    tiles, tok = si.synthetic_dataset(20000, seed)
+    vis = tiles.astype(np.int64) * si.VIT_TILE_TOKENS
+    Qt = 16384
+    Qv = max(1, int(round(Qt * float(tiles.sum()) / float(tok.sum()))))
+
+    def ratios(groups, packed):
+        gs = groups[:len(groups) // n_dev * n_dev]
+        dv, dt = [], []
+        for k in range(0, len(gs), n_dev):
+            dv.append(ob.ob_dist_ratio([int(vis[g].sum()) for g in gs[k:k + n_dev]]))
+            dt.append(ob.ob_dist_ratio([int(tok[g].sum()) for g in gs[k:k + n_dev]]))
+        pad = 0.0 if packed else float(np.mean([ob.ob_pad_ratio(tok[g].astype(np.int64)) for g in gs]))
+        return {"mini_batches": len(gs), "pad_ratio": pad, "dist_ratio_vit": float(np.mean(dv)),
+                "dist_ratio_llm": float(np.mean(dt))}
+
+    def isf(qv, qt, qvm, qtm, iters):
+        t0 = time.perf_counter()
+        groups, left, _ = ob.ob_pack_isf(tiles, tok, qv, qt, qvm, qtm, iters, seed)
+        ms = (time.perf_counter() - t0) * 1e3
+        r = ratios(groups, True)
+        r.update(leftover=int(len(left)), ms=ms)
+        if len(left):
+            # the whole dataset: what is left after the last iteration is grouped by one more sampling
+            # pass that keeps every candidate (filter thresholds 0), then shuffled in among the rest
+            more, _, _ = ob.ob_pack_isf(tiles[left], tok[left], qv, qt, 0, 0, 1, seed)
+            everything = groups + [left[g] for g in more]
+            order = np.random.default_rng(seed).permutation(len(everything))
+            whole = ratios([everything[i] for i in order], True)
+            r.update(dist_ratio_vit_all_samples=whole["dist_ratio_vit"],
+                     dist_ratio_llm_all_samples=whole["dist_ratio_llm"])
+        return r
+
+    full = isf(Qv, Qt, Qv, Qt - 128, 10)
+    B = max(1, 20000 // max(full["mini_batches"], 1))
+    arms = {"random": ratios(ob.ob_pack_random(len(tok), B, seed)[0], False),
+            "length_group": ratios(ob.ob_pack_length_group(tok, B, seed)[0], False),
+            "device_group": ratios(ob.ob_pack_device_group(tok, B, seed)[0], False),
+            "isf": full}
+    return {"report": "packer", "samples": 20000, "seed": seed, "devices_per_step": n_dev, "Qv": Qv, "Qt": Qt,
+            "samples_per_mini_batch_of_the_fixed_size_arms": B, "arms": arms,
+            "isf_convergence": {str(t): isf(Qv, Qt, Qv, Qt - 128, t) for t in range(1, 11)},
+            "q_ablation": {"Qv, Qt-64": isf(Qv, Qt, Qv, Qt - 64, 10), "Qv, Qt-128": full,
+                           "Qv, Qt-256": isf(Qv, Qt, Qv, Qt - 256, 10),
+                           "Qv-1, Qt-128": isf(Qv, Qt, Qv - 1, Qt - 128, 10)},
+            "context": "paper, InternVL-Chat-1.2 data (Table 3 / Table 5): random arm PadRatio 0.31, DistRatio "
+                       "0.34 / 0.30; ISF PadRatio 0, DistRatio 0.02 / 0.14; other data, context only"}
+
+
+def bmp_report(seed, n_stages=8, radius=2, top_k=10):
+    """Balanced model partitioning (Sec. 4.2) of a 45-layer ViT-6B-shaped + 48-layer LLM-20B-shaped
+    stack: per-layer forward times measured here (one block of config 4 on 16 tiles, one block of
+    config 5 on the matching LLM-side batch), ACTIV = bytes of the layer output (the last ViT layer's
+    output is sub-sampled 4x before it is sent), volumes weighted by a per-byte link time."""
+    import torch
+    import paper_2407_20761_amd as ob
+    import synth_inputs as si
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+
+    def block_fwd_ms(cfg, cu):
+        shape = si.CONFIGS[cfg]
+        desc = ob.make_desc(shape)
+        T = int(cu[-1])
+        w = {}
+        for name, shp in si.weight_shapes(shape).items():
+            t = torch.randn(shp, generator=gen, device=dev, dtype=torch.float32) * 0.02
+            w[name] = (t + 1.0 if name in ("n1_g", "n2_g") else t).to(torch.bfloat16)
+        x = (torch.randn((T, shape.hidden), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+        y = torch.empty_like(x)
+        saved = torch.empty(ob.ob_block_saved_bytes(desc, T), dtype=torch.uint8, device=dev)
+        ws = torch.empty(ob.ob_block_workspace_bytes(desc, T), dtype=torch.uint8, device=dev)
+        seg = ob.Segments(cu, device=dev)
+        for _ in range(3):
+            ob.ob_block_fwd(desc, w, x, y, saved, seg, ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            ob.ob_block_fwd(desc, w, x, y, saved, seg, ws)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / 10, T, shape.hidden
+
+    n_tiles = 16
+    vit_ms, Tv, Hv = block_fwd_ms(4, ob.ob_build_cu_seqlens_vit(n_tiles, si.VIT_TILE_TOKENS))
+    # the same mini-batch on the LLM side: 256 visual tokens per tile plus text, four samples
+    lens = np.array([4 * 256 + 1100, 5 * 256 + 300, 3 * 256 + 2000, 4 * 256 + 596], dtype=np.int32)
+    llm_ms, Tt, Ht = block_fwd_ms(5, si.lengths_to_cu(lens))
+    n_vit, n_llm = 45, 48
+    fwd = [vit_ms] * n_vit + [llm_ms] * n_llm
+    activ_mb = [Tv * Hv * 2 / 1e6] * (n_vit - 1) + [Tv // 4 * Hv * 2 / 1e6] + [Tt * Ht * 2 / 1e6] * n_llm
+    ms_per_mb = 1.0 / 153.0          # one xGMI link, 153 GB/s
+    anchor = ob.ob_bmp_anchor(fwd, n_stages)
+    ranked, n_cand = ob.ob_bmp_search(fwd, activ_mb, n_stages, radius, ms_per_mb, top_k)
+
+    def describe(P):
+        cuts = [1] + list(P) + [len(fwd) + 1]
+        t = [sum(fwd[cuts[i] - 1:cuts[i + 1] - 1]) for i in range(n_stages)]
+        return {"P": list(P), "layers_per_stage": [cuts[i + 1] - cuts[i] for i in range(n_stages)],
+                "max_stage_fwd_ms": max(t), "min_stage_fwd_ms": min(t)}
+
+    even = tuple(1 + round((i + 1) * len(fwd) / n_stages) for i in range(n_stages - 1))
+    return {"report": "bmp", "layers": {"vit": n_vit, "llm": n_llm}, "stages": n_stages, "radius": radius,
+            "fwd_ms_per_layer": {"vit": vit_ms, "llm": llm_ms}, "tokens": {"vit": Tv, "llm": Tt},
+            "activation_mb": {"vit": activ_mb[0], "vit_last_subsampled": activ_mb[n_vit - 1], "llm": activ_mb[-1]},
+            "comm_ms_per_mb": ms_per_mb, "candidates": n_cand, "anchor": describe(anchor),
+            "layer_count_split": describe(even),
+            "top": [dict(describe(P), score=sc) for sc, P in ranked],
+            "note": "ranking only (Eq. 4 + Eq. 5); timing the top candidates in a real pipeline (Eq. 3) needs "
+                    "more than one GPU and is not part of this build"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +182,11 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--spread-batches", type=int, default=50)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--report", choices=["packer", "bmp"], default=None,
+                    help="instead of the step benchmark print one JSON line of a host-side report: "
+                         "'packer' = grouping arms, ISF convergence and Q' ablation on the synthetic "
+                         "dataset (no GPU needed); 'bmp' = model-partition search fed by measured "
+                         "per-block forward times")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="before the warm-up, copy this many MiB device-to-device three times: a "
                          "kernel of known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -71,6 +195,13 @@ def main():
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
               "--gpus N with N > 1 is not supported", file=sys.stderr)
         sys.exit(2)
+
+    if args.report == "packer":
+        print(json.dumps(packer_report(args.seed)))
+        return
+    if args.report == "bmp":
+        print(json.dumps(bmp_report(args.seed)))
+        return
 
     import torch
 
