@@ -194,3 +194,39 @@ def qkv_tensors(total_tokens: int, nq: int, nkv: int, d: int, seed: int = 0, std
     mk = lambda n: round_to_bf16(rng.standard_normal((total_tokens, n, d), dtype=np.float32)
                                  * np.float32(std))
     return mk(nq), mk(nkv), mk(nkv), mk(nq)
+
+
+# ----------------------------------------------------------------------------------------------
+# ViT -> LLM hand-over (sub-sampling + connector): weights and the visual rows of a packed batch
+# ----------------------------------------------------------------------------------------------
+
+CONNECTOR_NAMES = ("n_g", "n_b", "w1", "b1", "w2", "b2")
+
+
+def connector_weights(vit_hidden: int, llm_hidden: int, seed: int = 0, std: float = 0.02) -> dict:
+    """bf16-representable float32 weights: LayerNorm gain 1 + N(0, std^2) and beta over 4 Hv
+    channels, W1 [Ht, 4 Hv], W2 [Ht, Ht], biases."""
+    rng = np.random.default_rng([seed, 0xC0EC])
+    W = 4 * vit_hidden
+    shapes = {"n_g": (W,), "n_b": (W,), "w1": (llm_hidden, W), "b1": (llm_hidden,),
+              "w2": (llm_hidden, llm_hidden), "b2": (llm_hidden,)}
+    w = {}
+    for name, shp in shapes.items():
+        a = rng.standard_normal(shp, dtype=np.float32) * np.float32(std)
+        if name == "n_g":
+            a = a + np.float32(1.0)
+        w[name] = round_to_bf16(a)
+    return w
+
+
+def visual_rows(tiles_per_sample, text_per_sample, tokens_per_tile: int = LLM_TOKENS_PER_TILE):
+    """Rows of the packed LLM batch that hold visual tokens: each sample is laid out as its
+    tiles' visual tokens followed by its text tokens.  Returns (dst_rows int32 [sum tiles *
+    tokens_per_tile], cu int32 [n_samples + 1])."""
+    rows, cu, pos = [], [0], 0
+    for nt, tx in zip(tiles_per_sample, text_per_sample):
+        nv = int(nt) * tokens_per_tile
+        rows.append(np.arange(pos, pos + nv, dtype=np.int32))
+        pos += nv + int(tx)
+        cu.append(pos)
+    return np.concatenate(rows) if rows else np.zeros(0, np.int32), np.asarray(cu, dtype=np.int32)
