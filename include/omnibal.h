@@ -154,6 +154,41 @@ size_t ob_gemm_workspace_bytes(int layout, int M, int N, int K);
 int ob_gemm_bf16(int layout, int M, int N, int K, const void *A, const void *B, void *C,
                  const void *bias, const void *R, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* ---- ViT -> LLM hand-over of a mixed stage (App. A; the "token sub-sampling" of Sec. 5.4) ------
+ * The paper names the step but fixes neither it nor the connector; what runs here is
+ *   c1  per tile of grid*grid + 1 ViT rows (class token first, patches row-major): drop the class
+ *       token; sub-sampled token (r, c), r, c < grid/2, is the channel-wise concatenation of the
+ *       patches (2r + dr, 2c + dc), channel block 2 dr + dc   -> [n_tok, 4 Hv], n_tok = n_tiles grid^2/4
+ *   c2  LayerNorm over the 4 Hv channels (n_g, n_b)
+ *   c3  h = un W1^T + b1,  a = GELU(h)            w1 [Ht, 4 Hv]
+ *   c4  z = a W2^T + b2                            w2 [Ht, Ht]
+ *   c5  row i of z is written to row dst_rows[i] of x_llm [llm_tokens, Ht]; other rows (text) are
+ *       left as the caller filled them.
+ * dst_rows (int32, n_tok entries, host and device copies like cu_seqlens) must be distinct and
+ * inside [0, llm_tokens): checked on the host.  bf16 only (dtype OB_BF16); vit_hidden and
+ * llm_hidden multiples of 64, 4 vit_hidden <= 16384, grid even.
+ * ob_connector_bwd: given dx_llm [llm_tokens, Ht] it reads the rows dst_rows, writes every row of
+ * dv [n_tiles (grid^2 + 1), Hv] (class rows: zeros) and all six weight gradients (flags:
+ * OB_BWD_ACCUMULATE only).  `saved` carries un, h, a and the row statistics from the forward. */
+typedef struct {
+    int vit_hidden, llm_hidden, grid;
+    int dtype;         /* ob_dtype, OB_BF16 */
+    float norm_eps;
+} ob_connector_desc;
+typedef struct { const void *n_g, *n_b, *w1, *b1, *w2, *b2; } ob_connector_weights;
+typedef struct { void *n_g, *n_b, *w1, *b1, *w2, *b2; } ob_connector_grads;
+size_t ob_connector_saved_bytes(const ob_connector_desc *desc, int n_tiles);
+size_t ob_connector_workspace_bytes(const ob_connector_desc *desc, int n_tiles);
+int ob_connector_fwd(const ob_connector_desc *desc, const ob_connector_weights *w, const void *v,
+                     int n_tiles, const int32_t *dst_rows_host, const int32_t *dst_rows_dev,
+                     void *x_llm, int llm_tokens, void *saved, size_t saved_bytes, void *ws,
+                     size_t ws_bytes, void *hip_stream);
+int ob_connector_bwd(const ob_connector_desc *desc, const ob_connector_weights *w,
+                     const ob_connector_grads *g, int flags, const void *v, const void *dx_llm,
+                     void *dv, int n_tiles, const int32_t *dst_rows_host,
+                     const int32_t *dst_rows_dev, int llm_tokens, const void *saved,
+                     size_t saved_bytes, void *ws, size_t ws_bytes, void *hip_stream);
+
 /* T x T byte mask (1 = allowed) written by the same segment/causal predicate the attention
  * kernels use; for bit-exact mask tests, T <= 4096. */
 int ob_debug_materialize_mask(const ob_segments *seg, int mask, uint8_t *mask_dev, void *hip_stream);

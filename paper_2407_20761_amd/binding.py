@@ -51,6 +51,22 @@ class ob_segments(C.Structure):
                 ("total_tokens", C.c_int), ("max_seqlen", C.c_int)]
 
 
+CONNECTOR_FIELDS = ("n_g", "n_b", "w1", "b1", "w2", "b2")
+
+
+class ob_connector_desc(C.Structure):
+    _fields_ = [("vit_hidden", C.c_int), ("llm_hidden", C.c_int), ("grid", C.c_int), ("dtype", C.c_int),
+                ("norm_eps", C.c_float)]
+
+
+class ob_connector_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in CONNECTOR_FIELDS]
+
+
+class ob_connector_grads(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in CONNECTOR_FIELDS]
+
+
 class OmnibalError(RuntimeError):
     def __init__(self, status, text):
         super().__init__(f"omnibal status {status}: {text}")
@@ -86,6 +102,13 @@ _SIGNATURES = {
     "ob_gemm_workspace_bytes": (_Z, [_I, _I, _I, _I]),
     "ob_gemm_bf16": (_I, [_I, _I, _I, _I, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "ob_debug_materialize_mask": (_I, [_SEG, _I, _P, _P]),
+    "ob_connector_saved_bytes": (_Z, [C.POINTER(ob_connector_desc), _I]),
+    "ob_connector_workspace_bytes": (_Z, [C.POINTER(ob_connector_desc), _I]),
+    "ob_connector_fwd": (_I, [C.POINTER(ob_connector_desc), C.POINTER(ob_connector_weights), _P, _I, _i32p, _P,
+                              _P, _I, _P, _Z, _P, _Z, _P]),
+    "ob_connector_bwd": (_I, [C.POINTER(ob_connector_desc), C.POINTER(ob_connector_weights),
+                              C.POINTER(ob_connector_grads), _I, _P, _P, _P, _I, _i32p, _P, _I, _P, _Z, _P, _Z,
+                              _P]),
     "ob_pack_isf": (_I, [_i32p, _i32p, C.c_int64, C.c_int64, C.c_int64, C.c_int64, C.c_int64, _I,
                          C.c_uint64, _i64p, _i64p, _i64p, _i64p, _i64p, _i64p]),
     "ob_pack_random": (_I, [C.c_int64, C.c_int64, C.c_uint64, _i64p, _i64p, _i64p, _i64p, _i64p]),
@@ -229,6 +252,55 @@ def ob_gemm_bf16(layout, M, N, K, A, B, Cout, bias=None, R=None, ws=None, stream
     _check(lib.ob_gemm_bf16(layout, M, N, K, _ptr(A), _ptr(B), _ptr(Cout), _ptr(bias), _ptr(R),
                             _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                             _stream(stream)))
+
+
+class RowIndex:
+    """Host and device copies of an int32 row list (the visual rows of a packed LLM batch)."""
+
+    def __init__(self, rows_host, device="cuda"):
+        self.host = np.ascontiguousarray(rows_host, dtype=np.int32)
+        self.dev = torch.from_numpy(self.host).to(device) if device else None
+
+    @property
+    def host_ptr(self):
+        return self.host.ctypes.data_as(_i32p)
+
+
+def make_connector_desc(vit_hidden, llm_hidden, grid=32, norm_eps=1e-5, dtype=OB_BF16) -> ob_connector_desc:
+    return ob_connector_desc(int(vit_hidden), int(llm_hidden), int(grid), dtype, float(norm_eps))
+
+
+def _connector_struct(cls, tensors: dict):
+    return cls(*[None if tensors.get(n) is None else tensors[n].data_ptr() for n in CONNECTOR_FIELDS])
+
+
+def _nbytes(t):
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def ob_connector_saved_bytes(desc, n_tiles) -> int:
+    return lib.ob_connector_saved_bytes(C.byref(desc), n_tiles)
+
+
+def ob_connector_workspace_bytes(desc, n_tiles) -> int:
+    return lib.ob_connector_workspace_bytes(C.byref(desc), n_tiles)
+
+
+def ob_connector_fwd(desc, weights: dict, v, n_tiles, dst_rows: RowIndex, x_llm, llm_tokens, saved, ws,
+                     stream=None):
+    w = _connector_struct(ob_connector_weights, weights)
+    _check(lib.ob_connector_fwd(C.byref(desc), C.byref(w), _ptr(v), n_tiles, dst_rows.host_ptr,
+                                _ptr(dst_rows.dev), _ptr(x_llm), llm_tokens, _ptr(saved), _nbytes(saved),
+                                _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ob_connector_bwd(desc, weights: dict, grads: dict, flags, v, dx_llm, dv, n_tiles, dst_rows: RowIndex,
+                     llm_tokens, saved, ws, stream=None):
+    w = _connector_struct(ob_connector_weights, weights)
+    g = _connector_struct(ob_connector_grads, grads)
+    _check(lib.ob_connector_bwd(C.byref(desc), C.byref(w), C.byref(g), int(flags), _ptr(v), _ptr(dx_llm),
+                                _ptr(dv), n_tiles, dst_rows.host_ptr, _ptr(dst_rows.dev), llm_tokens,
+                                _ptr(saved), _nbytes(saved), _ptr(ws), _nbytes(ws), _stream(stream)))
 
 
 def ob_debug_materialize_mask(seg: Segments, mask, out, stream=None):

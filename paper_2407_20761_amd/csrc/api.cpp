@@ -38,7 +38,8 @@ struct ProfState {
 ProfState g_prof;
 const char *const kClassNames[K_COUNT] = {
     "gemm", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "attn_delta", "norm_fwd",
-    "norm_bwd", "rotary", "act_fwd", "act_bwd", "colsum", "reduce_partials"};
+    "norm_bwd", "rotary", "act_fwd", "act_bwd", "colsum", "reduce_partials",
+    "subsample_norm_fwd", "subsample_norm_bwd", "rows_copy"};
 }  // namespace
 
 ProfScope::ProfScope(int c, hipStream_t s, double work) : slot(-1), stream(s) {

@@ -17,7 +17,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // ---- opt-in per-kernel-class timing (ob_prof_begin / ob_prof_end) --------------------------
 enum KClass {
     K_GEMM = 0, K_ATTN_FWD, K_ATTN_BWD_DQ, K_ATTN_BWD_DKV, K_ATTN_DELTA, K_NORM_FWD,
-    K_NORM_BWD, K_ROTARY, K_ACT_FWD, K_ACT_BWD, K_COLSUM, K_REDUCE, K_COUNT
+    K_NORM_BWD, K_ROTARY, K_ACT_FWD, K_ACT_BWD, K_COLSUM, K_REDUCE, K_CONN_FWD, K_CONN_BWD, K_ROWS, K_COUNT
 };
 // Brackets one kernel launch with a pair of events on its stream while profiling is on;
 // `work` is the launch's algorithmic FLOPs (MFMA kernels) or bytes (HBM-bound kernels).
@@ -60,6 +60,22 @@ void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T,
 void launch_attn_delta(const void *d_o, const void *o, int ldo, const float *lse, float *delta,
                        float *lse2, int T, int nq, int d, hipStream_t s);
 void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out, hipStream_t s);
+
+// ---- ViT -> LLM hand-over (connector.hip) ------------------------------------------------------
+// n_tok = n_tiles * (g/2)^2 sub-sampled tokens of 4 Hv channels; stats [n_tok, 2] = (mean, rstd)
+int subsample_max_width();
+void launch_subsample_norm_fwd(const void *v, const void *gamma, const void *beta, void *un, float *stats,
+                               int n_tok, int g, int Hv, float eps, hipStream_t s);
+// writes every row of dv [n_tiles (g^2 + 1), Hv] (class rows: zeros)
+void launch_subsample_norm_bwd(const void *dun, const void *v, const float *stats, const void *gamma, void *dv,
+                               int n_tok, int n_tiles, int g, int Hv, hipStream_t s);
+// partial [subsample_wgrad_partials(n_tok)][2][4 Hv] fp32: gain sums, then beta sums
+int subsample_wgrad_partials(int n_tok);
+void launch_subsample_norm_wgrad(const void *dun, const void *v, const float *stats, float *partial, int n_tok,
+                                 int g, int Hv, hipStream_t s);
+// big[rows[i]] = small[i]  /  small[i] = big[rows[i]];  rows of H bf16 elements, H % 8 == 0
+void launch_rows_scatter(const void *small, void *big, const int32_t *rows_dev, int n_rows, int H, hipStream_t s);
+void launch_rows_gather(void *small, const void *big, const int32_t *rows_dev, int n_rows, int H, hipStream_t s);
 
 // ---- attention (attention.hip) ---------------------------------------------------------------
 void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int ldq,

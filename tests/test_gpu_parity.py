@@ -336,3 +336,59 @@ def test_config3_full_batch_one_segment_against_oracle():
     outside = np.ones(T, bool)
     outside[a:b] = False
     assert np.abs(dx[outside]).max() == 0.0
+
+
+# ---- ViT -> LLM hand-over: sub-sampling + connector ---------------------------------------------
+
+CONNECTOR_CASES = [
+    # Hv, Ht, grid, tiles per sample, text tokens per sample
+    (128, 256, 8, [2, 1], [5, 0]),
+    (1024, 4096, 32, [1, 1], [37, 300]),       # the 300M-class encoder into the 7B-class decoder
+    (3200, 6144, 32, [1], [129]),              # the 6B-class encoder into the 20B-class decoder
+]
+
+
+@pytest.mark.parametrize("Hv,Ht,grid,tiles,text", CONNECTOR_CASES)
+def test_connector_fwd_bwd(Hv, Ht, grid, tiles, text):
+    from oracle import connector as orc_conn
+    _say(f"connector Hv={Hv} Ht={Ht} grid={grid} tiles={tiles} text={text}")
+    n_tiles, per_tile = sum(tiles), grid * grid // 4
+    w_np = si.connector_weights(Hv, Ht, seed=Hv + Ht)
+    dst, cu = si.visual_rows(tiles, text, tokens_per_tile=per_tile)
+    T = int(cu[-1])
+    v_np, _ = si.activations(n_tiles * (grid * grid + 1), Hv, seed=1, std=1.0)
+    x_np, dx_np = si.activations(T, Ht, seed=2, std=1.0)
+    eps = 1e-5
+
+    ref_out, cache = orc_conn.connector_fwd(w_np, v_np, n_tiles, grid, eps, x_np, dst)
+    ref_dv, ref_g = orc_conn.connector_bwd(w_np, cache, dx_np, n_tiles, grid, eps, dst)
+
+    desc = ob.make_connector_desc(Hv, Ht, grid, eps)
+    w = {n: to_dev(a) for n, a in w_np.items()}
+    g = {n: torch.zeros_like(t) for n, t in w.items()}
+    saved = bytes_buf(ob.ob_connector_saved_bytes(desc, n_tiles))
+    ws = bytes_buf(ob.ob_connector_workspace_bytes(desc, n_tiles))
+    rows = ob.RowIndex(dst)
+    v, x_llm, dx_llm = to_dev(v_np), to_dev(x_np), to_dev(dx_np)
+    dv = torch.full((n_tiles * (grid * grid + 1), Hv), 7.0, dtype=torch.bfloat16, device="cuda")
+    ob.ob_connector_fwd(desc, w, v, n_tiles, rows, x_llm, T, saved, ws)
+    ob.ob_connector_bwd(desc, w, g, 0, v, dx_llm, dv, n_tiles, rows, T, saved, ws)
+    torch.cuda.synchronize()
+
+    out = to_np(x_llm)
+    text_rows = np.setdiff1d(np.arange(T), dst)
+    np.testing.assert_array_equal(out[text_rows], x_np[text_rows].astype(np.float64))   # untouched, bit for bit
+    assert rel_err(out[dst], ref_out[dst]) < TOL
+    dv_np = to_np(dv)
+    cls = np.arange(n_tiles) * (grid * grid + 1)
+    assert not dv_np[cls].any()                                                         # class rows: exact zeros
+    assert rel_err(dv_np, ref_dv) < TOL
+    for n in si.CONNECTOR_NAMES:
+        assert rel_err(to_np(g[n]), ref_g[n]) < TOL, n
+
+    # a second backward with the accumulate flag doubles every weight gradient (up to bf16 rounding)
+    first = {n: to_np(t) for n, t in g.items()}
+    ob.ob_connector_bwd(desc, w, g, ob.OB_BWD_ACCUMULATE, v, dx_llm, dv, n_tiles, rows, T, saved, ws)
+    torch.cuda.synchronize()
+    for n in si.CONNECTOR_NAMES:
+        assert rel_err(to_np(g[n]), 2 * first[n]) < 1e-2, n

@@ -234,3 +234,50 @@ def test_recompute_plan_equals_oracle():
     assert ob.ob_recompute_plan(10 << 30, 0, 1, 0.0, 8, per_block, 5.0) == (0, min(8, (10 << 30) // per_block))
     with pytest.raises(RuntimeError):
         ob.ob_recompute_plan(-1, 1, 1, 1.0, 1, 1, 1.0)
+
+
+# ---- ViT -> LLM hand-over: validation happens on the host, before anything is launched ---------
+
+def test_connector_argument_validation_and_sizes():
+    d = ob.make_connector_desc(128, 256, grid=4)
+    n_tiles, n_tok = 3, 3 * 4
+    sv, wk = ob.ob_connector_saved_bytes(d, n_tiles), ob.ob_connector_workspace_bytes(d, n_tiles)
+    # un [n_tok, 4 Hv] + h, a [n_tok, Ht] bf16 + (mean, rstd) per token, each member padded to 256 bytes
+    pad = lambda b: (b + 255) // 256 * 256
+    assert sv == pad(n_tok * 512 * 2) + 2 * pad(n_tok * 256 * 2) + pad(n_tok * 8)
+    assert wk >= pad(n_tok * 512 * 2) + 3 * pad(n_tok * 256 * 2)
+    for bad in (ob.make_connector_desc(100, 256, 4), ob.make_connector_desc(128, 250, 4),
+                ob.make_connector_desc(4160, 256, 4), ob.make_connector_desc(128, 256, 4, dtype=ob.OB_FP32)):
+        assert ob.ob_connector_saved_bytes(bad, n_tiles) == 0
+    assert ob.ob_connector_saved_bytes(ob.make_connector_desc(128, 256, 5), n_tiles) == 0     # odd grid
+    assert ob.ob_connector_saved_bytes(d, 0) == 0
+
+    # pointer and row-list checks need no device: fake non-null addresses are never dereferenced
+    class Fake:
+        def __init__(self, n=1 << 30): self.n = n
+        def data_ptr(self): return 0x1000
+        def numel(self): return self.n
+        def element_size(self): return 1
+    w = {n: Fake() for n in ob.CONNECTOR_FIELDS}
+    rows = ob.RowIndex(np.arange(n_tok), device=None)
+    rows.dev = Fake()
+    call = lambda **kw: ob.ob_connector_fwd(kw.get("d", d), kw.get("w", w), Fake(), n_tiles, kw.get("rows", rows),
+                                            Fake(), kw.get("T", 40), kw.get("saved", Fake()), kw.get("ws", Fake()),
+                                            stream=type("S", (), {"cuda_stream": 0})())
+    def status(**kw):
+        with pytest.raises(ob.OmnibalError) as e:
+            call(**kw)
+        return e.value.status
+    assert status(w={**w, "b2": None}) == ob.OB_EINVAL
+    assert status(T=n_tok - 1) == ob.OB_EINVAL                       # fewer LLM rows than visual tokens
+    dup = ob.RowIndex(np.r_[np.arange(n_tok - 1), 0], device=None); dup.dev = Fake()
+    assert status(rows=dup) == ob.OB_EINVAL and "twice" in ob.ob_last_error()
+    far = ob.RowIndex(np.r_[np.arange(n_tok - 1), 40], device=None); far.dev = Fake()
+    assert status(rows=far) == ob.OB_EINVAL and "outside" in ob.ob_last_error()
+    assert status(saved=Fake(sv - 1)) == ob.OB_EWORKSPACE
+    assert status(ws=Fake(wk - 1)) == ob.OB_EWORKSPACE
+    bwd = lambda flags: ob.ob_connector_bwd(d, w, w, flags, Fake(), Fake(), Fake(), n_tiles, rows, 40, Fake(), Fake(),
+                                            stream=type("S", (), {"cuda_stream": 0})())
+    with pytest.raises(ob.OmnibalError) as e:
+        bwd(ob.OB_BWD_RECOMPUTE)
+    assert e.value.status == ob.OB_EINVAL
