@@ -173,6 +173,116 @@ def bmp_report(seed, n_stages=8, radius=2, top_k=10):
                     "more than one GPU and is not part of this build"}
 
 
+def mixed_report(seed, n_vit=4, n_llm=4, steps=3):
+    """One mixed pipeline stage (App. A) on one balanced mini-batch: the last n_vit blocks of the
+    6B-shaped ViT (config 4), the token sub-sampling + connector, the first n_llm blocks of the
+    20B-shaped LLM (config 5); forward through all three, then backward through all three."""
+    import torch
+    import paper_2407_20761_amd as ob
+    import synth_inputs as si
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    vs, ts = si.CONFIGS[4], si.CONFIGS[5]
+    vdesc, tdesc = ob.make_desc(vs), ob.make_desc(ts)
+    cdesc = ob.make_connector_desc(vs.hidden, ts.hidden, 32, 1e-5)
+    tiles, tok = si.synthetic_dataset(20000, seed)
+    Qv, Qt = 96, ts.budget
+    groups, _, _ = ob.ob_pack_isf(tiles, tok, Qv, Qt, Qv - 8, Qt - 128, 10, seed)
+    groups = groups[:steps + 1]
+
+    def rand_w(shapes, gains):
+        w = {}
+        for name, shp in shapes.items():
+            t = torch.randn(shp, generator=gen, device=dev, dtype=torch.float32) * 0.02
+            w[name] = (t + 1.0 if name in gains else t).to(torch.bfloat16)
+        return w
+
+    vw = [rand_w(si.weight_shapes(vs), ("n1_g", "n2_g")) for _ in range(n_vit)]
+    tw = [rand_w(si.weight_shapes(ts), ("n1_g", "n2_g")) for _ in range(n_llm)]
+    W = 4 * vs.hidden
+    cw = rand_w({"n_g": (W,), "n_b": (W,), "w1": (ts.hidden, W), "b1": (ts.hidden,),
+                 "w2": (ts.hidden, ts.hidden), "b2": (ts.hidden,)}, ("n_g",))
+    zeros = lambda w: {n: torch.zeros_like(t) for n, t in w.items()}
+    vg, tg, cg = [zeros(w) for w in vw], [zeros(w) for w in tw], zeros(cw)
+    max_tiles = max(int(tiles[g].sum()) for g in groups)
+    Tv_max, Tt_max = max_tiles * si.VIT_TILE_TOKENS, max(int(tok[g].sum()) for g in groups)
+    buf = lambda n: torch.empty(max(int(n), 256), dtype=torch.uint8, device=dev)
+    vact = [torch.empty((Tv_max, vs.hidden), dtype=torch.bfloat16, device=dev) for _ in range(n_vit + 1)]
+    tact = [torch.empty((Tt_max, ts.hidden), dtype=torch.bfloat16, device=dev) for _ in range(n_llm + 1)]
+    vact[0].copy_((torch.randn((Tv_max, vs.hidden), generator=gen, device=dev) * 0.02).to(torch.bfloat16))
+    text_embed = (torch.randn((Tt_max, ts.hidden), generator=gen, device=dev) * 0.02).to(torch.bfloat16)
+    dy = torch.randn((Tt_max, ts.hidden), generator=gen, device=dev).to(torch.bfloat16)
+    vgb = [torch.empty((Tv_max, vs.hidden), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    tgb = [torch.empty((Tt_max, ts.hidden), dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    vsaved = [buf(ob.ob_block_saved_bytes(vdesc, Tv_max)) for _ in range(n_vit)]
+    tsaved = [buf(ob.ob_block_saved_bytes(tdesc, Tt_max)) for _ in range(n_llm)]
+    csaved = buf(ob.ob_connector_saved_bytes(cdesc, max_tiles))
+    ws = buf(max(ob.ob_block_workspace_bytes(vdesc, Tv_max), ob.ob_block_workspace_bytes(tdesc, Tt_max),
+                 ob.ob_connector_workspace_bytes(cdesc, max_tiles)))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(7)]
+
+    def step(group):
+        nt = int(tiles[group].sum())
+        vseg = ob.Segments(ob.ob_build_cu_seqlens_vit(nt, si.VIT_TILE_TOKENS), device=dev)
+        cu_t = ob.ob_build_cu_seqlens_llm(group, tok)[0]
+        tseg = ob.Segments(cu_t, device=dev)
+        dst, _ = si.visual_rows(tiles[group], tok[group] - si.LLM_TOKENS_PER_TILE * tiles[group])
+        rows = ob.RowIndex(dst, device=dev)
+        Tv, Tt = nt * si.VIT_TILE_TOKENS, int(cu_t[-1])
+        ev[0].record()
+        for i in range(n_vit):
+            ob.ob_block_fwd(vdesc, vw[i], vact[i][:Tv], vact[i + 1][:Tv], vsaved[i], vseg, ws)
+        ev[1].record()
+        tact[0][:Tt].copy_(text_embed[:Tt])          # the text rows; the visual rows are overwritten next
+        ob.ob_connector_fwd(cdesc, cw, vact[n_vit][:Tv], nt, rows, tact[0][:Tt], Tt, csaved, ws)
+        ev[2].record()
+        for i in range(n_llm):
+            ob.ob_block_fwd(tdesc, tw[i], tact[i][:Tt], tact[i + 1][:Tt], tsaved[i], tseg, ws)
+        ev[3].record()
+        g_in = dy[:Tt]
+        for i in reversed(range(n_llm)):
+            g_out = tgb[i & 1][:Tt]
+            ob.ob_block_bwd(tdesc, tw[i], tg[i], 0, tact[i][:Tt], g_in, g_out, tsaved[i], tseg, ws)
+            g_in = g_out
+        ev[4].record()
+        dv = vgb[n_vit & 1][:Tv]
+        ob.ob_connector_bwd(cdesc, cw, cg, 0, vact[n_vit][:Tv], g_in, dv, nt, rows, Tt, csaved, ws)
+        ev[5].record()
+        g_in = dv
+        for i in reversed(range(n_vit)):
+            g_out = vgb[i & 1][:Tv]
+            ob.ob_block_bwd(vdesc, vw[i], vg[i], 0, vact[i][:Tv], g_in, g_out, vsaved[i], vseg, ws)
+            g_in = g_out
+        ev[6].record()
+        n_tok = nt * si.LLM_TOKENS_PER_TILE
+        flops = (step_flops(vs, vseg.cu_host, n_vit) + step_flops(ts, cu_t, n_llm)
+                 + 3.0 * 2.0 * n_tok * (W * ts.hidden + ts.hidden * ts.hidden))
+        return nt, Tt, flops
+
+    step(groups[0])
+    torch.cuda.synchronize()
+    parts = np.zeros(6)
+    flops, info = 0.0, []
+    t0 = time.perf_counter()
+    for g in groups[1:steps + 1]:
+        nt, Tt, f = step(g)
+        ev[6].synchronize()
+        parts += [ev[i].elapsed_time(ev[i + 1]) for i in range(6)]
+        flops += f
+        info.append({"samples": len(g), "tiles": nt, "llm_tokens": Tt})
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    names = ["vit_fwd", "connector_fwd", "llm_fwd", "llm_bwd", "connector_bwd", "vit_bwd"]
+    return {"report": "mixed", "stage": {"vit_blocks": n_vit, "vit": vs.name, "llm_blocks": n_llm, "llm": ts.name,
+                                         "connector": f"2x2 sub-sampling, LayerNorm({W}), {W}->{ts.hidden} GELU "
+                                                      f"{ts.hidden}->{ts.hidden}"},
+            "steps": steps, "ms_per_step": elapsed * 1e3 / steps, "tflops": flops / elapsed / 1e12,
+            "ms_per_part": {n: float(p / steps) for n, p in zip(names, parts)}, "batches": info,
+            "activation_mb_before_subsampling": info[-1]["tiles"] * si.VIT_TILE_TOKENS * vs.hidden * 2 / 1e6,
+            "activation_mb_after_connector": info[-1]["tiles"] * si.LLM_TOKENS_PER_TILE * ts.hidden * 2 / 1e6}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -182,11 +292,12 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--spread-batches", type=int, default=50)
     ap.add_argument("--skip-cpu-baseline", action="store_true")
-    ap.add_argument("--report", choices=["packer", "bmp"], default=None,
+    ap.add_argument("--report", choices=["packer", "bmp", "mixed"], default=None,
                     help="instead of the step benchmark print one JSON line of a host-side report: "
                          "'packer' = grouping arms, ISF convergence and Q' ablation on the synthetic "
                          "dataset (no GPU needed); 'bmp' = model-partition search fed by measured "
-                         "per-block forward times")
+                         "per-block forward times; 'mixed' = a pipeline stage holding ViT blocks, the "
+                         "token sub-sampling + connector and LLM blocks, run on one mini-batch")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="before the warm-up, copy this many MiB device-to-device three times: a "
                          "kernel of known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -201,6 +312,9 @@ def main():
         return
     if args.report == "bmp":
         print(json.dumps(bmp_report(args.seed)))
+        return
+    if args.report == "mixed":
+        print(json.dumps(mixed_report(args.seed)))
         return
 
     import torch
@@ -313,6 +427,8 @@ def main():
     prof = ob.ob_prof_end()
     kernels = {}
     for name, (ms, cnt, work) in prof.items():
+        if cnt == 0:
+            continue
         mfma = name in ("gemm", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv")
         rate = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
         kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
