@@ -4,10 +4,13 @@
 //   "NT" A[M,K] B[N,K] (forward)   "NN" A[M,K] B[K,N] (dgrad)   "TN" A[K,M] B[K,N] (wgrad, K = tokens)
 //
 // One workgroup (4 wavefronts, each a 128x128 block of 4x4 MFMA 32x32x16 tiles, 256 accumulator
-// registers) owns a 256x256 tile of C and walks K in steps of 64 over two LDS stages.  Tiles are
-// copied global -> LDS asynchronously by buffer loads that write LDS directly (no registers in
-// between); the hardware range check of the buffer descriptor turns every access past the end of
-// an operand (row tails of M / N, the ragged token tail of K) into zeros.  A K-contiguous operand
+// registers) owns a 256x256 tile of C and walks K in steps of 64 over two LDS stages.  Tiles go
+// global -> registers -> LDS: every wave issues one 16-byte-per-lane buffer load after every few
+// MFMAs, all K step long, and writes each vector to LDS one whole K step after it was requested,
+// so the memory pipeline sees a steady stream (a burst of a K step's loads blocks the wave's
+// instruction issue, MFMAs included, until the cache has taken them) and no wait ever meets a
+// load in flight.  The hardware range check of the buffer descriptor turns every access past the end
+// of an operand (row tails of M / N, the ragged token tail of K) into zeros.  A K-contiguous operand
 // is staged as [row][64 k] and a fragment is one 16-byte LDS read; a K-major operand is staged as
 // it lies in memory, [k][rows], and the fragment comes out of two transposing LDS reads, so dgrad
 // and wgrad need no re-layout pass.  16-byte chunks are XOR-swizzled on the way in (the global
@@ -124,18 +127,24 @@ struct Operand {
         base += step;
         nrec = nrec > step ? nrec - step : 0u;
     }
-    // asynchronous global -> LDS copy of this wave's share of the tile; loads past the end of the
-    // source (rows beyond M / N / K) deliver zeros
-    __device__ __forceinline__ void issue(unsigned char OB_LDS *__restrict__ dst, int wave) const {
-        // the descriptor must sit in scalar registers: pin its (uniform) parts explicitly
+    // descriptor of the current K step; must sit in scalar registers: pin its (uniform) parts explicitly
+    // (live = false: an empty range, every load returns zeros without touching memory)
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t descriptor(bool live) const {
         const uint64_t b = (uint64_t)base;
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(((uint64_t)hi << 32) | lo), 0, (int)__builtin_amdgcn_readfirstlane(nrec), 0x00020000);
-#pragma unroll
-        for (int p = 0; p < LD; ++p)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst + (wave * LD + p) * 1024, 16, voff[p], 0, 0, 0);
+        return __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)hi << 32) | lo), 0,
+                                                 live ? (int)__builtin_amdgcn_readfirstlane(nrec) : 0, 0x00020000);
+    }
+    // piece p (1 KB per wave) of this wave's share of the K step behind `rsrc`: global -> registers;
+    // loads past the end of the source (rows beyond M / N / K) deliver zeros
+    __device__ __forceinline__ u32x4 load(__amdgpu_buffer_rsrc_t rsrc, int p) const {
+        return __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[p], 0, 0);
+    }
+    // registers -> its place in the stage (lane-linear inside the 1 KB piece: the swizzle was applied
+    // by the choice of each lane's global address)
+    __device__ __forceinline__ void store(unsigned char OB_LDS *__restrict__ dst, int wave, int lane, int p, u32x4 v) const {
+        *(u32x4 OB_LDS *)(dst + (wave * LD + p) * 1024 + lane * 16) = v;
     }
     // fragment for MFMA tile i (32 x-values) at k-step t: lane l holds x = l % 32, k = 8 (l / 32) .. +7
     __device__ __forceinline__ bf16x8 frag(const unsigned char OB_LDS *__restrict__ tile, int i, int t) const {
@@ -171,17 +180,74 @@ __device__ __forceinline__ void mfma_step(const bf16x8 (&af)[Cfg<BM, BN, WM, WN>
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
 }
 
-// scheduling hint for "fragment reads of the next k-step + MFMAs of this one": pin "LDS read(s),
-// one MFMA" pairs at the front so every read has MFMA work to hide behind
+// The copy stream of one wave: G = A_LD + B_LD vectors in flight, vector g < A_LD is piece g of A,
+// the others pieces of B.  A "copy group" writes vector g (requested one K step ago) to the stage
+// being refilled and re-issues its load for the K step after.
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
-__device__ __forceinline__ void pin_reads_into_mfmas() {
+struct CopyStream {
     using C = Cfg<BM, BN, WM, WN>;
-    constexpr int READS = C::TM * (AK ? 2 : 1) + C::TN * (BKM ? 2 : 1);
-    constexpr int PER = READS > C::TM * C::TN ? 2 : 1;
+    static constexpr int G = C::A_LD + C::B_LD;
+    static_assert(G % 4 == 0, "copy groups are dealt to the four k-steps of a K step");
+    u32x4 v[G];
+    __amdgpu_buffer_rsrc_t ra, rb;
+    int k_left;   // K steps not yet given a descriptor
+
+    __device__ __forceinline__ void next_k(Operand<BM, WM * WN, AK> &opa, Operand<BN, WM * WN, BKM> &opb) {
+        const bool live = k_left > 0;
+        --k_left;
+        ra = opa.descriptor(live);
+        rb = opb.descriptor(live);
+        opa.advance();
+        opb.advance();
+    }
+    __device__ __forceinline__ void request(const Operand<BM, WM * WN, AK> &opa, const Operand<BN, WM * WN, BKM> &opb, int g) {
+        v[g] = g < C::A_LD ? opa.load(ra, g) : opb.load(rb, g - C::A_LD);
+    }
+    __device__ __forceinline__ void deliver(const Operand<BM, WM * WN, AK> &opa, const Operand<BN, WM * WN, BKM> &opb,
+                                            unsigned char OB_LDS *__restrict__ dst, int wave, int lane, int g) const {
+        if (g < C::A_LD) opa.store(dst, wave, lane, g, v[g]);
+        else opb.store(dst + BM * ROW_BYTES, wave, lane, g - C::A_LD, v[g]);
+    }
+};
+
+// One k-step (16 k): the MFMAs on the fragments in (af_use, bf_use), cut into as many runs as the
+// k-step has copy groups.  Each run opens with its share of the fragment reads of k-step t_rd of
+// `rd` (into af_rd / bf_rd; READ = false: none), then copy group q * GROUPS + run: deliver to
+// `fill`, request the next K step (COPY = false: none), then the run's MFMAs.  The runs are kept
+// in this order so that buffer loads and LDS traffic leave the wave evenly spaced between MFMAs.
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM, bool READ, bool COPY>
+__device__ __forceinline__ void k_step(const unsigned char OB_LDS *__restrict__ rd, int t_rd,
+                                       unsigned char OB_LDS *__restrict__ fill, int q,
+                                       CopyStream<BM, BN, WM, WN, AK, BKM> &cs,
+                                       const Operand<BM, WM * WN, AK> &opa,
+                                       const Operand<BN, WM * WN, BKM> &opb, int wave, int lane,
+                                       bf16x8 (&af_rd)[Cfg<BM, BN, WM, WN>::TM], bf16x8 (&bf_rd)[Cfg<BM, BN, WM, WN>::TN],
+                                       const bf16x8 (&af_use)[Cfg<BM, BN, WM, WN>::TM],
+                                       const bf16x8 (&bf_use)[Cfg<BM, BN, WM, WN>::TN],
+                                       f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
+    using C = Cfg<BM, BN, WM, WN>;
+    constexpr int GROUPS = (C::A_LD + C::B_LD) / 4;
+    constexpr int RUN = C::TM * C::TN / GROUPS;       // MFMAs per run
+    constexpr int FPR = (C::TM + C::TN) / GROUPS;     // fragments read per run
+    static_assert(C::TM * C::TN % GROUPS == 0 && (C::TM + C::TN) % GROUPS == 0, "uneven runs");
 #pragma unroll
-    for (int r = 0; r < READS / PER; ++r) {
-        __builtin_amdgcn_sched_group_barrier(0x100, PER, 0);  // LDS reads
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);    // one MFMA
+    for (int g = 0; g < GROUPS; ++g) {
+        if (READ) {
+#pragma unroll
+            for (int f = g * FPR; f < (g + 1) * FPR; ++f) {
+                if (f < C::TM) af_rd[f] = opa.frag(rd, f, t_rd);
+                else bf_rd[f - C::TM] = opb.frag(rd + BM * ROW_BYTES, f - C::TM, t_rd);
+            }
+        }
+        if (COPY) {
+            cs.deliver(opa, opb, fill, wave, lane, q * GROUPS + g);
+            cs.request(opa, opb, q * GROUPS + g);
+        }
+#pragma unroll
+        for (int m = g * RUN; m < (g + 1) * RUN; ++m)
+            acc[m / C::TN][m % C::TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf_use[m % C::TN], af_use[m / C::TN],
+                                                                               acc[m / C::TN][m % C::TN], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -198,47 +264,64 @@ __device__ __forceinline__ void read_frags(const unsigned char OB_LDS *__restric
     for (int j = 0; j < C::TN; ++j) bfr[j] = opb.frag(src + BM * ROW_BYTES, j, t);
 }
 
+// quarter q of the copy groups: deliver to `fill`, request the K step behind the stream's descriptors
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+__device__ __forceinline__ void copy_quarter(CopyStream<BM, BN, WM, WN, AK, BKM> &cs,
+                                             const Operand<BM, WM * WN, AK> &opa,
+                                             const Operand<BN, WM * WN, BKM> &opb,
+                                             unsigned char OB_LDS *__restrict__ fill, int wave, int lane, int q) {
+    constexpr int GROUPS = CopyStream<BM, BN, WM, WN, AK, BKM>::G / 4;
+#pragma unroll
+    for (int g = q * GROUPS; g < (q + 1) * GROUPS; ++g) {
+        cs.deliver(opa, opb, fill, wave, lane, g);
+        cs.request(opa, opb, g);
+    }
+}
+
 // k-steps 0 .. 2 of the stage in `cur`: the fragments of k-step 0 are already in af[0] / bfr[0];
-// on return the fragments of k-step 3 are in af[1] / bfr[1] and `cur` is not read again.
+// on return the fragments of k-step 3 are in af[1] / bfr[1] and `cur` is not read again.  Copy
+// quarters 1 .. 3 go to `fill` (the other stage).
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __device__ __forceinline__ void stage_front(const unsigned char OB_LDS *__restrict__ cur,
+                                            unsigned char OB_LDS *__restrict__ fill,
+                                            CopyStream<BM, BN, WM, WN, AK, BKM> &cs,
                                             const Operand<BM, WM * WN, AK> &opa,
-                                            const Operand<BN, WM * WN, BKM> &opb,
+                                            const Operand<BN, WM * WN, BKM> &opb, int wave, int lane,
                                             bf16x8 (&af)[2][Cfg<BM, BN, WM, WN>::TM],
                                             bf16x8 (&bfr)[2][Cfg<BM, BN, WM, WN>::TN],
                                             f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
 #pragma unroll
-    for (int t = 0; t < 3; ++t) {
-        read_frags<BM, BN, WM, WN, AK, BKM>(cur, opa, opb, t + 1, af[(t + 1) & 1], bfr[(t + 1) & 1]);
-        mfma_step<BM, BN, WM, WN>(af[t & 1], bfr[t & 1], acc);
-        pin_reads_into_mfmas<BM, BN, WM, WN, AK, BKM>();
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    for (int t = 0; t < 3; ++t)
+        k_step<BM, BN, WM, WN, AK, BKM, true, true>(cur, t + 1, fill, t + 1, cs, opa, opb, wave, lane, af[(t + 1) & 1],
+                                                    bfr[(t + 1) & 1], af[t & 1], bfr[t & 1], acc);
 }
 
 // k-step 3 of the current stage (fragments in af[1] / bfr[1]) overlapped with the fragment reads
-// of k-step 0 of the stage in `nxt` (into af[0] / bfr[0]).
+// of k-step 0 of the stage in `nxt` (into af[0] / bfr[0]) and copy quarter 0 into `fill` (the
+// stage just left).
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM, bool NEXT>
 __device__ __forceinline__ void stage_back(const unsigned char OB_LDS *__restrict__ nxt,
+                                           unsigned char OB_LDS *__restrict__ fill,
+                                           CopyStream<BM, BN, WM, WN, AK, BKM> &cs,
                                            const Operand<BM, WM * WN, AK> &opa,
-                                           const Operand<BN, WM * WN, BKM> &opb,
+                                           const Operand<BN, WM * WN, BKM> &opb, int wave, int lane,
                                            bf16x8 (&af)[2][Cfg<BM, BN, WM, WN>::TM],
                                            bf16x8 (&bfr)[2][Cfg<BM, BN, WM, WN>::TN],
                                            f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
-    if (NEXT) read_frags<BM, BN, WM, WN, AK, BKM>(nxt, opa, opb, 0, af[0], bfr[0]);
-    mfma_step<BM, BN, WM, WN>(af[1], bfr[1], acc);
-    if (NEXT) pin_reads_into_mfmas<BM, BN, WM, WN, AK, BKM>();
-    __builtin_amdgcn_sched_barrier(0);
+    k_step<BM, BN, WM, WN, AK, BKM, NEXT, NEXT>(nxt, 0, fill, 0, cs, opa, opb, wave, lane, af[0], bfr[0], af[1], bfr[1], acc);
 }
 
 // C[M,N] = op(A) op(B) (+bias) (+R): A is [M,K] (AK = false) or [K,M] (AK = true); B is [N,K]
 // (BKM = false) or [K,N] (BKM = true).
 //
-// Two LDS stages.  The barrier of a K step sits between its third and fourth k-step: by then the
+// Two LDS stages.  The barrier of K step s sits between its third and fourth k-step: by then the
 // step's last LDS reads have been issued (their data is needed only by the MFMAs after the
-// barrier), so behind the barrier the buffer can be refilled with K step s+2, and the first
-// fragments of step s+1 (landed since the previous barrier) are read while the fourth k-step's
-// MFMAs run.  No LDS latency and no barrier skew is exposed between K steps.
+// barrier), so behind the barrier the stage can be refilled, and the first fragments of step
+// s + 1 are read while the fourth k-step's MFMAs run.  The refill of a stage takes the four
+// k-steps between two barriers (the fourth of step s, the first three of step s + 1) and writes K
+// step s + 2, whose vectors were requested during the same four k-steps one K step earlier; the
+// registers freed by each write take the request for K step s + 3 right away.  Requests past the
+// last K step fall outside the descriptor's range: zeros, no memory access.
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     int M, int N, int K, const __bf16 *__restrict__ A, int lda, const __bf16 *__restrict__ B,
@@ -275,45 +358,52 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     unsigned char OB_LDS *s0 = (unsigned char OB_LDS *)st0;
     unsigned char OB_LDS *s1 = (unsigned char OB_LDS *)st1;
     const int nk = (K + BK - 1) / BK;
-    constexpr int WAIT_VM0 = 0x0F70;  // s_waitcnt vmcnt(0) only
-#define OB_ISSUE(dst)                            \
-    do {                                         \
-        opa.issue((dst), wave);                  \
-        opb.issue((dst) + BM * ROW_BYTES, wave); \
-        opa.advance();                           \
-        opb.advance();                           \
-    } while (0)
-#define OB_SYNC()                                 \
-    do {                                          \
-        __builtin_amdgcn_s_waitcnt(0);            \
-        __syncthreads();                          \
+    using CS = CopyStream<BM, BN, WM, WN, AK, BKM>;
+    CS cs;
+    cs.k_left = nk;
+    // own LDS traffic done (reads landed in registers, writes in the stage), then the barrier;
+    // buffer loads stay in flight across it
+#define OB_SYNC()                                  \
+    do {                                           \
+        __builtin_amdgcn_s_waitcnt(0xC07F);        \
+        __syncthreads();                           \
     } while (0)
     bf16x8 af[2][C::TM], bfr[2][C::TN];
-    OB_ISSUE(s0);
+    // prologue: K step 0 into stage 0; K step 1 requested, its first quarter delivered to stage 1
+    // and re-requested for K step 2 -- the state every trip of the loop starts from
+    cs.next_k(opa, opb);
+#pragma unroll
+    for (int g = 0; g < CS::G; ++g) cs.request(opa, opb, g);
+#pragma unroll
+    for (int g = 0; g < CS::G; ++g) cs.deliver(opa, opb, s0, wave, lane, g);
+    cs.next_k(opa, opb);
+#pragma unroll
+    for (int g = 0; g < CS::G; ++g) cs.request(opa, opb, g);
+    cs.next_k(opa, opb);
+    copy_quarter<BM, BN, WM, WN, AK, BKM>(cs, opa, opb, s1, wave, lane, 0);
     OB_SYNC();
-    if (nk > 1) OB_ISSUE(s1);
     read_frags<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, 0, af[0], bfr[0]);
     int kt = 0;
     for (; kt + 2 < nk; kt += 2) {       // two K steps per trip: stage 0 then stage 1, both with successors
-        stage_front<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, af, bfr, acc);
-        OB_SYNC();                       // stage 1 landed everywhere; nobody reads stage 0 any more
-        OB_ISSUE(s0);                    // K step kt + 2
-        stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, opa, opb, af, bfr, acc);
-        stage_front<BM, BN, WM, WN, AK, BKM>(s1, opa, opb, af, bfr, acc);
+        stage_front<BM, BN, WM, WN, AK, BKM>(s0, s1, cs, opa, opb, wave, lane, af, bfr, acc);
+        OB_SYNC();                       // stage 1 written everywhere; nobody reads stage 0 any more
+        cs.next_k(opa, opb);
+        stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
+        stage_front<BM, BN, WM, WN, AK, BKM>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
         OB_SYNC();
-        if (kt + 3 < nk) OB_ISSUE(s1);   // K step kt + 3
-        stage_back<BM, BN, WM, WN, AK, BKM, true>(s0, opa, opb, af, bfr, acc);
+        cs.next_k(opa, opb);
+        stage_back<BM, BN, WM, WN, AK, BKM, true>(s0, s1, cs, opa, opb, wave, lane, af, bfr, acc);
     }
-    // here kt is even, stage 0 holds K step kt (its first fragments are in registers) and, when
-    // kt + 1 < nk, stage 1 holds or is receiving K step kt + 1
-    stage_front<BM, BN, WM, WN, AK, BKM>(s0, opa, opb, af, bfr, acc);
+    // here kt is even, stage 0 holds K step kt (its first fragments are in registers) and stage 1
+    // is receiving K step kt + 1 (zeros when that is past the end)
+    stage_front<BM, BN, WM, WN, AK, BKM>(s0, s1, cs, opa, opb, wave, lane, af, bfr, acc);
     if (kt + 1 < nk) {
         OB_SYNC();
-        stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, opa, opb, af, bfr, acc);
-        stage_front<BM, BN, WM, WN, AK, BKM>(s1, opa, opb, af, bfr, acc);
+        cs.next_k(opa, opb);
+        stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
+        stage_front<BM, BN, WM, WN, AK, BKM>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
     }
-    stage_back<BM, BN, WM, WN, AK, BKM, false>(s0, opa, opb, af, bfr, acc);
-#undef OB_ISSUE
+    stage_back<BM, BN, WM, WN, AK, BKM, false>(s0, s0, cs, opa, opb, wave, lane, af, bfr, acc);
 #undef OB_SYNC
 
     // Epilogue.  A lane holds, per MFMA tile, output row m = lx and columns n = 8 g + 4 lh + (0..3):
@@ -321,7 +411,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     // wave transposes 32-row slabs of its tile through its share of the (now idle) stage buffers
     // as fp32, and reads them back so that 16 (or 8) consecutive lanes cover one contiguous row
     // segment; bias and residual are added on the way out, then one rounding to bf16.
-    __syncthreads();  // every wave is done reading the last stage
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __syncthreads();  // every wave is done reading the last stage and writing the other one
     constexpr int CW = BN / WN;            // columns of the wave's tile
     constexpr int RSTR = CW * 4 + 16;      // fp32 row stride in LDS, padded against bank conflicts
     constexpr int LPR = CW / 8;            // lanes per row on the way out (8 columns each)
