@@ -234,9 +234,11 @@ __device__ __forceinline__ void k_step(const unsigned char OB_LDS *__restrict__ 
     for (int g = 0; g < GROUPS; ++g) {
         if (READ) {
 #pragma unroll
+            // B fragments first, then A in order: the next k-step's run r starts with A fragment r
+            // (and needs every B fragment), so the fragments read last are the ones needed last
             for (int f = g * FPR; f < (g + 1) * FPR; ++f) {
-                if (f < C::TM) af_rd[f] = opa.frag(rd, f, t_rd);
-                else bf_rd[f - C::TM] = opb.frag(rd + BM * ROW_BYTES, f - C::TM, t_rd);
+                if (f < C::TN) bf_rd[f] = opb.frag(rd + BM * ROW_BYTES, f, t_rd);
+                else af_rd[f - C::TN] = opa.frag(rd, f - C::TN, t_rd);
             }
         }
         if (COPY) {
@@ -386,20 +388,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     int kt = 0;
     for (; kt + 2 < nk; kt += 2) {       // two K steps per trip: stage 0 then stage 1, both with successors
         stage_front<BM, BN, WM, WN, AK, BKM>(s0, s1, cs, opa, opb, wave, lane, af, bfr, acc);
+        cs.next_k(opa, opb);             // scalar work, kept off the path behind the barrier
         OB_SYNC();                       // stage 1 written everywhere; nobody reads stage 0 any more
-        cs.next_k(opa, opb);
         stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
         stage_front<BM, BN, WM, WN, AK, BKM>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
-        OB_SYNC();
         cs.next_k(opa, opb);
+        OB_SYNC();
         stage_back<BM, BN, WM, WN, AK, BKM, true>(s0, s1, cs, opa, opb, wave, lane, af, bfr, acc);
     }
     // here kt is even, stage 0 holds K step kt (its first fragments are in registers) and stage 1
     // is receiving K step kt + 1 (zeros when that is past the end)
     stage_front<BM, BN, WM, WN, AK, BKM>(s0, s1, cs, opa, opb, wave, lane, af, bfr, acc);
     if (kt + 1 < nk) {
-        OB_SYNC();
         cs.next_k(opa, opb);
+        OB_SYNC();
         stage_back<BM, BN, WM, WN, AK, BKM, true>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
         stage_front<BM, BN, WM, WN, AK, BKM>(s1, s0, cs, opa, opb, wave, lane, af, bfr, acc);
     }
@@ -457,7 +459,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                 bf16x8 o;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) o[e] = (__bf16)v[e];
-                *(bf16x8 *)(Cm + (size_t)m * ldc + n_out) = o;
+                __builtin_nontemporal_store(o, (bf16x8 *)(Cm + (size_t)m * ldc + n_out));
             }
         }
     }
