@@ -234,10 +234,11 @@ __device__ __forceinline__ void k_step(const unsigned char OB_LDS *__restrict__ 
     for (int g = 0; g < GROUPS; ++g) {
         if (READ) {
 #pragma unroll
-            // B fragments first, then A in order: the next k-step's run r starts with A fragment r
-            // (and needs every B fragment), so the fragments read last are the ones needed last
+            // read order a0 b0 b1 .. b(TN-1) a1 a2 ..: the order in which the next k-step's MFMAs
+            // first touch them, so the fragments read last are the ones needed last
             for (int f = g * FPR; f < (g + 1) * FPR; ++f) {
-                if (f < C::TN) bf_rd[f] = opb.frag(rd + BM * ROW_BYTES, f, t_rd);
+                if (f == 0) af_rd[0] = opa.frag(rd, 0, t_rd);
+                else if (f <= C::TN) bf_rd[f - 1] = opb.frag(rd + BM * ROW_BYTES, f - 1, t_rd);
                 else af_rd[f - C::TN] = opa.frag(rd, f - C::TN, t_rd);
             }
         }
