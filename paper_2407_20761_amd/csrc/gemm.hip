@@ -167,19 +167,6 @@ struct Operand {
     }
 };
 
-// MFMA work of one k-step (16 k) on fragments already in registers.
-template <int BM, int BN, int WM, int WN>
-__device__ __forceinline__ void mfma_step(const bf16x8 (&af)[Cfg<BM, BN, WM, WN>::TM],
-                                          const bf16x8 (&bfr)[Cfg<BM, BN, WM, WN>::TN],
-                                          f32x16 (&acc)[Cfg<BM, BN, WM, WN>::TM][Cfg<BM, BN, WM, WN>::TN]) {
-    using C = Cfg<BM, BN, WM, WN>;
-#pragma unroll
-    for (int i = 0; i < C::TM; ++i)
-#pragma unroll
-        for (int j = 0; j < C::TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-}
-
 // The copy stream of one wave: G = A_LD + B_LD vectors in flight, vector g < A_LD is piece g of A,
 // the others pieces of B.  A "copy group" writes vector g (requested one K step ago) to the stage
 // being refilled and re-issues its load for the K step after.

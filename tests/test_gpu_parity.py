@@ -392,3 +392,57 @@ def test_connector_fwd_bwd(Hv, Ht, grid, tiles, text):
     torch.cuda.synchronize()
     for n in si.CONNECTOR_NAMES:
         assert rel_err(to_np(g[n]), 2 * first[n]) < 1e-2, n
+
+
+def test_mixed_stage_chain_vit_block_handover_llm_block():
+    """One ViT block -> sub-sampling + connector -> one LLM block on one mini-batch, forward and backward,
+    against the oracle's chain: checks that the entry points compose (row layouts, the visual rows of
+    the packed LLM batch, the gradient handed from the LLM input back to the ViT output)."""
+    from oracle import connector as orc_conn
+    grid, tiles, text = 8, [2, 1, 1], [9, 40, 3]
+    vs = si.small_shape(name="vit", hidden=128, n_q_heads=2, n_kv_heads=2, mlp_dim=256, mask=si.MASK_BIDIR)
+    ts = si.small_shape(name="llm", hidden=256, n_q_heads=4, n_kv_heads=2, mlp_dim=512, norm=si.NORM_RMSNORM,
+                        mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL, use_rotary=True, has_bias=False, norm_eps=1e-6)
+    n_tiles, per_tile, eps = sum(tiles), grid * grid // 4, 1e-5
+    cu_v = orc_pack.cu_seqlens_vit(n_tiles, grid * grid + 1)
+    dst, cu_t = si.visual_rows(tiles, text, tokens_per_tile=per_tile)
+    Tv, Tt = int(cu_v[-1]), int(cu_t[-1])
+    _say(f"mixed chain: {n_tiles} tiles, Tv={Tv}, Tt={Tt}")
+    wv, wt, wc = si.block_weights(vs, seed=11), si.block_weights(ts, seed=12), si.connector_weights(vs.hidden, ts.hidden, seed=13)
+    xv, _ = si.activations(Tv, vs.hidden, seed=14, std=1.0)
+    x_text, dy = si.activations(Tt, ts.hidden, seed=15, std=1.0)
+
+    # oracle chain
+    yv_ref, cv = orc.block_fwd(vs, wv, xv, cu_v)
+    xt_ref, cc = orc_conn.connector_fwd(wc, yv_ref, n_tiles, grid, eps, x_text, dst)
+    yt_ref, ct = orc.block_fwd(ts, wt, xt_ref, cu_t)
+    dxt_ref, gt_ref, _ = orc.block_bwd(ts, wt, ct, dy, cu_t)
+    dyv_ref, gc_ref = orc_conn.connector_bwd(wc, cc, dxt_ref, n_tiles, grid, eps, dst)
+    dxv_ref, gv_ref, _ = orc.block_bwd(vs, wv, cv, dyv_ref, cu_v)
+
+    # HIP chain
+    seg_v, seg_t, rows = ob.Segments(cu_v), ob.Segments(cu_t), ob.RowIndex(dst)
+    rv, rt = BlockRun(vs, wv, Tv), BlockRun(ts, wt, Tt)
+    cdesc = ob.make_connector_desc(vs.hidden, ts.hidden, grid, eps)
+    cw = {n: to_dev(a) for n, a in wc.items()}
+    cg = {n: torch.zeros_like(t) for n, t in cw.items()}
+    csaved = bytes_buf(ob.ob_connector_saved_bytes(cdesc, n_tiles))
+    cws = bytes_buf(ob.ob_connector_workspace_bytes(cdesc, n_tiles))
+    x_v, x_t, dy_t = to_dev(xv), to_dev(x_text), to_dev(dy)
+    y_v = rv.fwd(x_v, seg_v)
+    ob.ob_connector_fwd(cdesc, cw, y_v, n_tiles, rows, x_t, Tt, csaved, cws)
+    y_t = rt.fwd(x_t, seg_t)
+    dx_t = rt.bwd(x_t, dy_t, seg_t)
+    dy_v = torch.empty_like(y_v)
+    ob.ob_connector_bwd(cdesc, cw, cg, 0, y_v, dx_t, dy_v, n_tiles, rows, Tt, csaved, cws)
+    dx_v = rv.bwd(x_v, dy_v, seg_v)
+    torch.cuda.synchronize()
+
+    errs = {"y_llm": rel_err(to_np(y_t), yt_ref), "dx_llm": rel_err(to_np(dx_t), dxt_ref),
+            "dy_vit": rel_err(to_np(dy_v), dyv_ref), "dx_vit": rel_err(to_np(dx_v), dxv_ref)}
+    errs.update({"vit.d" + n: rel_err(to_np(rv.g[n]), gv_ref[n]) for n in gv_ref})
+    errs.update({"conn.d" + n: rel_err(to_np(cg[n]), gc_ref[n]) for n in gc_ref})
+    errs.update({"llm.d" + n: rel_err(to_np(rt.g[n]), gt_ref[n]) for n in gt_ref})
+    _say("  " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
