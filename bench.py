@@ -444,7 +444,7 @@ def main():
            (T_avg, H, Dq), (T_avg, HD, H), (T_avg, H, upF), (T_avg, F, H),      # dgrad
            (Dq, H, T_avg), (H, HD, T_avg), (upF, H, T_avg), (H, F, T_avg)]      # wgrad
     alg_bytes = sum(2.0 * (m * k + n * k + m * n) for m, n, k in mnk) + 2 * 2.0 * T_avg * H
-    roofline = {"kernel": "gemm_kernel (bf16 MFMA 32x32x16; NT, NN and TN instances)", "bound": "mfma",
+    roofline = {"kernel": "gemm_kernel (bf16 MFMA 16x16x32; NT, NN and TN instances)", "bound": "mfma",
                 "achieved": g_ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": g_ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config, "gemm"),
                 "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
