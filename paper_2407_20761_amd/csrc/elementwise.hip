@@ -121,16 +121,34 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
             for (int e = 0; e < 8; ++e) g[i][e] = (float)t[e];
         }
     }
+    // the loads of a row are issued one row ahead (x, dh) or in front of the row's two reductions
+    // (dres), so that the barriers of the reductions never leave the memory pipe empty
+    bf16x8 nx[MAX_VEC], nd[MAX_VEC];
+    float nmean = 0.f, nrstd = 0.f;
+    auto fetch = [&](int row) {
+        nmean = stats[2 * (size_t)row];
+        nrstd = stats[2 * (size_t)row + 1];
+#pragma unroll
+        for (int i = 0; i < MAX_VEC; ++i) {
+            const int c = threadIdx.x + i * NORM_THREADS;
+            if (c < nvec) {
+                nx[i] = *(const bf16x8 *)(x + (size_t)row * H + c * 8);
+                nd[i] = *(const bf16x8 *)(dh + (size_t)row * H + c * 8);
+            }
+        }
+    };
+    if ((int)blockIdx.x < T) fetch(blockIdx.x);
     for (int row = blockIdx.x; row < T; row += gridDim.x) {
-        const float mean = stats[2 * (size_t)row], rstd = stats[2 * (size_t)row + 1];
+        const float mean = nmean, rstd = nrstd;
         float xh[MAX_VEC][8], dxh[MAX_VEC][8];
+        bf16x8 tr[MAX_VEC];
         float s1 = 0.f, s2 = 0.f;
 #pragma unroll
         for (int i = 0; i < MAX_VEC; ++i) {
             const int c = threadIdx.x + i * NORM_THREADS;
             if (c < nvec) {
-                const bf16x8 tx = *(const bf16x8 *)(x + (size_t)row * H + c * 8);
-                const bf16x8 td = *(const bf16x8 *)(dh + (size_t)row * H + c * 8);
+                const bf16x8 tx = nx[i], td = nd[i];
+                tr[i] = *(const bf16x8 *)(dres + (size_t)row * H + c * 8);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float d = (float)td[e];
@@ -143,17 +161,17 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
                 }
             }
         }
+        if (row + (int)gridDim.x < T) fetch(row + gridDim.x);
         s2 = block_sum(s2, red) / H;
         s1 = LAYERNORM ? block_sum(s1, red) / H : 0.f;
 #pragma unroll
         for (int i = 0; i < MAX_VEC; ++i) {
             const int c = threadIdx.x + i * NORM_THREADS;
             if (c < nvec) {
-                const bf16x8 tr = *(const bf16x8 *)(dres + (size_t)row * H + c * 8);
                 bf16x8 o;
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    o[e] = (__bf16)((float)tr[e] + rstd * (dxh[i][e] - s1 - xh[i][e] * s2));
+                    o[e] = (__bf16)((float)tr[i][e] + rstd * (dxh[i][e] - s1 - xh[i][e] * s2));
                 *(bf16x8 *)(dx + (size_t)row * H + c * 8) = o;
             }
         }
