@@ -446,11 +446,14 @@ template <bool AK, bool BKM>
 void launch_layout(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
                    const void *bias, const void *R, int ldr, hipStream_t s) {
     // 256x256 tiles run one workgroup per CU, 128x128 tiles two; take the shape whose last round
-    // of tiles leaves fewer CUs idle (the small tile pays ~15 % in operand re-reads)
+    // of tiles leaves fewer CUs idle.  Two small workgroups on a CU deliver about 0.72 of a big
+    // one's rate (twice the fragment reads per MFMA); measured: dW_qkv of config 3 (6144 x 4096,
+    // 1.5 rounds of big tiles against 3 full rounds of small ones) 782 against 905 us, 1024 x 4096
+    // (a quarter round of big tiles) 236 against 114 us.
     const double big = (double)((M + 255) / 256) * ((N + 255) / 256);
     const double small = (double)((M + 127) / 128) * ((N + 127) / 128);
     const double eff_big = big / (ceil(big / 256.0) * 256.0);
-    const double eff_small = 0.85 * small / (ceil(small / 512.0) * 512.0);
+    const double eff_small = 0.72 * small / (ceil(small / 512.0) * 512.0);
     if (eff_big >= eff_small)
         launch_tile<256, 256, 2, 2, AK, BKM>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
     else
