@@ -106,8 +106,9 @@ int ob_prof_end(double *ms_per_class, int64_t *launches_per_class, double *work_
  * rows of nkv*d elements with row stride ldkv -- so q,k,v may be column slices of one
  * [T, (nq+2nkv) d] buffer.  Cross-segment score tiles are never computed.
  * The backward needs ob_varlen_attn_bwd_workspace_bytes() bytes of scratch: Delta_i = sum_d dO_i O_i
- * and the log-sum-exp in base-2 units ([nq, T] fp32 each) and, when nq > nkv, one fp32 dK and dV partial per query head of a group, which
- * a second kernel sums in head order (no atomics: results are bitwise reproducible). */
+ * and the log-sum-exp in base-2 units ([nq, T] fp32 each).  With nq > nkv the workgroup that owns a
+ * tile of key rows walks the query heads of its group in order and keeps dK / dV in registers
+ * (no atomics, no partial sums in memory: results are bitwise reproducible). */
 int ob_varlen_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
                        int ldq, int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d,
                        float scale, int mask, int dtype, void *hip_stream);

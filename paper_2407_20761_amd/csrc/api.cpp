@@ -138,14 +138,13 @@ Saved saved_layout(const Dims &m) {
     s.total = L.off;
     return s;
 }
-struct Work { size_t dact, dup, dh, dx1, d_o, dqkv, delta, lse2, attn_part, partial, gemm, gemm_bytes, total; };
+struct Work { size_t dact, dup, dh, dx1, d_o, dqkv, delta, lse2, partial, gemm, gemm_bytes, total; };
 size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
 Work work_layout(const Dims &m) {
     Layout L; Work w; const size_t T = m.T;
     w.dact = L.take(T * m.F * 2); w.dup = L.take(T * m.upF * 2); w.dh = L.take(T * m.H * 2);
     w.dx1 = L.take(T * m.H * 2); w.d_o = L.take(T * m.HD * 2); w.dqkv = L.take(T * m.Dqkv * 2);
     w.delta = L.take((size_t)m.nq * T * 4); w.lse2 = L.take((size_t)m.nq * T * 4);
-    w.attn_part = L.take(attn_bwd_partial_bytes(m.T, m.nq, m.nkv, m.d));
     const size_t maxC = max3(m.upF, m.Dqkv, m.H);
     w.partial = L.take(max3((size_t)norm_bwd_partials(m.T) * 2 * m.H * 4, (size_t)colsum_partials(m.T) * maxC * 4, 0));
     size_t g = 0;
@@ -230,7 +229,7 @@ extern "C" int ob_varlen_attn_fwd(const void *q, const void *k, const void *v, v
 
 extern "C" size_t ob_varlen_attn_bwd_workspace_bytes(int total_tokens, int nq, int nkv, int d) {
     if (total_tokens < 1 || nq < 1 || nkv < 1 || d < 1 || nq % nkv) return 0;
-    return 2 * align_up((size_t)total_tokens * nq * 4, 256) + align_up(attn_bwd_partial_bytes(total_tokens, nq, nkv, d), 256);
+    return 2 * align_up((size_t)total_tokens * nq * 4, 256);
 }
 
 extern "C" int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k, const void *v,
@@ -250,9 +249,8 @@ extern "C" int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k,
     }
     const size_t rows = align_up((size_t)seg->total_tokens * nq * 4, 256);
     float *delta = (float *)ws, *lse2 = (float *)((unsigned char *)ws + rows);
-    float *part = (float *)((unsigned char *)ws + 2 * rows);
     launch_attn_delta(d_o, o, ldo, lse, delta, lse2, seg->total_tokens, nq, d, s);
-    launch_attn_bwd(d_o, q, k, v, lse2, delta, dq, dk, dv, part, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, s);
+    launch_attn_bwd(d_o, q, k, v, lse2, delta, dq, dk, dv, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, s);
     return check_launch("ob_varlen_attn_bwd");
 }
 
@@ -402,7 +400,7 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
     launch_attn_delta(d_o, o, m.HD, lse, delta, lse2, m.T, m.nq, m.d, s);
     launch_attn_bwd(d_o, qkv, qkv + (size_t)m.nq * m.d * 2, qkv + (size_t)(m.nq + m.nkv) * m.d * 2, lse2, delta, dqkv,
                     dqkv + (size_t)m.nq * m.d * 2, dqkv + (size_t)(m.nq + m.nkv) * m.d * 2,
-                    (float *)at(ws, wk.attn_part), m.Dqkv, m.Dqkv, m.HD, seg,
+                    m.Dqkv, m.Dqkv, m.HD, seg,
                     m.nq, m.nkv, m.d, scale, desc->mask, s);
     if (desc->use_rotary)
         launch_rotary(dqkv, m.Dqkv, m.T, m.nq + m.nkv, m.d, seg->cu_dev, seg->n_seg, desc->rotary_base, -1.0f, s);

@@ -677,8 +677,7 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
-    __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, float *__restrict__ part_dk,
-    float *__restrict__ part_dv, int nkv, int ldq, int ldkv, int ldo,
+    __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int ldq, int ldkv, int ldo,
     const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale) {
     __shared__ __attribute__((aligned(1024))) unsigned char q_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char do_s0[Tile<D>::BYTES];
@@ -692,7 +691,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     __shared__ int sh[8];
     const TileInfo ti = find_tile(cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
-    const int head = blockIdx.y, kvh = head / group;
+    const int kvh = blockIdx.y;  // one workgroup per key/value head: the group's query heads run one after another
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int pair = wave & 3;
@@ -732,26 +731,48 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     // causal: query rows before this workgroup's first key row see none of its keys
     const int q_begin = CAUSAL ? ti.seg_start + ((ti.row0 - ti.seg_start) / ST) * ST : ti.seg_start;
     const int n_iter = (ti.seg_end - q_begin + ST - 1) / ST;
-#define OB_ISSUE_DKV(it_, stage_)                                                                             \
-    do {                                                                                                      \
-        const int q0_ = q_begin + (it_) * ST;                                                                 \
-        const long off_ = (long)q0_ * own_ld2 + (long)head * D * 2;                                           \
-        tl.issue(own_base + off_, own_total - off_, role_g ? dos##stage_ : qs##stage_, pair);                 \
-        if (wave == 0) issue_row_stats(lse2_all + (size_t)head * T + q0_, (long)T - q0_, lses##stage_, lane); \
-        if (wave == 4) issue_row_stats(delta + (size_t)head * T + q0_, (long)T - q0_, dlts##stage_, lane);    \
+#define OB_ISSUE_DKV(hq_, it_, stage_)                                                                         \
+    do {                                                                                                       \
+        const int head_ = kvh * group + (hq_);                                                                 \
+        const int q0_ = q_begin + (it_) * ST;                                                                  \
+        const long off_ = (long)q0_ * own_ld2 + (long)head_ * D * 2;                                           \
+        tl.issue(own_base + off_, own_total - off_, role_g ? dos##stage_ : qs##stage_, pair);                  \
+        if (wave == 0) issue_row_stats(lse2_all + (size_t)head_ * T + q0_, (long)T - q0_, lses##stage_, lane); \
+        if (wave == 4) issue_row_stats(delta + (size_t)head_ * T + q0_, (long)T - q0_, dlts##stage_, lane);    \
     } while (0)
-    OB_ISSUE_DKV(0, 0);
     // causal: only the first two query tiles touch some pair's diagonal; either way only the last
-    // tile can be ragged.  The tiles in between run mask-free in a single-path loop.
+    // tile can be ragged.  The tiles in between need no mask.
     const int n_head = CAUSAL ? min(2, n_iter) : 0;
     const int n_mid_end = max(n_head, n_iter - (((ti.seg_end - q_begin) % ST) ? 1 : 0));
-    int it = 0;
+    // Order of work: first the masked tiles of every query head of the group (phase 0), then the
+    // mask-free ones of every head (phase 1) in one single-path loop -- the sums do not care, and one
+    // loop nest per phase keeps the accumulators in place (a loop over the heads around the per-head
+    // loops made the register allocator spill them).  A cursor names a tile: (phase, head in group, j).
+    const int cnt0 = n_head + (n_iter - n_mid_end), cnt1 = n_mid_end - n_head;
+    struct Cursor { int phase, hq, j; };
+    auto tile_of = [&](const Cursor &c) { return c.phase ? n_head + c.j : (c.j < n_head ? c.j : n_mid_end + c.j - n_head); };
+    auto step = [&](Cursor &c) {   // to the next tile in the order of work; phase 2 = past the end
+        const int cnt = c.phase ? cnt1 : cnt0;
+        if (c.j + 1 < cnt) { ++c.j; return; }
+        c.j = 0;
+        if (c.hq + 1 < group) { ++c.hq; return; }
+        c.hq = 0;
+        ++c.phase;
+        if (c.phase == 1 && cnt1 == 0) c.phase = 2;
+    };
+    Cursor cur = {0, 0, 0};
+    if (cnt0 == 0) cur.phase = cnt1 ? 1 : 2;
+    Cursor nxt = cur;
+    step(nxt);
+    OB_ISSUE_DKV(cur.hq, tile_of(cur), 0);
+#define OB_ISSUE_NEXT(stage_) OB_ISSUE_DKV(nxt.hq, tile_of(nxt), stage_)
+    int gi = 0;  // tiles done; its parity names the stage that holds the current tile
 #define OB_DKV_ITER(MASKED, QS, DOS, LSES, DLTS, ISSUE_NEXT)                                                 \
     {                                                                                                       \
-        const int q0 = q_begin + it * ST;                                                                   \
+        const int q0 = q_begin + tile_of(cur) * ST;                                                         \
         __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                               \
         __syncthreads();                                                                                    \
-        if (it + 1 < n_iter) { ISSUE_NEXT; }                                                                \
+        if (nxt.phase < 2) { ISSUE_NEXT; }                                                                  \
         const unsigned char OB_LDS *const row_tile = role_g ? (DOS) : (QS);                                 \
         const unsigned char OB_LDS *const tr_tile = role_g ? (QS) : (DOS);                                  \
         const float OB_LDS *const stat = role_g ? (DLTS) : (LSES);                                          \
@@ -772,76 +793,41 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
             dkv_dscores(acc_x, stat, pk);                                                                   \
         }                                                                                                   \
         if (live) dkv_outputs<D>(tr_tile, tl, pk, acc_out);                                                 \
-        ++it;                                                                                               \
+        cur = nxt;                                                                                          \
+        step(nxt);                                                                                          \
+        ++gi;                                                                                               \
     }
-#define OB_DKV_STAGE0(MASKED) OB_DKV_ITER(MASKED, qs0, dos0, lses0, dlts0, OB_ISSUE_DKV(it + 1, 1))
-#define OB_DKV_STAGE1(MASKED) OB_DKV_ITER(MASKED, qs1, dos1, lses1, dlts1, OB_ISSUE_DKV(it + 1, 0))
+#define OB_DKV_STAGE0(MASKED) OB_DKV_ITER(MASKED, qs0, dos0, lses0, dlts0, OB_ISSUE_NEXT(1))
+#define OB_DKV_STAGE1(MASKED) OB_DKV_ITER(MASKED, qs1, dos1, lses1, dlts1, OB_ISSUE_NEXT(0))
 #define OB_DKV_ANY(MASKED)                                                                                 \
-    OB_DKV_ITER(MASKED, (it & 1) ? qs1 : qs0, (it & 1) ? dos1 : dos0, (it & 1) ? lses1 : lses0,             \
-                (it & 1) ? dlts1 : dlts0, if (it & 1) OB_ISSUE_DKV(it + 1, 0); else OB_ISSUE_DKV(it + 1, 1))
-    while (it < n_head) OB_DKV_ANY(true)
-    while (it + 1 < n_mid_end) {  // it is even here: two tiles per trip with constant stage buffers
+    OB_DKV_ITER(MASKED, (gi & 1) ? qs1 : qs0, (gi & 1) ? dos1 : dos0, (gi & 1) ? lses1 : lses0,             \
+                (gi & 1) ? dlts1 : dlts0, if (gi & 1) OB_ISSUE_NEXT(0); else OB_ISSUE_NEXT(1))
+    while (cur.phase == 0) OB_DKV_ANY(true)
+    if ((gi & 1) && cur.phase == 1) OB_DKV_ANY(false)  // the two-tile loop below starts on stage 0
+    while (cur.phase == 1 && nxt.phase == 1) {  // gi is even here: two tiles per trip with constant stage buffers
         OB_DKV_STAGE0(false)
         OB_DKV_STAGE1(false)
     }
-    while (it < n_mid_end) OB_DKV_ANY(false)
-    while (it < n_iter) OB_DKV_ANY(true)
+    while (cur.phase == 1) OB_DKV_ANY(false)
 #undef OB_DKV_ANY
 #undef OB_DKV_STAGE1
 #undef OB_DKV_STAGE0
 #undef OB_DKV_ITER
+#undef OB_ISSUE_NEXT
 #undef OB_ISSUE_DKV
     if (!kv_live) return;
+    // dV^T / dK^T of the whole group of query heads sit in the accumulators: one rounding to bf16
     const float out_scale = role_g ? scale : 1.0f;
-    if (group == 1) {
-        __bf16 *const dst = role_g ? dk : dv;
+    __bf16 *const dst = role_g ? dk : dv;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                bf16x4 ov;
+        for (int g = 0; g < 4; ++g) {
+            bf16x4 ov;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc_out[dt][4 * g + e] * out_scale);
-                *(bf16x4 *)(dst + (size_t)kv_row * ldkv + kvh * D + dt * 32 + g * 8 + lh * 4) = ov;
-            }
-    } else {
-        // one fp32 partial per query head of the group, summed in fixed order by the reduce kernel
-        float *const dst = role_g ? part_dk : part_dv;
-        const size_t pbase = ((size_t)(head % group) * T + kv_row) * ((size_t)nkv * D) + (size_t)kvh * D;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 pv;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) pv[e] = acc_out[dt][4 * g + e] * out_scale;
-                *(f32x4 *)(dst + pbase + dt * 32 + g * 8 + lh * 4) = pv;
-            }
-    }
-}
-
-// dk / dv = sum over the group's query heads of the fp32 partials, in head order
-__global__ __launch_bounds__(256) void attn_dkv_reduce_kernel(const float *__restrict__ part_dk,
-                                                              const float *__restrict__ part_dv,
-                                                              __bf16 *__restrict__ dk, __bf16 *__restrict__ dv,
-                                                              int T, int width, int ldkv, int group) {
-    const int per_row = width / 4;
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (long)T * per_row) return;
-    const long row = i / per_row;
-    const int c = (int)(i % per_row) * 4;
-    f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
-    for (int g = 0; g < group; ++g) {
-        const size_t off = ((size_t)g * T + row) * width + c;
-        const f32x4 a = *(const f32x4 *)(part_dk + off), b = *(const f32x4 *)(part_dv + off);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { sk[e] += a[e]; sv[e] += b[e]; }
-    }
-    bf16x4 ok_, ov_;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { ok_[e] = (__bf16)sk[e]; ov_[e] = (__bf16)sv[e]; }
-    *(bf16x4 *)(dk + (size_t)row * ldkv + c) = ok_;
-    *(bf16x4 *)(dv + (size_t)row * ldkv + c) = ov_;
+            for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc_out[dt][4 * g + e] * out_scale);
+            *(bf16x4 *)(dst + (size_t)kv_row * ldkv + kvh * D + dt * 32 + g * 8 + lh * 4) = ov;
+        }
 }
 
 // algorithmic forward FLOPs: 4 nq d sum_seg A(s), A = s^2 or s (s + 1) / 2 (causal)
@@ -872,8 +858,8 @@ int count_tiles(const ob_segments *seg, int tile_rows) {
                                                       int, int, int, const int32_t *, int, int, int, float);  \
     template __global__ void attn_bwd_dkv_kernel<D, C>(const __bf16 *, const __bf16 *, const __bf16 *,        \
                                                        const __bf16 *, const float *, const float *,          \
-                                                       __bf16 *, __bf16 *, float *, float *, int, int, int,   \
-                                                       int, const int32_t *, int, int, int, float);
+                                                       __bf16 *, __bf16 *, int, int, int,                     \
+                                                       const int32_t *, int, int, int, float);
 OB_ATTN_INSTANCES(64, true)
 OB_ATTN_INSTANCES(64, false)
 OB_ATTN_INSTANCES(128, true)
@@ -906,34 +892,24 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
 }
 
 void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse2,
-                     const float *delta, void *dq, void *dk, void *dv, float *part, int ldq, int ldkv,
+                     const float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv,
                      int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
                      hipStream_t s) {
     const bool causal = mask == OB_MASK_SEG_CAUSAL;
     const int tiles = count_tiles(seg, QT);
     const int T = seg->total_tokens, group = nq / nkv;
-    const dim3 grid_q(tiles, nq);
-    float *part_dk = part, *part_dv = part ? part + (size_t)group * T * nkv * d : nullptr;
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
+        const dim3 grid_q(tiles, nq);
         OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 512, (const __bf16 *)d_o, (const __bf16 *)q,
                          (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
                          seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
     }
     ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
-    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_q, 512, (const __bf16 *)d_o, (const __bf16 *)q,
-                     (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dk, (__bf16 *)dv, part_dk,
-                     part_dv, nkv, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, T, group, scale);
-    if (group > 1) {
-        const long quads = (long)T * (nkv * d / 4);
-        hipLaunchKernelGGL(attn_dkv_reduce_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s,
-                           part_dk, part_dv, (__bf16 *)dk, (__bf16 *)dv, T, nkv * d, ldkv, group);
-    }
-}
-
-// fp32 scratch of the backward behind Delta: one dK and one dV partial per query head of a group
-size_t attn_bwd_partial_bytes(int T, int nq, int nkv, int d) {
-    return nq == nkv ? 0 : (size_t)2 * (nq / nkv) * T * nkv * d * 4;
+    const dim3 grid_kv(tiles, nkv);
+    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_kv, 512, (const __bf16 *)d_o, (const __bf16 *)q,
+                     (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dk, (__bf16 *)dv, ldq, ldkv,
+                     ldo, seg->cu_dev, seg->n_seg, T, group, scale);
 }
 
 }  // namespace ob

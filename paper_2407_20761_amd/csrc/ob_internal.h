@@ -81,12 +81,10 @@ void launch_rows_gather(void *small, const void *big, const int32_t *rows_dev, i
 void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int ldq,
                      int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale,
                      int mask, hipStream_t s);
-// part: attn_bwd_partial_bytes() bytes of fp32 scratch (unused, may be null, when nq == nkv)
 void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse2,
-                     const float *delta, void *dq, void *dk, void *dv, float *part, int ldq, int ldkv,
+                     const float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv,
                      int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
                      hipStream_t s);
-size_t attn_bwd_partial_bytes(int T, int nq, int nkv, int d);
 
 // ---- fp32 debug path (debug_fp32.hip): every tensor fp32, plain FMA kernels --------------------
 namespace f32 {
