@@ -249,35 +249,50 @@ __device__ __forceinline__ int find_segment(const int32_t *__restrict__ cu, int 
 
 // In-place rotation of the first n_heads_rot heads of each row of qkv (the q heads then the k
 // heads are contiguous there): pair (i, i + d/2) by sign * pos * base^(-2 i / d).
-// One workgroup per token; thread = (head, 4-wide slice of the half dimension).
+// One workgroup per token.  The angle depends on (token, i) only, so its cosine and sine are
+// computed once per token (d/2 values, in LDS) and shared by all heads; the token's position is
+// its distance to the largest segment start not behind it, found by one wave in parallel.
 __global__ __launch_bounds__(256) void rotary_kernel(__bf16 *__restrict__ qkv, int ld, int T,
                                                      int n_heads_rot, int d,
                                                      const int32_t *__restrict__ cu, int n_seg,
                                                      float log2_base, float sign) {
     const int t = blockIdx.x;
-    __shared__ int pos_s;
-    if (threadIdx.x == 0) pos_s = t - cu[find_segment(cu, n_seg, t)];
-    __syncthreads();
-    const float pos = (float)pos_s;
-    const int half = d / 2, per_head = half / 4;
-    for (int w = threadIdx.x; w < n_heads_rot * per_head; w += blockDim.x) {
-        const int head = w / per_head, i0 = (w % per_head) * 4;
-        __bf16 *p = qkv + (size_t)t * ld + head * d + i0;
-        typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-        const bf16x4 a = *(const bf16x4 *)p, b = *(const bf16x4 *)(p + half);
-        bf16x4 oa, obb;
+    const int half = d / 2;   // <= 64
+    __shared__ float cs_s[64], sn_s[64];
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        int start = 0;
+        for (int j0 = 0; j0 < n_seg; j0 += 64) {
+            const int j = j0 + lane;
+            const int c = j < n_seg ? cu[j] : 0;
+            start = max(start, c <= t ? c : 0);
+        }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const float theta = exp2f(-2.0f * (float)(i0 + e) / (float)d * log2_base);
+        for (int o = 32; o > 0; o >>= 1) start = max(start, __shfl_xor(start, o));
+        if (lane < half) {
+            const float theta = exp2f(-2.0f * (float)lane / (float)d * log2_base);
             float sn, cs;
-            sincosf(pos * theta, &sn, &cs);
-            sn *= sign;
+            sincosf((float)(t - start) * theta, &sn, &cs);
+            cs_s[lane] = cs;
+            sn_s[lane] = sn * sign;
+        }
+    }
+    __syncthreads();
+    const int per_head = half / 8;
+    for (int w = threadIdx.x; w < n_heads_rot * per_head; w += blockDim.x) {
+        const int head = w / per_head, i0 = (w % per_head) * 8;
+        __bf16 *p = qkv + (size_t)t * ld + head * d + i0;
+        const bf16x8 a = *(const bf16x8 *)p, b = *(const bf16x8 *)(p + half);
+        bf16x8 oa, obb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float cs = cs_s[i0 + e], sn = sn_s[i0 + e];
             const float x1 = (float)a[e], x2 = (float)b[e];
             oa[e] = (__bf16)(x1 * cs - x2 * sn);
             obb[e] = (__bf16)(x2 * cs + x1 * sn);
         }
-        *(bf16x4 *)p = oa;
-        *(bf16x4 *)(p + half) = obb;
+        *(bf16x8 *)p = oa;
+        *(bf16x8 *)(p + half) = obb;
     }
 }
 
