@@ -190,6 +190,95 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
     }
 }
 
+// The same backward with one wavefront per row (H <= 64 * 8 * NV): no workgroup barrier anywhere, the
+// row sums are wave reductions, and the next row's loads are in flight while the current row is
+// worked on (one wave per SIMD, 24 KB per wave in flight at H = 4096).  Every wave keeps its own
+// column sums and writes its own partial: partial[(blockIdx.x * 4 + wave)][2][H].
+template <bool LAYERNORM, int NV>
+__global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
+    const __bf16 *__restrict__ dh, const __bf16 *__restrict__ x, const float *__restrict__ stats,
+    const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ dres, __bf16 *__restrict__ dx,
+    float *__restrict__ partial, int T, int H) {
+    const int nvec = H / 8, lane = threadIdx.x & 63;
+    const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), n_slots = gridDim.x * 4;
+    bf16x8 g[NV];
+    float dg[NV][8], db[NV][8];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dg[i][e] = db[i][e] = 0.f;
+        g[i] = c < nvec ? *(const bf16x8 *)(gamma + c * 8) : bf16x8{};
+    }
+    bf16x8 nx[NV], nd[NV], nr[NV];
+    float nmean = 0.f, nrstd = 0.f;
+    auto fetch = [&](int row) {
+        nmean = stats[2 * (size_t)row];
+        nrstd = stats[2 * (size_t)row + 1];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nvec) {
+                nx[i] = *(const bf16x8 *)(x + (size_t)row * H + c * 8);
+                nd[i] = *(const bf16x8 *)(dh + (size_t)row * H + c * 8);
+                nr[i] = *(const bf16x8 *)(dres + (size_t)row * H + c * 8);
+            }
+        }
+    };
+    if (slot < T) fetch(slot);
+    for (int row = slot; row < T; row += n_slots) {
+        const float mean = nmean, rstd = nrstd;
+        bf16x8 cx[NV], cd[NV], cr[NV];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) { cx[i] = nx[i]; cd[i] = nd[i]; cr[i] = nr[i]; }
+        if (row + n_slots < T) fetch(row + n_slots);
+        float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            if (lane + 64 * i < nvec) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float d = (float)cd[i][e];
+                    const float xh = ((float)cx[i][e] - mean) * rstd;
+                    const float dxh = d * (float)g[i][e];
+                    dg[i][e] += d * xh;
+                    db[i][e] += d;
+                    s1 += dxh;
+                    s2 += dxh * xh;
+                }
+            }
+        }
+        s2 = wave_sum(s2) / H;
+        s1 = LAYERNORM ? wave_sum(s1) / H : 0.f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nvec) {
+                bf16x8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float xh = ((float)cx[i][e] - mean) * rstd;
+                    const float dxh = (float)cd[i][e] * (float)g[i][e];
+                    o[e] = (__bf16)((float)cr[i][e] + rstd * (dxh - s1 - xh * s2));
+                }
+                *(bf16x8 *)(dx + (size_t)row * H + c * 8) = o;
+            }
+        }
+    }
+    float *pg = partial + (size_t)slot * 2 * H, *pb = pg + H;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        if (c < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                pg[c * 8 + e] = dg[i][e];
+                pb[c * 8 + e] = db[i][e];
+            }
+        }
+    }
+}
+
 // out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]; fixed summation order.
 // A workgroup owns 32 columns; its 8 groups of 32 lanes each sum every 8th partial (four
 // independent chains per lane to keep loads in flight), then the 8 sums are combined in LDS.
@@ -414,10 +503,30 @@ void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *bet
 
 int norm_bwd_partials(int T) { return T < 1024 ? T : 1024; }
 
+template <int NV>
+static void launch_norm_bwd_wave(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
+                                 const void *dres, void *dx, float *partial, int T, int H, int nb, hipStream_t s) {
+    if (norm == OB_LAYERNORM)
+        hipLaunchKernelGGL((norm_bwd_wave_kernel<true, NV>), dim3(nb / 4), dim3(256), 0, s, (const __bf16 *)dh,
+                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
+                           (__bf16 *)dx, partial, T, H);
+    else
+        hipLaunchKernelGGL((norm_bwd_wave_kernel<false, NV>), dim3(nb / 4), dim3(256), 0, s, (const __bf16 *)dh,
+                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
+                           (__bf16 *)dx, partial, T, H);
+}
+
 void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
                      const void *dres, void *dx, float *partial, int T, int H, hipStream_t s) {
     ProfScope prof(K_NORM_BWD, s, 8.0 * T * H);
     const int nb = norm_bwd_partials(T);
+    // a wave per row while a row fits 8 vectors per lane and there are whole workgroups of rows
+    if (H <= 4096 && nb % 4 == 0) {
+        if (H <= 1024) launch_norm_bwd_wave<2>(norm, dh, x, stats, gamma, dres, dx, partial, T, H, nb, s);
+        else if (H <= 2048) launch_norm_bwd_wave<4>(norm, dh, x, stats, gamma, dres, dx, partial, T, H, nb, s);
+        else launch_norm_bwd_wave<8>(norm, dh, x, stats, gamma, dres, dx, partial, T, H, nb, s);
+        return;
+    }
     if (norm == OB_LAYERNORM)
         hipLaunchKernelGGL(norm_bwd_kernel<true>, dim3(nb), dim3(NORM_THREADS), 0, s, (const __bf16 *)dh,
                            (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
