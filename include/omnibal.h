@@ -166,14 +166,15 @@ int ob_gemm_bf16(int layout, int M, int N, int K, const void *A, const void *B, 
  *   c5  row i of z is written to row dst_rows[i] of x_llm [llm_tokens, Ht]; other rows (text) are
  *       left as the caller filled them.
  * dst_rows (int32, n_tok entries, host and device copies like cu_seqlens) must be distinct and
- * inside [0, llm_tokens): checked on the host.  bf16 only (dtype OB_BF16); vit_hidden and
+ * inside [0, llm_tokens): checked on the host.  dtype OB_BF16, or OB_FP32 for the debug variant
+ * (every tensor, weight and gradient fp32; plain kernels, same steps); vit_hidden and
  * llm_hidden multiples of 64, 4 vit_hidden <= 16384, grid even.
  * ob_connector_bwd: given dx_llm [llm_tokens, Ht] it reads the rows dst_rows, writes every row of
  * dv [n_tiles (grid^2 + 1), Hv] (class rows: zeros) and all six weight gradients (flags:
  * OB_BWD_ACCUMULATE only).  `saved` carries un, h, a and the row statistics from the forward. */
 typedef struct {
     int vit_hidden, llm_hidden, grid;
-    int dtype;         /* ob_dtype, OB_BF16 */
+    int dtype;         /* ob_dtype */
     float norm_eps;
 } ob_connector_desc;
 typedef struct { const void *n_g, *n_b, *w1, *b1, *w2, *b2; } ob_connector_weights;

@@ -38,7 +38,7 @@ CWork work_layout(const CDims &m) {
 
 int validate(const ob_connector_desc *d, int n_tiles, const char *who, CDims *out) {
     if (!d) return fail(OB_EINVAL, "%s: desc is null", who);
-    if (d->dtype != OB_BF16) return fail(OB_EUNSUPPORTED, "%s: only OB_BF16 is built for the connector", who);
+    if (d->dtype != OB_BF16 && d->dtype != OB_FP32) return fail(OB_EUNSUPPORTED, "%s: dtype must be OB_BF16 or OB_FP32", who);
     if (d->vit_hidden < 64 || d->llm_hidden < 64 || d->vit_hidden % 64 || d->llm_hidden % 64)
         return fail(OB_EUNSUPPORTED, "%s: vit_hidden and llm_hidden must be positive multiples of 64", who);
     if (4 * d->vit_hidden > subsample_max_width())
@@ -73,12 +73,14 @@ inline const unsigned char *at(const void *base, size_t off) { return (const uns
 extern "C" size_t ob_connector_saved_bytes(const ob_connector_desc *desc, int n_tiles) {
     CDims m;
     if (validate(desc, n_tiles, "ob_connector_saved_bytes", &m)) return 0;
+    if (desc->dtype == OB_FP32) return f32::connector_saved_bytes(m.n_tok, m.Hv, m.Ht);
     return saved_layout(m).total;
 }
 
 extern "C" size_t ob_connector_workspace_bytes(const ob_connector_desc *desc, int n_tiles) {
     CDims m;
     if (validate(desc, n_tiles, "ob_connector_workspace_bytes", &m)) return 0;
+    if (desc->dtype == OB_FP32) return f32::connector_work_bytes(m.n_tok, m.Hv, m.Ht);
     return work_layout(m).total;
 }
 
@@ -92,6 +94,15 @@ extern "C" int ob_connector_fwd(const ob_connector_desc *desc, const ob_connecto
     if (!v || !x_llm) return fail(OB_EINVAL, "%s: v / x_llm is null", who);
     if (!w || !w->n_g || !w->n_b || !w->w1 || !w->b1 || !w->w2 || !w->b2) return fail(OB_EINVAL, "%s: a weight pointer is null", who);
     if (int rc = validate_rows(dst_rows_host, dst_rows_dev, m.n_tok, llm_tokens, who)) return rc;
+    if (desc->dtype == OB_FP32) {   // debug path: same steps, every tensor fp32
+        if (!saved || saved_bytes < f32::connector_saved_bytes(m.n_tok, m.Hv, m.Ht))
+            return fail(OB_EWORKSPACE, "%s: saved buffer too small (%zu bytes given)", who, saved_bytes);
+        if (!ws || ws_bytes < f32::connector_work_bytes(m.n_tok, m.Hv, m.Ht))
+            return fail(OB_EWORKSPACE, "%s: workspace too small (%zu bytes given)", who, ws_bytes);
+        f32::connector_fwd(w, v, m.n_tok, m.g, m.Hv, m.Ht, desc->norm_eps, dst_rows_dev, x_llm, saved, ws,
+                           (hipStream_t)hip_stream);
+        return check_launch(who);
+    }
     const CSaved sv = saved_layout(m);
     const CWork wk = work_layout(m);
     if (!saved || saved_bytes < sv.total) return fail(OB_EWORKSPACE, "%s: saved buffer too small (%zu bytes given)", who, saved_bytes);
@@ -119,6 +130,15 @@ extern "C" int ob_connector_bwd(const ob_connector_desc *desc, const ob_connecto
     if (!w || !w->n_g || !w->w1 || !w->w2) return fail(OB_EINVAL, "%s: a weight pointer is null", who);
     if (!g || !g->n_g || !g->n_b || !g->w1 || !g->b1 || !g->w2 || !g->b2) return fail(OB_EINVAL, "%s: a gradient pointer is null", who);
     if (int rc = validate_rows(dst_rows_host, dst_rows_dev, m.n_tok, llm_tokens, who)) return rc;
+    if (desc->dtype == OB_FP32) {
+        if (!saved || saved_bytes < f32::connector_saved_bytes(m.n_tok, m.Hv, m.Ht))
+            return fail(OB_EWORKSPACE, "%s: saved buffer too small (%zu bytes given)", who, saved_bytes);
+        if (!ws || ws_bytes < f32::connector_work_bytes(m.n_tok, m.Hv, m.Ht))
+            return fail(OB_EWORKSPACE, "%s: workspace too small (%zu bytes given)", who, ws_bytes);
+        f32::connector_bwd(w, g, flags & OB_BWD_ACCUMULATE ? 1 : 0, dx_llm, dv, m.n_tok, m.n_tiles, m.g, m.Hv, m.Ht,
+                           dst_rows_dev, saved, ws, (hipStream_t)hip_stream);
+        return check_launch(who);
+    }
     const CSaved sv = saved_layout(m);
     const CWork wk = work_layout(m);
     if (!saved || saved_bytes < sv.total) return fail(OB_EWORKSPACE, "%s: saved buffer too small (%zu bytes given)", who, saved_bytes);

@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(int layernorm, const floa
     if (threadIdx.x == 0) { stat[2 * blockIdx.x] = mean; stat[2 * blockIdx.x + 1] = rstd; }
 }
 
-// dx = res + norm_bwd(dh); xh = (x - mean) rstd, gy = dh g:
+// dx = res + norm_bwd(dh) (res may be null: no residual); xh = (x - mean) rstd, gy = dh g:
 //   LayerNorm dx = rstd (gy - mean(gy) - xh mean(gy xh));  RMSNorm dx = rstd (gy - xh mean(gy xh))
 __global__ __launch_bounds__(256) void norm_bwd_kernel(int layernorm, const float *__restrict__ dh,
                                                        const float *__restrict__ x,
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void norm_bwd_kernel(int layernorm, const floa
     const float m2 = block_sum(s2, sh) / H;
     for (int i = threadIdx.x; i < H; i += 256) {
         const float gy = dh[row + i] * g[i], xh = (x[row + i] - mean) * rstd;
-        dx[row + i] = res[row + i] + rstd * (gy - m1 - xh * m2);
+        dx[row + i] = (res ? res[row + i] : 0.f) + rstd * (gy - m1 - xh * m2);
     }
 }
 
@@ -322,6 +322,48 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(const float *__restri
     }
 }
 
+// ---- ViT -> LLM hand-over: patch gather / its adjoint, row scatter / gather ----------------------
+
+// u[i][b Hv + c] = v[row(i, b)][c]: token i = (tile, r, cq) of the (g/2)^2 grid, block b = 2 dr + dc
+// takes patch (2r + dr, 2cq + dc); row 0 of every tile (the class token) is skipped
+__global__ __launch_bounds__(256) void subsample_gather_kernel(const float *__restrict__ v, float *__restrict__ u,
+                                                               long n, int g, int Hv) {
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n) return;
+    const int W = 4 * Hv, half = g / 2;
+    const long i = e / W;
+    const int col = (int)(e % W), b = col / Hv, c = col % Hv;
+    const int tile = (int)(i / (half * half)), rem = (int)(i % (half * half)), r = rem / half, cq = rem % half;
+    const long row = (long)tile * (g * g + 1) + 1 + (long)(2 * r + (b >> 1)) * g + (2 * cq + (b & 1));
+    u[e] = v[row * Hv + c];
+}
+
+// the adjoint: every patch row receives its channel block of du, class rows become zero
+__global__ __launch_bounds__(256) void subsample_scatter_kernel(const float *__restrict__ du, float *__restrict__ dv,
+                                                                long n, int g, int Hv) {
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n) return;
+    const int half = g / 2, per_tile = g * g + 1;
+    const long row = e / Hv;
+    const int c = (int)(e % Hv), tile = (int)(row / per_tile), p = (int)(row % per_tile);
+    if (p == 0) { dv[e] = 0.f; return; }
+    const int pr = (p - 1) / g, pc = (p - 1) % g;
+    const long i = ((long)tile * half + pr / 2) * half + pc / 2;
+    const int b = 2 * (pr & 1) + (pc & 1);
+    dv[e] = du[i * 4 * Hv + b * Hv + c];
+}
+
+// SCATTER: big[rows[i]][:] = small[i][:];  else small[i][:] = big[rows[i]][:]
+__global__ __launch_bounds__(256) void rows_copy_kernel(float *__restrict__ small, float *__restrict__ big,
+                                                        const int32_t *__restrict__ rows, long n, int C, int scatter) {
+    const long e = (long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= n) return;
+    const long i = e / C;
+    const int c = (int)(e % C);
+    if (scatter) big[(long)rows[i] * C + c] = small[e];
+    else small[e] = big[(long)rows[i] * C + c];
+}
+
 inline unsigned blocks_for(long threads) { return (unsigned)((threads + 255) / 256); }
 
 void gemm(int layout, int M, int N, int K, const float *A, const float *B, float *C, const float *bias,
@@ -459,6 +501,80 @@ void block_bwd(const ob_block_desc *dsc, const ob_block_weights *w, const ob_blo
                        OB_F(w->n1_g), dx1, OB_FM(dx), H);
     hipLaunchKernelGGL(norm_wgrad_kernel, dim3(blocks_for(H)), dim3(256), 0, s, dh, OB_F(x), OB_F(b + sv.stat1),
                        OB_FM(g->n1_g), beta ? OB_FM(g->n1_b) : nullptr, T, H, acc);
+}
+
+
+// ---- hand-over, fp32: the same steps as the bf16 path, every tensor in fp32, u kept in `saved` ----
+struct ConnSaved { size_t u, un, h, a, stats, total; };
+struct ConnWork { size_t z, da, dh, dun, du, total; };
+static ConnSaved conn_saved(long n, int W, int Ht) {
+    ConnSaved s; size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += up256(bytes); return o; };
+    s.u = take(n * W * 4); s.un = take(n * W * 4); s.h = take(n * Ht * 4); s.a = take(n * Ht * 4); s.stats = take(n * 8);
+    s.total = off;
+    return s;
+}
+static ConnWork conn_work(long n, int W, int Ht) {
+    ConnWork w; size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t o = off; off += up256(bytes); return o; };
+    w.z = take(n * Ht * 4); w.da = take(n * Ht * 4); w.dh = take(n * Ht * 4); w.dun = take(n * W * 4); w.du = take(n * W * 4);
+    w.total = off;
+    return w;
+}
+size_t connector_saved_bytes(long n_tok, int Hv, int Ht) { return conn_saved(n_tok, 4 * Hv, Ht).total; }
+size_t connector_work_bytes(long n_tok, int Hv, int Ht) { return conn_work(n_tok, 4 * Hv, Ht).total; }
+
+void connector_fwd(const ob_connector_weights *w, const void *v, int n_tok, int g, int Hv, int Ht, float eps,
+                   const int32_t *rows_dev, void *x_llm, void *saved, void *ws, hipStream_t s) {
+    const int W = 4 * Hv;
+    const ConnSaved sv = conn_saved(n_tok, W, Ht);
+    const ConnWork wk = conn_work(n_tok, W, Ht);
+    unsigned char *b = (unsigned char *)saved;
+    float *u = OB_FM(b + sv.u), *un = OB_FM(b + sv.un), *h = OB_FM(b + sv.h), *a = OB_FM(b + sv.a);
+    float *z = OB_FM((unsigned char *)ws + wk.z);
+    hipLaunchKernelGGL(subsample_gather_kernel, dim3(blocks_for((long)n_tok * W)), dim3(256), 0, s, OB_F(v), u,
+                       (long)n_tok * W, g, Hv);
+    hipLaunchKernelGGL(norm_fwd_kernel, dim3(n_tok), dim3(256), 0, s, 1, u, OB_F(w->n_g), OB_F(w->n_b), un,
+                       OB_FM(b + sv.stats), W, eps);
+    gemm(0, n_tok, Ht, W, un, OB_F(w->w1), h, OB_F(w->b1), nullptr, 0, s);
+    hipLaunchKernelGGL(act_fwd_kernel, dim3(blocks_for((long)n_tok * Ht)), dim3(256), 0, s, 0, h, a, (long)n_tok * Ht, Ht);
+    gemm(0, n_tok, Ht, Ht, a, OB_F(w->w2), z, OB_F(w->b2), nullptr, 0, s);
+    hipLaunchKernelGGL(rows_copy_kernel, dim3(blocks_for((long)n_tok * Ht)), dim3(256), 0, s, z, OB_FM(x_llm), rows_dev,
+                       (long)n_tok * Ht, Ht, 1);
+}
+
+void connector_bwd(const ob_connector_weights *w, const ob_connector_grads *gr, int acc, const void *dx_llm, void *dv,
+                   int n_tok, int n_tiles, int g, int Hv, int Ht, const int32_t *rows_dev, const void *saved, void *ws,
+                   hipStream_t s) {
+    const int W = 4 * Hv;
+    const ConnSaved sv = conn_saved(n_tok, W, Ht);
+    const ConnWork wk = conn_work(n_tok, W, Ht);
+    const unsigned char *b = (const unsigned char *)saved;
+    unsigned char *wb = (unsigned char *)ws;
+    const float *u = OB_F(b + sv.u), *un = OB_F(b + sv.un), *h = OB_F(b + sv.h), *a = OB_F(b + sv.a);
+    const float *stats = OB_F(b + sv.stats);
+    float *dz = OB_FM(wb + wk.z), *da = OB_FM(wb + wk.da), *dh = OB_FM(wb + wk.dh), *dun = OB_FM(wb + wk.dun);
+    float *du = OB_FM(wb + wk.du);
+    auto colsum = [&](const float *src, int C, void *out) {
+        hipLaunchKernelGGL(colsum_kernel, dim3(blocks_for(C)), dim3(256), 0, s, src, n_tok, C, OB_FM(out), acc);
+    };
+    hipLaunchKernelGGL(rows_copy_kernel, dim3(blocks_for((long)n_tok * Ht)), dim3(256), 0, s, dz,
+                       (float *)dx_llm /* read only */, rows_dev, (long)n_tok * Ht, Ht, 0);
+    gemm(2, Ht, Ht, n_tok, dz, a, OB_FM(gr->w2), nullptr, nullptr, acc, s);
+    colsum(dz, Ht, gr->b2);
+    gemm(1, n_tok, Ht, Ht, dz, OB_F(w->w2), da, nullptr, nullptr, 0, s);
+    hipLaunchKernelGGL(act_bwd_kernel, dim3(blocks_for((long)n_tok * Ht)), dim3(256), 0, s, 0, da, h, dh,
+                       (long)n_tok * Ht, Ht);
+    gemm(2, Ht, W, n_tok, dh, un, OB_FM(gr->w1), nullptr, nullptr, acc, s);
+    colsum(dh, Ht, gr->b1);
+    gemm(1, n_tok, W, Ht, dh, OB_F(w->w1), dun, nullptr, nullptr, 0, s);
+    // un = LayerNorm(u): du = norm_bwd(dun), no residual
+    hipLaunchKernelGGL(norm_bwd_kernel, dim3(n_tok), dim3(256), 0, s, 1, dun, u, stats, OB_F(w->n_g),
+                       (const float *)nullptr, du, W);
+    hipLaunchKernelGGL(norm_wgrad_kernel, dim3(blocks_for(W)), dim3(256), 0, s, dun, u, stats, OB_FM(gr->n_g),
+                       OB_FM(gr->n_b), n_tok, W, acc);
+    const long n_dv = (long)n_tiles * (g * g + 1) * Hv;
+    hipLaunchKernelGGL(subsample_scatter_kernel, dim3(blocks_for(n_dv)), dim3(256), 0, s, du, OB_FM(dv), n_dv, g, Hv);
 }
 
 }  // namespace f32

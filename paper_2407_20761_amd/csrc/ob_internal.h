@@ -103,6 +103,14 @@ void block_fwd(const ob_block_desc *dsc, const ob_block_weights *w, const void *
 void block_bwd(const ob_block_desc *dsc, const ob_block_weights *w, const ob_block_grads *g, int accumulate,
                const void *x, const void *dy, void *dx, const void *saved, const ob_segments *seg, void *ws,
                hipStream_t s);
+// the ViT -> LLM hand-over with every tensor in fp32 (n_tok = n_tiles (g/2)^2 sub-sampled tokens)
+size_t connector_saved_bytes(long n_tok, int Hv, int Ht);
+size_t connector_work_bytes(long n_tok, int Hv, int Ht);
+void connector_fwd(const ob_connector_weights *w, const void *v, int n_tok, int g, int Hv, int Ht, float eps,
+                   const int32_t *rows_dev, void *x_llm, void *saved, void *ws, hipStream_t s);
+void connector_bwd(const ob_connector_weights *w, const ob_connector_grads *gr, int accumulate, const void *dx_llm,
+                   void *dv, int n_tok, int n_tiles, int g, int Hv, int Ht, const int32_t *rows_dev, const void *saved,
+                   void *ws, hipStream_t s);
 }  // namespace f32
 
 }  // namespace ob

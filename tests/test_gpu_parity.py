@@ -413,6 +413,45 @@ def test_connector_fwd_bwd(Hv, Ht, grid, tiles, text):
         assert rel_err(to_np(g[n]), 2 * first[n]) < 1e-2, n
 
 
+@pytest.mark.parametrize("Hv,Ht,grid,tiles,text", CONNECTOR_CASES[:2])
+def test_fp32_debug_connector(Hv, Ht, grid, tiles, text):
+    """The hand-over with every tensor in fp32: composition, gather / scatter and the analytic backward
+    against the fp64 oracle at the tolerance bf16 storage cannot reach."""
+    from oracle import connector as orc_conn
+    _say(f"fp32 connector Hv={Hv} Ht={Ht} grid={grid} tiles={tiles} text={text}")
+    n_tiles, per_tile = sum(tiles), grid * grid // 4
+    w_np = si.connector_weights(Hv, Ht, seed=Hv + Ht)
+    dst, cu = si.visual_rows(tiles, text, tokens_per_tile=per_tile)
+    T = int(cu[-1])
+    v_np, _ = si.activations(n_tiles * (grid * grid + 1), Hv, seed=1, std=1.0)
+    x_np, dx_np = si.activations(T, Ht, seed=2, std=1.0)
+    eps = 1e-5
+    ref_out, cache = orc_conn.connector_fwd(w_np, v_np, n_tiles, grid, eps, x_np, dst)
+    ref_dv, ref_g = orc_conn.connector_bwd(w_np, cache, dx_np, n_tiles, grid, eps, dst)
+
+    f32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    desc = ob.make_connector_desc(Hv, Ht, grid, eps, dtype=ob.OB_FP32)
+    w = {n: f32(a) for n, a in w_np.items()}
+    g = {n: torch.zeros_like(t) for n, t in w.items()}
+    saved = bytes_buf(ob.ob_connector_saved_bytes(desc, n_tiles))
+    ws = bytes_buf(ob.ob_connector_workspace_bytes(desc, n_tiles))
+    rows = ob.RowIndex(dst)
+    v, x_llm, dx_llm = f32(v_np), f32(x_np), f32(dx_np)
+    dv = torch.full((n_tiles * (grid * grid + 1), Hv), 7.0, dtype=torch.float32, device="cuda")
+    ob.ob_connector_fwd(desc, w, v, n_tiles, rows, x_llm, T, saved, ws)
+    ob.ob_connector_bwd(desc, w, g, 0, v, dx_llm, dv, n_tiles, rows, T, saved, ws)
+    torch.cuda.synchronize()
+    out = x_llm.cpu().numpy().astype(np.float64)
+    text_rows = np.setdiff1d(np.arange(T), dst)
+    np.testing.assert_array_equal(out[text_rows], x_np[text_rows].astype(np.float32).astype(np.float64))
+    assert rel_err(out[dst], ref_out[dst]) < TOL_FP32
+    dv_np = dv.cpu().numpy().astype(np.float64)
+    assert not dv_np[np.arange(n_tiles) * (grid * grid + 1)].any()
+    assert rel_err(dv_np, ref_dv) < TOL_FP32
+    for n in si.CONNECTOR_NAMES:
+        assert rel_err(g[n].cpu().numpy(), ref_g[n]) < TOL_FP32, n
+
+
 def test_mixed_stage_chain_vit_block_handover_llm_block():
     """One ViT block -> sub-sampling + connector -> one LLM block on one mini-batch, forward and backward,
     against the oracle's chain: checks that the entry points compose (row layouts, the visual rows of

@@ -247,8 +247,12 @@ def test_connector_argument_validation_and_sizes():
     assert sv == pad(n_tok * 512 * 2) + 2 * pad(n_tok * 256 * 2) + pad(n_tok * 8)
     assert wk >= pad(n_tok * 512 * 2) + 3 * pad(n_tok * 256 * 2)
     for bad in (ob.make_connector_desc(100, 256, 4), ob.make_connector_desc(128, 250, 4),
-                ob.make_connector_desc(4160, 256, 4), ob.make_connector_desc(128, 256, 4, dtype=ob.OB_FP32)):
+                ob.make_connector_desc(4160, 256, 4), ob.make_connector_desc(128, 256, 4, dtype=7)):
         assert ob.ob_connector_saved_bytes(bad, n_tiles) == 0
+    # the fp32 debug variant keeps u as well, four bytes per element
+    d32 = ob.make_connector_desc(128, 256, grid=4, dtype=ob.OB_FP32)
+    assert ob.ob_connector_saved_bytes(d32, n_tiles) == 2 * pad(n_tok * 512 * 4) + 2 * pad(n_tok * 256 * 4) + pad(n_tok * 8)
+    assert ob.ob_connector_workspace_bytes(d32, n_tiles) == 3 * pad(n_tok * 256 * 4) + 2 * pad(n_tok * 512 * 4)
     assert ob.ob_connector_saved_bytes(ob.make_connector_desc(128, 256, 5), n_tiles) == 0     # odd grid
     assert ob.ob_connector_saved_bytes(d, 0) == 0
 
