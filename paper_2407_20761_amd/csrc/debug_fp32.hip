@@ -11,8 +11,6 @@ namespace ob {
 namespace f32 {
 namespace {
 
-constexpr float LOG2E = 1.4426950408889634f;
-
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
