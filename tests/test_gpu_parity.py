@@ -176,9 +176,16 @@ def test_block_config1_fwd_bwd():
     _check_block(shape, cu, seed=0)
 
 
-@pytest.mark.parametrize("variant", ["llm-like", "vit-like", "vit-d128-rms"])
+@pytest.mark.parametrize("variant", ["llm-like", "llm-many-segments", "vit-like", "vit-d128-rms"])
 def test_block_small_variants(variant):
-    if variant == "llm-like":
+    if variant == "llm-many-segments":
+        # more segments than a wavefront has lanes (the rotary kernel's segment lookup and the attention
+        # kernels' tile lookup walk them in rounds), many of them shorter than a tile, token count odd
+        shape = si.small_shape(hidden=256, n_q_heads=4, n_kv_heads=1, head_dim=64, mlp_dim=256,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
+                               use_rotary=True, has_bias=False, norm_eps=1e-6)
+        lens = [1 + (7 * i) % 13 for i in range(150)] + [131, 2]
+    elif variant == "llm-like":
         shape = si.small_shape(hidden=512, n_q_heads=4, n_kv_heads=2, head_dim=128, mlp_dim=320,
                                norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
                                use_rotary=True, has_bias=False, norm_eps=1e-6)
