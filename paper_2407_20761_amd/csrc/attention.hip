@@ -37,6 +37,7 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float NEG_BIG = -1.0e30f;
 constexpr int QT = 128;  // rows owned by a workgroup (4 waves x 32)
+constexpr int QT_DQ = 64;  // the dQ kernel: 2 pairs of waves x 32 rows, two workgroups per CU
 constexpr int ST = 64;   // rows of a streamed tile
 constexpr int WAIT_VM0 = 0x0F70;  // s_waitcnt vmcnt(0) only
 
@@ -373,15 +374,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward, part 1: dQ.  A workgroup owns 128 query rows of one head and streams the segment's
+// backward, part 1: dQ.  A workgroup owns 64 query rows of one head and streams the segment's
 // 64-row key/value tiles (up to the diagonal when causal); P is rebuilt from the saved
-// log-sum-exp.  Eight wavefronts form four pairs, one pair per 32 query rows; the two waves of a
+// log-sum-exp.  Four wavefronts form two pairs, one pair per 32 query rows; the two waves of a
 // pair each take one 32-row half of every streamed tile through all three products
 //   S^T = K Q^T,  P = 2^(scale log2(e) S - lse2),  dP^T = V dO^T,  dS^T = P (dP^T - Delta),
 //   dQ^T += K^T dS^T
 // and keep their own dQ partial, which the pair adds once at the end through LDS.  Half the
 // per-wave state of a single-wave design, so two waves fit on a SIMD and hide each other's
-// element-wise work and LDS waits.
+// element-wise work and LDS waits; two workgroups share a CU, and as nothing synchronises them
+// their MFMA and element-wise phases drift apart (one eight-wave workgroup, whose per-tile barrier
+// kept the two waves of every SIMD in step, was 10 % slower; without its barriers, 12 % faster).
 // ------------------------------------------------------------------------------------------------
 template <int D, bool CAUSAL, bool MASK>
 __device__ __forceinline__ void dq_half(const unsigned char OB_LDS *__restrict__ ks,
@@ -448,7 +451,7 @@ __device__ __forceinline__ void dq_half(const unsigned char OB_LDS *__restrict__
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(512) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo, const int32_t *__restrict__ cu, int n_seg,
@@ -456,21 +459,22 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(
     // stages 0 / 1 of the K and V tiles; after the last tile the same bytes carry the dQ partials
     __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * Tile<D>::BYTES];
     __shared__ int sh[8];
-    const TileInfo ti = find_tile(cu, n_seg, QT, sh);
+    const TileInfo ti = find_tile(cu, n_seg, QT_DQ, sh);
     if (ti.row0 < 0) return;
     const int head = blockIdx.y, kvh = head / group;
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int pair = wave & 3, half = wave >> 2;
+    const int pair = wave & 1, half = wave >> 1;
     const int q_row = min(ti.row0 + pair * 32 + lx, ti.seg_end - 1);
     const bool q_live = ti.row0 + pair * 32 + lx < ti.seg_end;
     const int pair_q_last = min(ti.row0 + pair * 32 + 31, ti.seg_end - 1);
     const float sl2 = scale * LOG2E;
     constexpr int BYTES = Tile<D>::BYTES, DT = D / 32;
 
-    // waves 0-3 copy the K tiles, waves 4-7 the V tiles
-    Tile<D> tl;
+    // waves 0-1 copy the K tiles, waves 2-3 the V tiles: two quarters of a tile each
+    Tile<D> tl, tl2;
     tl.init(ldkv, pair, lane);
+    tl2.init(ldkv, pair + 2, lane);
     const unsigned char *const own_base = (const unsigned char *)((half ? v : k) + kvh * D);
     const long own_bytes = (long)T * ldkv * 2 - (long)kvh * D * 2;
 
@@ -488,12 +492,13 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_dq[i][r] = 0.f;
 
-    const int kv_end = CAUSAL ? min(ti.seg_end, ti.row0 + QT) : ti.seg_end;
+    const int kv_end = CAUSAL ? min(ti.seg_end, ti.row0 + QT_DQ) : ti.seg_end;
     const int n_tiles = (kv_end - ti.seg_start + ST - 1) / ST;
     unsigned char OB_LDS *const sm = (unsigned char OB_LDS *)smem;  // [stage][K | V][BYTES]
     {
         const long off = (long)ti.seg_start * ldkv * 2;
         tl.issue(own_base + off, own_bytes - off, sm + half * BYTES, pair);
+        tl2.issue(own_base + off, own_bytes - off, sm + half * BYTES, pair + 2);
     }
     const int n_main = CAUSAL ? (ti.row0 - ti.seg_start) / ST : (ti.seg_end - ti.seg_start) / ST;
     int j = 0;
@@ -505,6 +510,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dq_kernel(
         if (j + 1 < n_tiles) {                                                                              \
             const long off = (long)(kv0 + ST) * ldkv * 2;                                                   \
             tl.issue(own_base + off, own_bytes - off, sm + (1 - (STAGE)) * 2 * BYTES + half * BYTES, pair); \
+            tl2.issue(own_base + off, own_bytes - off, sm + (1 - (STAGE)) * 2 * BYTES + half * BYTES, pair + 2); \
         }                                                                                                   \
         const unsigned char OB_LDS *const ks = sm + (STAGE) * 2 * BYTES + half * 32 * Tile<D>::RB;          \
         const unsigned char OB_LDS *const vs = ks + BYTES;                                                  \
@@ -900,8 +906,8 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     const int T = seg->total_tokens, group = nq / nkv;
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
-        const dim3 grid_q(tiles, nq);
-        OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 512, (const __bf16 *)d_o, (const __bf16 *)q,
+        const dim3 grid_q(count_tiles(seg, QT_DQ), nq);
+        OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 256, (const __bf16 *)d_o, (const __bf16 *)q,
                          (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
                          seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
     }
