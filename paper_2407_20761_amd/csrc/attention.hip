@@ -20,6 +20,8 @@
 // read 16-byte fragments; products that contract over the streamed rows read the same tile with
 // the transposing LDS read (ds_read_b64_tr_b16), so no tile is ever stored twice.  16-byte chunks
 // are XOR-swizzled by the row so that both kinds of read are free of bank conflicts.
+#include <type_traits>
+
 #include "ob_internal.h"
 
 namespace ob {
@@ -566,9 +568,9 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 //   role G (waves 4-7):  dP = dO V^T,  dS = P (dP - Delta),           dK^T += Q^T dS
 // P travels from the first to the second through LDS in the packed operand layout both use.  Each
 // wave keeps half of the state a single wave would need (so two fit on a SIMD and one's MFMAs hide
-// the other's element-wise work and LDS waits), and no product is computed twice.  Seen from the
-// code the two roles differ only in which operands they pick: both run "row-fragment tile x held
-// rows -> 32x32 scores", then "transposed tile x packed scores -> output".
+// the other's element-wise work and LDS waits), and no product is computed twice.  Both roles run
+// "row-fragment tile x held rows -> 32x32 scores" and "transposed tile x packed scores -> output";
+// role G does the second one tile late (see the kernel), so that it never waits for its partner.
 // ------------------------------------------------------------------------------------------------
 // scores of a 64-row streamed tile against the 32 held rows: acc[mt] = rows 32 mt .. of the tile
 template <int D>
@@ -685,15 +687,11 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int ldq, int ldkv, int ldo,
     const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale) {
-    __shared__ __attribute__((aligned(1024))) unsigned char q_s0[Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char do_s0[Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char q_s1[Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char do_s1[Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char p_s[4 * 4096];  // per pair: 4 x 64 lanes x 16 B
-    __shared__ __attribute__((aligned(256))) float lse_s0[ST];
-    __shared__ __attribute__((aligned(256))) float dlt_s0[ST];
-    __shared__ __attribute__((aligned(256))) float lse_s1[ST];
-    __shared__ __attribute__((aligned(256))) float dlt_s1[ST];
+    // three stages of the streamed Q and dO tiles (the dK side works one tile behind the dV side, see
+    // below), two buffers for the probabilities on their way from one to the other, row statistics
+    __shared__ __attribute__((aligned(1024))) unsigned char tiles_s[6 * Tile<D>::BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char p_s[2 * 4 * 4096];  // [buffer][pair]: 4 x 64 lanes x 16 B
+    __shared__ __attribute__((aligned(256))) float stat_s[6 * ST];              // lse2 x 3 stages, Delta x 3 stages
     __shared__ int sh[8];
     const TileInfo ti = find_tile(cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
@@ -728,23 +726,26 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_out[i][r] = 0.f;
 
-    unsigned char OB_LDS *const qs0 = (unsigned char OB_LDS *)q_s0, *const qs1 = (unsigned char OB_LDS *)q_s1;
-    unsigned char OB_LDS *const dos0 = (unsigned char OB_LDS *)do_s0, *const dos1 = (unsigned char OB_LDS *)do_s1;
-    float OB_LDS *const lses0 = (float OB_LDS *)lse_s0, *const lses1 = (float OB_LDS *)lse_s1;
-    float OB_LDS *const dlts0 = (float OB_LDS *)dlt_s0, *const dlts1 = (float OB_LDS *)dlt_s1;
+    constexpr int BYTES = Tile<D>::BYTES;
+    unsigned char OB_LDS *const tiles = (unsigned char OB_LDS *)tiles_s;
+    float OB_LDS *const stats = (float OB_LDS *)stat_s;
+#define OB_QS(S) (tiles + (S) * BYTES)
+#define OB_DOS(S) (tiles + (3 + (S)) * BYTES)
+#define OB_LSES(S) (stats + (S) * ST)
+#define OB_DLTS(S) (stats + (3 + (S)) * ST)
     unsigned char OB_LDS *const p_mine = (unsigned char OB_LDS *)p_s + pair * 4096 + lane * 16;
 
     // causal: query rows before this workgroup's first key row see none of its keys
     const int q_begin = CAUSAL ? ti.seg_start + ((ti.row0 - ti.seg_start) / ST) * ST : ti.seg_start;
     const int n_iter = (ti.seg_end - q_begin + ST - 1) / ST;
-#define OB_ISSUE_DKV(hq_, it_, stage_)                                                                         \
-    do {                                                                                                       \
-        const int head_ = kvh * group + (hq_);                                                                 \
-        const int q0_ = q_begin + (it_) * ST;                                                                  \
-        const long off_ = (long)q0_ * own_ld2 + (long)head_ * D * 2;                                           \
-        tl.issue(own_base + off_, own_total - off_, role_g ? dos##stage_ : qs##stage_, pair);                  \
-        if (wave == 0) issue_row_stats(lse2_all + (size_t)head_ * T + q0_, (long)T - q0_, lses##stage_, lane); \
-        if (wave == 4) issue_row_stats(delta + (size_t)head_ * T + q0_, (long)T - q0_, dlts##stage_, lane);    \
+#define OB_ISSUE_DKV(hq_, it_, S)                                                                             \
+    do {                                                                                                      \
+        const int head_ = kvh * group + (hq_);                                                                \
+        const int q0_ = q_begin + (it_) * ST;                                                                 \
+        const long off_ = (long)q0_ * own_ld2 + (long)head_ * D * 2;                                          \
+        tl.issue(own_base + off_, own_total - off_, role_g ? OB_DOS(S) : OB_QS(S), pair);                     \
+        if (wave == 0) issue_row_stats(lse2_all + (size_t)head_ * T + q0_, (long)T - q0_, OB_LSES(S), lane);  \
+        if (wave == 4) issue_row_stats(delta + (size_t)head_ * T + q0_, (long)T - q0_, OB_DLTS(S), lane);     \
     } while (0)
     // causal: only the first two query tiles touch some pair's diagonal; either way only the last
     // tile can be ragged.  The tiles in between need no mask.
@@ -766,61 +767,93 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
         ++c.phase;
         if (c.phase == 1 && cnt1 == 0) c.phase = 2;
     };
+    // the whole walk once per role, chosen outside the loops: each role's loop then carries only its own
+    // registers (role G keeps dP across trips, role P does not)
+    auto walk = [&](auto role_tag) {
+    constexpr bool RG = decltype(role_tag)::value;
     Cursor cur = {0, 0, 0};
     if (cnt0 == 0) cur.phase = cnt1 ? 1 : 2;
     Cursor nxt = cur;
     step(nxt);
     OB_ISSUE_DKV(cur.hq, tile_of(cur), 0);
-#define OB_ISSUE_NEXT(stage_) OB_ISSUE_DKV(nxt.hq, tile_of(nxt), stage_)
-    int gi = 0;  // tiles done; its parity names the stage that holds the current tile
-#define OB_DKV_ITER(MASKED, QS, DOS, LSES, DLTS, ISSUE_NEXT)                                                 \
+    // The dK side runs one tile behind: in the trip of tile n the role-P wave does S, P, dV of tile n
+    // and leaves P in buffer n % 2, while the role-G wave first finishes tile n - 1 (dS from the P it
+    // finds in buffer (n - 1) % 2 and the dP it kept in registers, then dK) and then forms dP of tile
+    // n.  One barrier per tile instead of two, the role-G wave never waits for its partner inside a
+    // trip, and the two waves of a SIMD start a trip in different kinds of work (MFMAs / element-wise).
+    // Stage n % 3 holds tile n: the load of tile n + 1 overwrites tile n - 2, which nobody needs any more.
+    int gi = 0, st = 0;        // tiles done; stage of the current tile
+    int left1 = group * cnt1;  // mask-free tiles not yet done
+    bool live_prev = false;    // role G: tile n - 1 took part
+    f32x16 dp_keep[2];         // role G: dP of tile n - 1
+#define OB_DKV_ITER(MASKED, S, PREV, NEXT)                                                                   \
     {                                                                                                       \
         const int q0 = q_begin + tile_of(cur) * ST;                                                         \
         __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                               \
         __syncthreads();                                                                                    \
-        if (nxt.phase < 2) { ISSUE_NEXT; }                                                                  \
-        const unsigned char OB_LDS *const row_tile = role_g ? (DOS) : (QS);                                 \
-        const unsigned char OB_LDS *const tr_tile = role_g ? (QS) : (DOS);                                  \
-        const float OB_LDS *const stat = role_g ? (DLTS) : (LSES);                                          \
-        /* a masked tile entirely before this pair's keys contributes nothing (but keeps the barriers) */   \
+        if (nxt.phase < 2) OB_ISSUE_DKV(nxt.hq, tile_of(nxt), NEXT);                                        \
+        /* a masked tile entirely before this pair's keys contributes nothing */                            \
         const bool live = !((MASKED) && CAUSAL && q0 + ST - 1 < pair_kv_first);                             \
-        f32x16 acc_x[2];                                                                                    \
-        bf16x8 pk[2][2];                                                                                    \
-        if (live) dkv_scores<D>(row_tile, tl, kvf, acc_x);                                                  \
-        if (live && !role_g) {                                                                              \
-            dkv_probs<CAUSAL, MASKED>(acc_x, stat, q0, ti.seg_end, kv_row, sl2, pk);                        \
-            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                \
-                *(bf16x8 OB_LDS *)(p_mine + i_ * 1024) = pk[i_ >> 1][i_ & 1];                               \
+        if constexpr (!RG) {                                                                                \
+            if (live) {                                                                                     \
+                f32x16 acc_x[2];                                                                            \
+                bf16x8 pk[2][2];                                                                            \
+                dkv_scores<D>(OB_QS(S), tl, kvf, acc_x);                                                    \
+                dkv_probs<CAUSAL, MASKED>(acc_x, OB_LSES(S), q0, ti.seg_end, kv_row, sl2, pk);              \
+                _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                            \
+                    *(bf16x8 OB_LDS *)(p_mine + (gi & 1) * 16384 + i_ * 1024) = pk[i_ >> 1][i_ & 1];        \
+                dkv_outputs<D>(OB_DOS(S), tl, pk, acc_out);                                                 \
+            }                                                                                               \
+        } else {                                                                                            \
+            if (live_prev) {                                                                                \
+                bf16x8 pk[2][2];                                                                            \
+                _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                            \
+                    pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + ((gi - 1) & 1) * 16384 + i_ * 1024); \
+                dkv_dscores(dp_keep, OB_DLTS(PREV), pk);                                                    \
+                dkv_outputs<D>(OB_QS(PREV), tl, pk, acc_out);                                               \
+            }                                                                                               \
+            if (live) dkv_scores<D>(OB_DOS(S), tl, kvf, dp_keep);                                           \
+            live_prev = live;                                                                               \
         }                                                                                                   \
-        __syncthreads();                                                                                    \
-        if (live && role_g) {                                                                               \
-            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                                \
-                pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + i_ * 1024);                         \
-            dkv_dscores(acc_x, stat, pk);                                                                   \
-        }                                                                                                   \
-        if (live) dkv_outputs<D>(tr_tile, tl, pk, acc_out);                                                 \
+        if (cur.phase == 1) --left1;                                                                        \
         cur = nxt;                                                                                          \
         step(nxt);                                                                                          \
         ++gi;                                                                                               \
+        st = (NEXT);                                                                                        \
     }
-#define OB_DKV_STAGE0(MASKED) OB_DKV_ITER(MASKED, qs0, dos0, lses0, dlts0, OB_ISSUE_NEXT(1))
-#define OB_DKV_STAGE1(MASKED) OB_DKV_ITER(MASKED, qs1, dos1, lses1, dlts1, OB_ISSUE_NEXT(0))
-#define OB_DKV_ANY(MASKED)                                                                                 \
-    OB_DKV_ITER(MASKED, (gi & 1) ? qs1 : qs0, (gi & 1) ? dos1 : dos0, (gi & 1) ? lses1 : lses0,             \
-                (gi & 1) ? dlts1 : dlts0, if (gi & 1) OB_ISSUE_NEXT(0); else OB_ISSUE_NEXT(1))
+#define OB_DKV_ANY(MASKED)                                                                                   \
+    {                                                                                                       \
+        const int s_ = st, p_ = st == 0 ? 2 : st - 1, n_ = st == 2 ? 0 : st + 1;                            \
+        OB_DKV_ITER(MASKED, s_, p_, n_)                                                                     \
+    }
     while (cur.phase == 0) OB_DKV_ANY(true)
-    if ((gi & 1) && cur.phase == 1) OB_DKV_ANY(false)  // the two-tile loop below starts on stage 0
-    while (cur.phase == 1 && nxt.phase == 1) {  // gi is even here: two tiles per trip with constant stage buffers
-        OB_DKV_STAGE0(false)
-        OB_DKV_STAGE1(false)
+    while (st != 0 && cur.phase == 1) OB_DKV_ANY(false)   // the three-tile loop below starts on stage 0
+    while (left1 >= 3) {  // three tiles per trip: constant stage addresses, a single straight path
+        OB_DKV_ITER(false, 0, 2, 1)
+        OB_DKV_ITER(false, 1, 0, 2)
+        OB_DKV_ITER(false, 2, 1, 0)
     }
     while (cur.phase == 1) OB_DKV_ANY(false)
+    // the dK side still owes the last tile
+    __syncthreads();
+    if (RG && live_prev) {
+        const int p_ = st == 0 ? 2 : st - 1;
+        bf16x8 pk[2][2];
+#pragma unroll
+        for (int i_ = 0; i_ < 4; ++i_)
+            pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + ((gi - 1) & 1) * 16384 + i_ * 1024);
+        dkv_dscores(dp_keep, OB_DLTS(p_), pk);
+        dkv_outputs<D>(OB_QS(p_), tl, pk, acc_out);
+    }
+    };
+    if (role_g) walk(std::true_type{}); else walk(std::false_type{});
 #undef OB_DKV_ANY
-#undef OB_DKV_STAGE1
-#undef OB_DKV_STAGE0
 #undef OB_DKV_ITER
-#undef OB_ISSUE_NEXT
 #undef OB_ISSUE_DKV
+#undef OB_DLTS
+#undef OB_LSES
+#undef OB_DOS
+#undef OB_QS
     if (!kv_live) return;
     // dV^T / dK^T of the whole group of query heads sit in the accumulators: one rounding to bf16
     const float out_scale = role_g ? scale : 1.0f;
