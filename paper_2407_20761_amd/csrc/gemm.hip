@@ -84,7 +84,8 @@ struct Operand {
     static constexpr int LD = X / 8 / NW;
     static constexpr int ROWB = X * 2;
     const unsigned char *base;
-    uint32_t nrec, step;
+    long left;                                   // bytes from `base` to the end of the source
+    uint32_t step;                               // bytes per K step
     uint32_t voff[LD];
     int rd[KMAJOR ? T : BK / 32];                // LDS read offsets: per tile i (k-major) / per k-step u
 
@@ -103,8 +104,7 @@ struct Operand {
                                          int lane, int wave_x0) {
         if (!KMAJOR) {
             base = (const unsigned char *)(src + (size_t)x0 * ld);
-            const long left = total_bytes - (long)x0 * ld * 2;
-            nrec = (uint32_t)(left > 0xFFFFFFFFl ? 0xFFFFFFFFl : left);
+            left = total_bytes - (long)x0 * ld * 2;
             step = ROW_BYTES;
 #pragma unroll
             for (int p = 0; p < LD; ++p) {
@@ -118,8 +118,7 @@ struct Operand {
             for (int u = 0; u < BK / 32; ++u) rd[u] = (wave_x0 + lx) * ROW_BYTES + (((4 * u + lq) ^ f) * 16);
         } else {
             base = (const unsigned char *)(src + x0);
-            const long left = total_bytes - (long)x0 * 2;
-            nrec = (uint32_t)(left > 0xFFFFFFFFl ? 0xFFFFFFFFl : left);
+            left = total_bytes - (long)x0 * 2;
             step = (uint32_t)BK * (uint32_t)ld * 2u;
             constexpr int KPB = 1024 / ROWB, CPR = ROWB / 16;
 #pragma unroll
@@ -140,7 +139,7 @@ struct Operand {
     }
     __device__ __forceinline__ void advance() {
         base += step;
-        nrec = nrec > step ? nrec - step : 0u;
+        left -= step;
     }
     // descriptor of the current K step; must sit in scalar registers: pin its (uniform) parts explicitly
     // (live = false: an empty range, every load returns zeros without touching memory)
@@ -148,8 +147,11 @@ struct Operand {
         const uint64_t b = (uint64_t)base;
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+        // the range a descriptor can check is 32 bits wide: a source with more than 4 GB left is
+        // clamped (no access of a K step reaches that far from `base`), one past its end is empty
+        const long cl = left < 0 ? 0 : (left > 0xFFFFFFFFl ? 0xFFFFFFFFl : left);
         return __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)hi << 32) | lo), 0,
-                                                 live ? (int)__builtin_amdgcn_readfirstlane(nrec) : 0, 0x00020000);
+                                                 live ? (int)__builtin_amdgcn_readfirstlane((uint32_t)cl) : 0, 0x00020000);
     }
     // piece p (1 KB per wave) of this wave's share of the K step behind `rsrc`: global -> registers;
     // loads past the end of the source (rows beyond M / N / K) deliver zeros

@@ -73,6 +73,28 @@ def test_gemm_full_size_sampled_outputs(layout, M, N, K):
     assert rel_err(got, ref) < 5e-3
 
 
+@pytest.mark.parametrize("layout", [1, 2])
+def test_gemm_k_major_operand_larger_than_4_gib(layout):
+    """A k-major operand of more than 2^32 bytes: the 32-bit range of a buffer descriptor must not
+    cut the contraction short (sampled outputs against fp32 products of the same device tensors)."""
+    if layout == 2:
+        M, N, K = 32768, 64, 98304 + 37          # A [K, M]: 6.4 GB
+    else:
+        M, N, K = 64, 196608 + 64, 16384         # B [K, N]: 6.4 GB
+    _say(f"gemm >4 GiB operand layout={layout} M={M} N={N} K={K}")
+    gen = torch.Generator(device="cuda").manual_seed(11 + layout)
+    a = torch.randn((K, M) if layout == 2 else (M, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    b = torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ob.ob_gemm_bf16(layout, M, N, K, a, b, c, None, None, None)
+    rows = torch.tensor([0, 1, M // 2 + 3, M - 1], device="cuda")
+    cols = torch.tensor([0, 5, N // 2 + 1, N - 64, N - 1], device="cuda")
+    a_rows = (a[:, rows].T if layout == 2 else a[rows]).float()              # [4, K]
+    ref = (a_rows.double() @ b[:, cols].double()).cpu().numpy()
+    got = to_np(c[rows][:, cols])
+    assert rel_err(got, ref) < 5e-3
+
+
 # ---- attention ------------------------------------------------------------------------------
 
 ATTN_CASES = [
