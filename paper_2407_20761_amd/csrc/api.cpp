@@ -128,13 +128,18 @@ struct Layout {
     size_t off = 0;
     size_t take(size_t bytes) { const size_t o = off; off += align_up(bytes, 256); return o; }
 };
-struct Saved { size_t h1, qkv, o, lse, x1, h2, up, act, stat1, stat2, total; };
+size_t max4(size_t a, size_t b, size_t c, size_t d) { a = a > b ? a : b; c = c > d ? c : d; return a > c ? a : c; }
+struct Saved { size_t h1, qkv, o, lse, x1, h2, up, act, stat1, stat2, gemm, gemm_bytes, total; };
 Saved saved_layout(const Dims &m) {
     Layout L; Saved s; const size_t T = m.T;
     s.h1 = L.take(T * m.H * 2); s.qkv = L.take(T * m.Dqkv * 2); s.o = L.take(T * m.HD * 2);
     s.lse = L.take((size_t)m.nq * T * 4); s.x1 = L.take(T * m.H * 2); s.h2 = L.take(T * m.H * 2);
     s.up = L.take(T * m.upF * 2); s.act = L.take(T * m.F * 2);
     s.stat1 = L.take(T * 2 * 4); s.stat2 = L.take(T * 2 * 4);
+    // scratch of the forward GEMMs (slice sums of a split contraction), not read by the backward pass
+    s.gemm_bytes = max4(gemm_workspace_bytes(0, m.T, m.Dqkv, m.H), gemm_workspace_bytes(0, m.T, m.H, m.HD),
+                        gemm_workspace_bytes(0, m.T, m.upF, m.H), gemm_workspace_bytes(0, m.T, m.H, m.F));
+    s.gemm = L.take(s.gemm_bytes);
     s.total = L.off;
     return s;
 }
@@ -312,19 +317,20 @@ static void block_fwd_bf16(const ob_block_desc *desc, const ob_block_weights *w,
     unsigned char *h1 = at(saved, sv.h1), *qkv = at(saved, sv.qkv), *o = at(saved, sv.o);
     unsigned char *x1 = at(saved, sv.x1), *h2 = at(saved, sv.h2), *up = at(saved, sv.up), *act = at(saved, sv.act);
     float *lse = (float *)at(saved, sv.lse);
+    void *gws = sv.gemm_bytes ? at(saved, sv.gemm) : nullptr;
     const float scale = 1.0f / sqrtf((float)m.d);
 
     launch_norm_fwd(desc->norm, x, w->n1_g, beta ? w->n1_b : nullptr, h1, (float *)at(saved, sv.stat1), m.T, m.H, desc->norm_eps, s);
-    launch_gemm_nt(m.T, m.Dqkv, m.H, h1, m.H, w->w_qkv, m.H, qkv, m.Dqkv, bias ? w->b_qkv : nullptr, nullptr, 0, s);
+    launch_gemm_nt(m.T, m.Dqkv, m.H, h1, m.H, w->w_qkv, m.H, qkv, m.Dqkv, bias ? w->b_qkv : nullptr, nullptr, 0, s, 0, gws);
     if (desc->use_rotary)
         launch_rotary(qkv, m.Dqkv, m.T, m.nq + m.nkv, m.d, seg->cu_dev, seg->n_seg, desc->rotary_base, 1.0f, s);
     launch_attn_fwd(qkv, qkv + (size_t)m.nq * m.d * 2, qkv + (size_t)(m.nq + m.nkv) * m.d * 2, o, lse, m.Dqkv,
                     m.Dqkv, m.HD, seg, m.nq, m.nkv, m.d, scale, desc->mask, s);
-    launch_gemm_nt(m.T, m.H, m.HD, o, m.HD, w->w_o, m.HD, x1, m.H, bias ? w->b_o : nullptr, x, m.H, s);
+    launch_gemm_nt(m.T, m.H, m.HD, o, m.HD, w->w_o, m.HD, x1, m.H, bias ? w->b_o : nullptr, x, m.H, s, 0, gws);
     launch_norm_fwd(desc->norm, x1, w->n2_g, beta ? w->n2_b : nullptr, h2, (float *)at(saved, sv.stat2), m.T, m.H, desc->norm_eps, s);
-    launch_gemm_nt(m.T, m.upF, m.H, h2, m.H, w->w_up, m.H, up, m.upF, bias ? w->b_up : nullptr, nullptr, 0, s);
+    launch_gemm_nt(m.T, m.upF, m.H, h2, m.H, w->w_up, m.H, up, m.upF, bias ? w->b_up : nullptr, nullptr, 0, s, 0, gws);
     launch_act_fwd(desc->mlp, up, act, m.T, m.F, s);
-    if (y) launch_gemm_nt(m.T, m.H, m.F, act, m.F, w->w_down, m.F, y, m.H, bias ? w->b_down : nullptr, x1, m.H, s);
+    if (y) launch_gemm_nt(m.T, m.H, m.F, act, m.F, w->w_down, m.F, y, m.H, bias ? w->b_down : nullptr, x1, m.H, s, 0, gws);
 }
 
 extern "C" int ob_block_fwd(const ob_block_desc *desc, const ob_block_weights *w, const void *x, void *y,
@@ -429,7 +435,7 @@ extern "C" int ob_gemm_bf16(int layout, int M, int N, int K, const void *A, cons
     if (layout != 2 && K % 64) return fail(OB_EUNSUPPORTED, "ob_gemm_bf16: K = %d must be a multiple of 64 for layouts NT / NN", K);
     if (layout == 2 && M % 64) return fail(OB_EUNSUPPORTED, "ob_gemm_bf16: M = %d must be a multiple of 64 for layout TN", M);
     const size_t need = gemm_workspace_bytes(layout, M, N, K);
-    if (need && (!ws || ws_bytes < need)) return fail(OB_EWORKSPACE, "ob_gemm_bf16: workspace too small (%zu < %zu)", ws_bytes, need);
+    if (need && ws && ws_bytes < need) return fail(OB_EWORKSPACE, "ob_gemm_bf16: workspace too small (%zu < %zu)", ws_bytes, need);
     return gemm_any(layout, M, N, K, A, B, C, bias, R, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 

@@ -21,7 +21,9 @@
 // address of each lane's chunk is free to choose) so that LDS reads are bank-conflict free.
 // The weight-side rows are the MFMA's first operand, so a lane's accumulators are runs of four
 // consecutive output columns; the epilogue transposes them through LDS into full-row stores.
+#include <algorithm>
 #include <cmath>
+#include <cstdlib>
 
 #include "ob_internal.h"
 
@@ -38,14 +40,16 @@ namespace {
 constexpr int BK = 64;           // k per LDS stage: 8 chunks of 16 bytes = 128 bytes per row
 constexpr int ROW_BYTES = BK * 2;
 
-// tile id -> (tile_m, tile_n): each XCD (blocks are dealt round-robin to the 8 XCDs) gets one
-// contiguous range of tile ids, and ids walk groups of GM tile-rows column by column, so the
-// tiles resident on one XCD at a time share A and B panels in that XCD's L2.
-__device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int &tm, int &tn) {
-    const int nblk = gridDim.x, pid = blockIdx.x;
-    const int per = nblk >> 3, rem = nblk & 7;
+// Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous range of the `count`
+// work items that the workgroups [first, first + count) of a launch stand for (first % 8 == 0).
+__device__ __forceinline__ int xcd_chunk(int pid, int count) {
+    const int per = count >> 3, rem = count & 7;
     const int xcd = pid & 7, loc = pid >> 3;
-    const int tile = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
+    return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
+}
+// tile id -> (tile_m, tile_n): ids walk groups of GM tile-rows column by column, so the tiles
+// resident on one XCD at a time share A and B panels in that XCD's L2.
+__device__ __forceinline__ void tile_of_id(int tile, int tiles_m, int tiles_n, int &tm, int &tn) {
     constexpr int GM = 8;
     const int width = GM * tiles_n;
     const int group = tile / width;
@@ -55,6 +59,14 @@ __device__ __forceinline__ void tile_coords(int tiles_m, int tiles_n, int &tm, i
     tm = first_m + in_group % gsz;
     tn = in_group / gsz;
 }
+
+// The tiles [n_full, n_full + n_tail) of a GEMM, those of an incomplete last round, have their
+// contraction cut into `splits` slices of k_chunk K steps; a slice leaves the fp32 sums of its
+// BM x BN tile at part[slice][tile - n_full] and tail_sum_kernel adds the slices.
+struct TailSplit {
+    float *part;          // null: no tile is split
+    int n_full, n_tail, splits, k_chunk;
+};
 
 template <int BM, int BN, int WM, int WN>
 struct Cfg {
@@ -140,6 +152,11 @@ struct Operand {
     __device__ __forceinline__ void advance() {
         base += step;
         left -= step;
+    }
+    // start the contraction `steps` K steps into the source
+    __device__ __forceinline__ void skip(int steps) {
+        base += (long)steps * step;
+        left -= (long)steps * step;
     }
     // descriptor of the current K step; must sit in scalar registers: pin its (uniform) parts explicitly
     // (live = false: an empty range, every load returns zeros without touching memory)
@@ -298,14 +315,19 @@ template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     int M, int N, int K, const __bf16 *__restrict__ A, int lda, const __bf16 *__restrict__ B,
     int ldb, __bf16 *__restrict__ Cm, int ldc, const __bf16 *__restrict__ bias,
-    const __bf16 *R, int ldr, int tiles_m, int tiles_n) {
+    const __bf16 *R, int ldr, int tiles_m, int tiles_n, TailSplit ts) {
     using C = Cfg<BM, BN, WM, WN>;
     constexpr int T = C::T;
     __shared__ __attribute__((aligned(1024))) unsigned char st0[C::STAGE];
     __shared__ __attribute__((aligned(1024))) unsigned char st1[C::STAGE];
 
+    // workgroups [0, n_full): whole tiles; then slice after slice of the tail tiles
+    const int pid = blockIdx.x, n_whole = ts.part ? ts.n_full : (int)gridDim.x;
+    const bool sliced = pid >= n_whole;
+    const int kz = sliced ? (pid - n_whole) / ts.n_tail : 0;
+    const int tail_tile = sliced ? xcd_chunk((pid - n_whole) % ts.n_tail, ts.n_tail) : 0;
     int tile_m, tile_n;
-    tile_coords(tiles_m, tiles_n, tile_m, tile_n);
+    tile_of_id(sliced ? n_whole + tail_tile : xcd_chunk(pid, n_whole), tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = __builtin_amdgcn_readfirstlane(tile_m) * BM;
     const int n0 = __builtin_amdgcn_readfirstlane(tile_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -328,7 +350,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 
     unsigned char OB_LDS *s0 = (unsigned char OB_LDS *)st0;
     unsigned char OB_LDS *s1 = (unsigned char OB_LDS *)st1;
-    const int nk = (K + BK - 1) / BK;
+    // a slice covers K steps [k_first, k_first + nk)
+    const int k_first = kz * ts.k_chunk;
+    const int nk = sliced ? min(ts.k_chunk, (K + BK - 1) / BK - k_first) : (K + BK - 1) / BK;
+    lp.opa.skip(k_first);
+    lp.opb.skip(k_first);
     lp.k_left = nk;
     // prologue: K step 0 into stage 0; K step 1 requested, the copy groups that follow a barrier
     // delivered to stage 1 and re-requested for K step 2: the state behind the barrier of a K step
@@ -404,7 +430,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             const f32x4 lo = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32);
             const f32x4 hi = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32 + 16);
             const int m = m0 + wm * (BM / WM) + ii * 32 + row;
-            if (m < M && n_out < N) {
+            if (sliced) {   // the whole tile, also its rows and columns beyond M and N (zeros)
+                float *dst = ts.part + ((size_t)(kz * ts.n_tail + tail_tile) * BM + (m - m0)) * BN + (n_out - n0);
+                *(f32x4 *)dst = lo;
+                *(f32x4 *)(dst + 4) = hi;
+            } else if (m < M && n_out < N) {
                 float o8[8];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) { o8[e] = lo[e] + bv[e]; o8[4 + e] = hi[e] + bv[4 + e]; }
@@ -425,7 +455,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #define OB_GEMM_INSTANCE(BM, BN, AK, BKM)                                                        \
     template __global__ void gemm_kernel<BM, BN, 2, 2, AK, BKM>(                                 \
         int, int, int, const __bf16 *, int, const __bf16 *, int, __bf16 *, int, const __bf16 *,    \
-        const __bf16 *, int, int, int);
+        const __bf16 *, int, int, int, TailSplit);
 OB_GEMM_INSTANCE(256, 256, false, false)
 OB_GEMM_INSTANCE(128, 128, false, false)
 OB_GEMM_INSTANCE(256, 256, false, true)
@@ -434,54 +464,169 @@ OB_GEMM_INSTANCE(256, 256, true, true)
 OB_GEMM_INSTANCE(128, 128, true, true)
 #undef OB_GEMM_INSTANCE
 
-template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
-void launch_tile(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
-                 const void *bias, const void *R, int ldr, hipStream_t s) {
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, AK, BKM>), dim3(tiles_m * tiles_n), dim3(WM * WN * 64),
-                       0, s, M, N, K, (const __bf16 *)A, lda, (const __bf16 *)B, ldb, (__bf16 *)C, ldc,
-                       (const __bf16 *)bias, (const __bf16 *)R, ldr, tiles_m, tiles_n);
+// C = sum over the slices of the tail tiles' fp32 sums (+ bias) (+ R); 8 outputs per lane, slices
+// added in order
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void tail_sum_kernel(TailSplit ts, int M, int N, int tiles_m, int tiles_n,
+                                                       const __bf16 *__restrict__ bias, const __bf16 *R, int ldr,
+                                                       __bf16 *__restrict__ Cm, int ldc) {
+    constexpr int PER_TILE = BM * BN / 8 / 256;      // workgroups per tile
+    const int t = blockIdx.x / PER_TILE;
+    const int e = ((blockIdx.x % PER_TILE) * 256 + threadIdx.x) * 8;
+    int tile_m, tile_n;
+    tile_of_id(ts.n_full + t, tiles_m, tiles_n, tile_m, tile_n);
+    const int m = tile_m * BM + e / BN, n = tile_n * BN + e % BN;
+    if (m >= M || n >= N) return;
+    const float *src = ts.part + (size_t)t * (BM * BN) + e;
+    const size_t slice = (size_t)ts.n_tail * (BM * BN);
+    f32x4 lo = *(const f32x4 *)src, hi = *(const f32x4 *)(src + 4);
+    for (int z = 1; z < ts.splits; ++z) {
+        lo += *(const f32x4 *)(src + z * slice);
+        hi += *(const f32x4 *)(src + z * slice + 4);
+    }
+    float o8[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { o8[i] = lo[i]; o8[4 + i] = hi[i]; }
+    if (bias) {
+        const bf16x8 b8 = *(const bf16x8 *)(bias + n);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o8[i] += (float)b8[i];
+    }
+    if (R) {
+        const bf16x8 r8 = *(const bf16x8 *)(R + (size_t)m * ldr + n);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o8[i] += (float)r8[i];
+    }
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = (__bf16)o8[i];
+    *(bf16x8 *)(Cm + (size_t)m * ldc + n) = o;
 }
 
-template <bool AK, bool BKM>
-void launch_layout(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
-                   const void *bias, const void *R, int ldr, hipStream_t s) {
-    // 256x256 tiles run one workgroup per CU, 128x128 tiles two; take the shape whose last round
-    // of tiles leaves fewer CUs idle.  Two small workgroups on a CU deliver about 0.72 of a big
-    // one's rate (twice the fragment reads per MFMA); measured: dW_qkv of config 3 (6144 x 4096,
-    // 1.5 rounds of big tiles against 3 full rounds of small ones) 782 against 905 us, 1024 x 4096
-    // (a quarter round of big tiles) 236 against 114 us.
-    const double big = (double)((M + 255) / 256) * ((N + 255) / 256);
-    const double small = (double)((M + 127) / 128) * ((N + 127) / 128);
+// How a GEMM is cut into workgroups: tile size, and which tiles have their contraction split.
+struct Plan {
+    bool big;
+    int n_full, n_tail, splits, k_chunk;   // splits == 1: every tile whole
+    size_t part_bytes() const { return splits > 1 ? (size_t)splits * n_tail * (big ? 256 * 256 : 128 * 128) * 4 : 0; }
+};
+
+// 256x256 tiles run one workgroup per CU, 128x128 tiles two; unsplit, take the shape whose last
+// round of tiles leaves fewer CUs idle.  Two small workgroups on a CU deliver about 0.72 of a big
+// one's rate (twice the fragment reads per MFMA); measured: 1024 x 4096 over 16325 tokens (a
+// quarter round of big tiles) 236 against 114 us.
+//
+// Tiles come in rounds of one per CU (two for small tiles), and the tiles of an incomplete last
+// round take as long as a full one: measured over 16325 tokens, 4096 x 12288 (3 rounds) runs at
+// 1409 TFLOP/s, 4096 x 14336 (3.5 rounds) at 1178, 4096 x 5120 (1.25 rounds) at 1008.  When the
+// caller has room for fp32 sums (`can_split`), the contraction of those last tiles is cut into as
+// many slices as fill the round, each slice a workgroup with a shorter K loop; a second kernel adds
+// the slices.  A GEMM of less than one round (the hidden x hidden weight gradients of a narrow
+// model over all tokens of the batch) is all tail.  Writing and re-reading the sums is dear (8 bytes
+// per element and slice), so the estimate has to promise a gain.  It counts microseconds as measured
+// on a mostly idle chip: a K step of a big tile 1.3, of a small tile 0.47 with a CU to itself and
+// 0.9 when it shares one; 3 K steps' worth of prologue and epilogue; the sums move at 4 TB/s; 3 for
+// the second launch.
+double estimate_us(bool big, int nk, double n_full, double n_tail, int splits, int k_chunk) {
+    const double slots = big ? 256.0 : 512.0;
+    const double area = big ? 65536.0 : 16384.0;
+    const bool roomy = !big && n_full == 0 && n_tail * splits <= 256.0;
+    const double step = big ? 1.3 : (roomy ? 0.47 : 0.9);
+    double t = n_full / slots * (nk + 3) * step;
+    if (splits > 1) t += ceil(n_tail * splits / slots) * (k_chunk + 3) * step + splits * n_tail * area * 8.0 / 4e6 + 3.0;
+    else t += ceil(n_tail / slots) * (nk + 3) * step;
+    return t;
+}
+
+Plan make_plan(int M, int N, int K, bool can_split) {
+    const int big = ((M + 255) / 256) * ((N + 255) / 256);
+    const int small = ((M + 127) / 128) * ((N + 127) / 128);
     const double eff_big = big / (ceil(big / 256.0) * 256.0);
     const double eff_small = 0.72 * small / (ceil(small / 512.0) * 512.0);
-    if (eff_big >= eff_small)
-        launch_tile<256, 256, 2, 2, AK, BKM>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
+    const bool use_big = eff_big >= eff_small;
+    Plan p{use_big, use_big ? big : small, 0, 1, 0};
+    const int nk = (K + BK - 1) / BK;
+    if (can_split && nk >= 16) {
+        double best = 0.93 * estimate_us(p.big, nk, 0, p.n_full, 1, 0);
+        for (int tile_big = 0; tile_big < 2; ++tile_big) {
+            const int tiles = tile_big ? big : small, slots = tile_big ? 256 : 512;
+            const int n_tail = tiles % slots, n_full = tiles - n_tail;
+            if (n_tail == 0) continue;
+            for (int z = 2; z <= 8 && nk / z >= 8; ++z) {
+                const int chunk = ((nk + z - 1) / z + 1) & ~1;       // whole trips of the two-step loop
+                const int slices = (nk + chunk - 1) / chunk;         // every slice has at least one K step
+                if (slices < 2) continue;
+                const double t = estimate_us(tile_big, nk, n_full, n_tail, slices, chunk);
+                if (t < best) { best = t; p = Plan{tile_big != 0, n_full, n_tail, slices, chunk}; }
+            }
+        }
+    }
+#ifdef OB_GEMM_TUNE   // build-time hook of the tile / split sweeps: OB_TILE=big|small, OB_SPLIT=n
+    if (getenv("OB_TILE") || getenv("OB_SPLIT")) {
+        if (const char *e = getenv("OB_TILE")) p.big = e[0] == 'b';
+        const int tiles = p.big ? big : small, slots = p.big ? 256 : 512;
+        const int z = getenv("OB_SPLIT") ? std::min(atoi(getenv("OB_SPLIT")), nk / 2) : 1;
+        p = Plan{p.big, tiles, 0, 1, 0};
+        if (z > 1 && can_split && tiles % slots) {
+            p.n_tail = tiles % slots;
+            p.n_full = tiles - p.n_tail;
+            p.k_chunk = ((nk + z - 1) / z + 1) & ~1;
+            p.splits = (nk + p.k_chunk - 1) / p.k_chunk;
+            if (p.splits < 2) p = Plan{p.big, tiles, 0, 1, 0};
+        }
+    }
+#endif
+    return p;
+}
+
+template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
+void launch_tile(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
+                 const void *bias, const void *R, int ldr, float *part, const Plan &p, hipStream_t s) {
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const TailSplit ts{p.splits > 1 ? part : nullptr, p.n_full, p.n_tail, p.splits, p.k_chunk};
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, AK, BKM>), dim3(p.n_full + p.n_tail * p.splits),
+                       dim3(WM * WN * 64), 0, s, M, N, K, (const __bf16 *)A, lda, (const __bf16 *)B, ldb,
+                       (__bf16 *)C, ldc, (const __bf16 *)bias, (const __bf16 *)R, ldr, tiles_m, tiles_n, ts);
+    if (p.splits > 1)
+        hipLaunchKernelGGL((tail_sum_kernel<BM, BN>), dim3(p.n_tail * (BM * BN / 8 / 256)), dim3(256), 0, s, ts, M, N,
+                           tiles_m, tiles_n, (const __bf16 *)bias, (const __bf16 *)R, ldr, (__bf16 *)C, ldc);
+}
+
+// `part` (may be null: nothing is split) has room for the plan's fp32 sums
+template <bool AK, bool BKM>
+void launch_layout(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C, int ldc,
+                   const void *bias, const void *R, int ldr, float *part, hipStream_t s) {
+    const Plan p = make_plan(M, N, K, part != nullptr);
+    if (p.big)
+        launch_tile<256, 256, 2, 2, AK, BKM>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, part, p, s);
     else
-        launch_tile<128, 128, 2, 2, AK, BKM>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
+        launch_tile<128, 128, 2, 2, AK, BKM>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, part, p, s);
 }
 
 }  // namespace
 
-void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
-                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s, int k_algo) {
-    ProfScope prof(K_GEMM, s, 2.0 * M * N * (k_algo > 0 ? k_algo : K));
-    launch_layout<false, false>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, s);
-}
+// fp32 sums of the slices of the tiles whose contraction is split; 0 for a GEMM without such tiles
+size_t gemm_workspace_bytes(int, int M, int N, int K) { return make_plan(M, N, K, true).part_bytes(); }
 
-size_t gemm_workspace_bytes(int, int, int, int) { return 0; }
+// ws (may be null): gemm_workspace_bytes(0, M, N, K) bytes
+void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
+                    int ldc, const void *bias, const void *R, int ldr, hipStream_t s, int k_algo, void *ws) {
+    ProfScope prof(K_GEMM, s, 2.0 * M * N * (k_algo > 0 ? k_algo : K));
+    launch_layout<false, false>(M, N, K, A, lda, B, ldb, C, ldc, bias, R, ldr, (float *)ws, s);
+}
 
 // layout 0 ("NT"): A[M,K] B[N,K]; 1 ("NN"): A[M,K] B[K,N]; 2 ("TN"): A[K,M] B[K,N].  All three
 // run natively: a K-major operand is staged as it lies in memory and transposed by the LDS read.
+// The timed span of a GEMM with split tiles includes the kernel that sums the slices.
 int gemm_any(int layout, int M, int N, int K, const void *A, const void *B, void *C,
-             const void *bias, const void *R, void *, size_t, hipStream_t s) {
+             const void *bias, const void *R, void *ws, size_t ws_bytes, hipStream_t s) {
     ProfScope prof(K_GEMM, s, 2.0 * M * N * K);
+    float *part = ws && ws_bytes >= gemm_workspace_bytes(layout, M, N, K) ? (float *)ws : nullptr;
     if (layout == 0)
-        launch_layout<false, false>(M, N, K, A, K, B, K, C, N, bias, R, N, s);
+        launch_layout<false, false>(M, N, K, A, K, B, K, C, N, bias, R, N, part, s);
     else if (layout == 1)
-        launch_layout<false, true>(M, N, K, A, K, B, N, C, N, bias, R, N, s);
+        launch_layout<false, true>(M, N, K, A, K, B, N, C, N, bias, R, N, part, s);
     else
-        launch_layout<true, true>(M, N, K, A, M, B, N, C, N, bias, R, N, s);
+        launch_layout<true, true>(M, N, K, A, M, B, N, C, N, bias, R, N, part, s);
     return check_launch("gemm");
 }
 

@@ -31,9 +31,10 @@ struct ProfScope {
 // ---- GEMM (gemm.hip) ---------------------------------------------------------------------
 // C[M,N] = A[M,K] B[N,K]^T (+bias[N]) (+R[M,N]); K % 64 == 0, N % 8 == 0, any M.
 // k_algo (<= K, 0 = K): the contraction length that counts as algorithmic work when K is padded.
+// ws (may be null): gemm_workspace_bytes(0, M, N, K) bytes of scratch for a split contraction.
 void launch_gemm_nt(int M, int N, int K, const void *A, int lda, const void *B, int ldb, void *C,
                     int ldc, const void *bias, const void *R, int ldr, hipStream_t s,
-                    int k_algo = 0);
+                    int k_algo = 0, void *ws = nullptr);
 size_t gemm_workspace_bytes(int layout, int M, int N, int K);
 int gemm_any(int layout, int M, int N, int K, const void *A, const void *B, void *C,
              const void *bias, const void *R, void *ws, size_t ws_bytes, hipStream_t s);

@@ -54,6 +54,37 @@ def test_gemm_against_fp64_matmul(layout, M, N, K):
     assert rel_err(to_np(c2), ref + bias + R) < 5e-3
 
 
+@pytest.mark.parametrize("layout,M,N,K", [(2, 1024, 1024, 12300), (2, 2048, 1024, 12300), (2, 512, 1024, 8219),
+                                          (2, 64, 64, 1000), (0, 257, 256, 4096), (1, 700, 512, 2112),
+                                          (2, 4096, 5120, 4100), (0, 4100, 4992, 4096), (1, 2500, 8192, 4160)])
+def test_gemm_split_contraction(layout, M, N, K):
+    """The tiles of an incomplete last round (all tiles, for the small weight gradients of config 2) have
+    their contraction cut into slices whose fp32 sums a second kernel adds; the last slice is shorter
+    than the rest, and the last three cases keep whole tiles beside the split ones."""
+    _say(f"gemm split layout={layout} M={M} N={N} K={K}")
+    need = ob.ob_gemm_workspace_bytes(layout, M, N, K)
+    assert need > 0                                                  # this case does split
+    rng = np.random.default_rng(M + N + K + layout)
+    A = si.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
+    B = si.round_to_bf16(rng.standard_normal((N, K), dtype=np.float32))
+    bias = si.round_to_bf16(rng.standard_normal((N,), dtype=np.float32))
+    R = si.round_to_bf16(rng.standard_normal((M, N), dtype=np.float32) * 4)
+    ref = A.astype(np.float64) @ B.astype(np.float64).T
+    a_dev = to_dev(A if layout != 2 else A.T.copy())
+    b_dev = to_dev(B if layout == 0 else B.T.copy())
+    ws = bytes_buf(need)
+    ws.fill_(0x7F)                                                   # stale contents must not matter
+    c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    ob.ob_gemm_bf16(layout, M, N, K, a_dev, b_dev, c, None, None, ws)
+    assert rel_err(to_np(c), ref) < 5e-3
+    c2 = to_dev(R)
+    ob.ob_gemm_bf16(layout, M, N, K, a_dev, b_dev, c2, to_dev(bias), c2, ws)   # in-place + bias
+    assert rel_err(to_np(c2), ref + bias + R) < 5e-3
+    c3 = torch.empty_like(c)
+    ob.ob_gemm_bf16(layout, M, N, K, a_dev, b_dev, c3, None, None, None)       # no scratch: unsplit
+    assert rel_err(to_np(c3), ref) < 5e-3
+
+
 @pytest.mark.parametrize("layout,M,N,K", [(0, 16384, 28672, 4096), (1, 16384, 4096, 14336), (2, 4096, 14336, 16325)])
 def test_gemm_full_size_sampled_outputs(layout, M, N, K):
     """Config 3's largest GEMMs in the launch shape the benchmark times (256x256 tiles, one per CU);
@@ -86,7 +117,8 @@ def test_gemm_k_major_operand_larger_than_4_gib(layout):
     a = torch.randn((K, M) if layout == 2 else (M, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     b = torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    ob.ob_gemm_bf16(layout, M, N, K, a, b, c, None, None, None)
+    ws = bytes_buf(ob.ob_gemm_workspace_bytes(layout, M, N, K))    # layout 2 splits: the second slice starts past 4 GiB
+    ob.ob_gemm_bf16(layout, M, N, K, a, b, c, None, None, ws)
     rows = torch.tensor([0, 1, M // 2 + 3, M - 1], device="cuda")
     cols = torch.tensor([0, 5, N // 2 + 1, N - 64, N - 1], device="cuda")
     a_rows = (a[:, rows].T if layout == 2 else a[rows]).float()              # [4, K]

@@ -166,8 +166,12 @@ def test_gemm_argument_validation():
     assert call(0, 64, 100, 64) == ob.OB_EUNSUPPORTED
     assert call(0, 64, 64, 100) == ob.OB_EUNSUPPORTED
     assert call(2, 100, 64, 77) == ob.OB_EUNSUPPORTED
-    for layout in (0, 1, 2):                      # all three layouts run without scratch
+    for layout in (0, 1, 2):                      # enough tiles, or a short contraction: no scratch
         assert ob.ob_gemm_workspace_bytes(layout, 128, 64, 128) == 0
+        assert ob.ob_gemm_workspace_bytes(layout, 16384, 4096, 16384) == 0
+    # 64 tiles of 128 x 128 over 193 K steps: 4 slices of fp32 sums, a tile on every CU
+    assert ob.ob_gemm_workspace_bytes(2, 1024, 1024, 12300) == 4 * 1024 * 1024 * 4
+    assert call(2, 1024, 1024, 12300, wsb=1024) == ob.OB_EWORKSPACE
     assert ob.lib.ob_debug_materialize_mask(C.byref(_seg([0, 4]).c), 1, None, None) == ob.OB_EINVAL
 
 
