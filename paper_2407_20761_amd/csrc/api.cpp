@@ -143,15 +143,17 @@ Saved saved_layout(const Dims &m) {
     s.total = L.off;
     return s;
 }
-struct Work { size_t dact, dup, dh, dx1, d_o, dqkv, delta, lse2, partial, gemm, gemm_bytes, total; };
-size_t max3(size_t a, size_t b, size_t c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
+struct Work { size_t dact, dup, dh, dx1, d_o, dqkv, delta, lse2, p_down, p_up, p_o, p_qkv, p_n2, p_n1, gemm, gemm_bytes, total; };
 Work work_layout(const Dims &m) {
     Layout L; Work w; const size_t T = m.T;
     w.dact = L.take(T * m.F * 2); w.dup = L.take(T * m.upF * 2); w.dh = L.take(T * m.H * 2);
     w.dx1 = L.take(T * m.H * 2); w.d_o = L.take(T * m.HD * 2); w.dqkv = L.take(T * m.Dqkv * 2);
     w.delta = L.take((size_t)m.nq * T * 4); w.lse2 = L.take((size_t)m.nq * T * 4);
-    const size_t maxC = max3(m.upF, m.Dqkv, m.H);
-    w.partial = L.take(max3((size_t)norm_bwd_partials(m.T) * 2 * m.H * 4, (size_t)colsum_partials(m.T) * maxC * 4, 0));
+    // fp32 partial sums of the column reductions, one region each: they are all summed by one
+    // launch at the end of the backward pass
+    const size_t ncs = colsum_partials(m.T), nnb = norm_bwd_partials(m.T);
+    w.p_down = L.take(ncs * m.H * 4); w.p_up = L.take(ncs * m.upF * 4); w.p_o = L.take(ncs * m.H * 4);
+    w.p_qkv = L.take(ncs * m.Dqkv * 4); w.p_n2 = L.take(nnb * 2 * m.H * 4); w.p_n1 = L.take(nnb * 2 * m.H * 4);
     size_t g = 0;
     auto upd = [&](int layout, int M, int N, int K) { const size_t b = gemm_workspace_bytes(layout, M, N, K); if (b > g) g = b; };
     upd(1, m.T, m.F, m.H);      // dact  = dy W_down
@@ -376,30 +378,36 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
     const float *lse = (const float *)at(saved, sv.lse);
     unsigned char *dact = at(ws, wk.dact), *dup = at(ws, wk.dup), *dh = at(ws, wk.dh), *dx1 = at(ws, wk.dx1);
     unsigned char *d_o = at(ws, wk.d_o), *dqkv = at(ws, wk.dqkv), *gws = at(ws, wk.gemm);
-    float *delta = (float *)at(ws, wk.delta), *partial = (float *)at(ws, wk.partial);
+    float *delta = (float *)at(ws, wk.delta);
     const float scale = 1.0f / sqrtf((float)m.d);
     const int ncs = colsum_partials(m.T), nnb = norm_bwd_partials(m.T);
     int rc;
-    auto bias_grad = [&](const void *src, int C, void *out) {
+    ReduceBatch sums;      // the column reductions' second halves, launched together at the end
+    auto bias_grad = [&](const void *src, int C, size_t region, void *out) {
+        float *partial = (float *)at(ws, region);
         launch_colsum(src, m.T, C, C, partial, s);
-        launch_reduce_partials(partial, ncs, C, out, C, acc, s);
+        sums.add(partial, ncs, C, out, C);
+    };
+    auto norm_grads = [&](size_t region, void *gamma_out, void *beta_out) {
+        const float *partial = (const float *)at(ws, region);
+        sums.add(partial, nnb, 2 * m.H, gamma_out, m.H);
+        if (beta) sums.add(partial + m.H, nnb, 2 * m.H, beta_out, m.H);
     };
 
     // y = x1 + act W_down^T + b_down
     if ((rc = gemm_any(1, m.T, m.F, m.H, dy, w->w_down, dact, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     if ((rc = gemm_any(2, m.H, m.F, m.T, dy, act, g->w_down, nullptr, acc ? g->w_down : nullptr, gws, wk.gemm_bytes, s))) return rc;
-    if (bias) bias_grad(dy, m.H, g->b_down);
+    if (bias) bias_grad(dy, m.H, wk.p_down, g->b_down);
     launch_act_bwd(desc->mlp, dact, up, dup, m.T, m.F, s);
     if ((rc = gemm_any(2, m.upF, m.H, m.T, dup, h2, g->w_up, nullptr, acc ? g->w_up : nullptr, gws, wk.gemm_bytes, s))) return rc;
-    if (bias) bias_grad(dup, m.upF, g->b_up);
+    if (bias) bias_grad(dup, m.upF, wk.p_up, g->b_up);
     if ((rc = gemm_any(1, m.T, m.H, m.upF, dup, w->w_up, dh, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // dx1 = dy + norm2_bwd(dh2)
-    launch_norm_bwd(desc->norm, dh, x1, (const float *)at(saved, sv.stat2), w->n2_g, dy, dx1, partial, m.T, m.H, s);
-    launch_reduce_partials(partial, nnb, 2 * m.H, g->n2_g, m.H, acc, s);
-    if (beta) launch_reduce_partials(partial + m.H, nnb, 2 * m.H, g->n2_b, m.H, acc, s);
+    launch_norm_bwd(desc->norm, dh, x1, (const float *)at(saved, sv.stat2), w->n2_g, dy, dx1, (float *)at(ws, wk.p_n2), m.T, m.H, s);
+    norm_grads(wk.p_n2, g->n2_g, g->n2_b);
     // x1 = x + o W_o^T + b_o
     if ((rc = gemm_any(2, m.H, m.HD, m.T, dx1, o, g->w_o, nullptr, acc ? g->w_o : nullptr, gws, wk.gemm_bytes, s))) return rc;
-    if (bias) bias_grad(dx1, m.H, g->b_o);
+    if (bias) bias_grad(dx1, m.H, wk.p_o, g->b_o);
     if ((rc = gemm_any(1, m.T, m.HD, m.H, dx1, w->w_o, d_o, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // attention
     float *lse2 = (float *)at(ws, wk.lse2);
@@ -412,12 +420,12 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
         launch_rotary(dqkv, m.Dqkv, m.T, m.nq + m.nkv, m.d, seg->cu_dev, seg->n_seg, desc->rotary_base, -1.0f, s);
     // qkv = h1 W_qkv^T + b_qkv
     if ((rc = gemm_any(2, m.Dqkv, m.H, m.T, dqkv, h1, g->w_qkv, nullptr, acc ? g->w_qkv : nullptr, gws, wk.gemm_bytes, s))) return rc;
-    if (bias) bias_grad(dqkv, m.Dqkv, g->b_qkv);
+    if (bias) bias_grad(dqkv, m.Dqkv, wk.p_qkv, g->b_qkv);
     if ((rc = gemm_any(1, m.T, m.H, m.Dqkv, dqkv, w->w_qkv, dh, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // dx = dx1 + norm1_bwd(dh1)
-    launch_norm_bwd(desc->norm, dh, x, (const float *)at(saved, sv.stat1), w->n1_g, dx1, dx, partial, m.T, m.H, s);
-    launch_reduce_partials(partial, nnb, 2 * m.H, g->n1_g, m.H, acc, s);
-    if (beta) launch_reduce_partials(partial + m.H, nnb, 2 * m.H, g->n1_b, m.H, acc, s);
+    launch_norm_bwd(desc->norm, dh, x, (const float *)at(saved, sv.stat1), w->n1_g, dx1, dx, (float *)at(ws, wk.p_n1), m.T, m.H, s);
+    norm_grads(wk.p_n1, g->n1_g, g->n1_b);
+    launch_reduce_batch(sums, acc, s);
     return check_launch("ob_block_bwd");
 }
 

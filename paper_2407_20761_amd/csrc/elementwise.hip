@@ -7,6 +7,7 @@
 namespace ob {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace {
 
@@ -282,10 +283,8 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
 // out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]; fixed summation order.
 // A workgroup owns 32 columns; its 8 groups of 32 lanes each sum every 8th partial (four
 // independent chains per lane to keep loads in flight), then the 8 sums are combined in LDS.
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial,
-                                                              int n_part, int stride,
-                                                              __bf16 *__restrict__ out, int C,
-                                                              int accumulate) {
+__device__ __forceinline__ void reduce_columns(const float *__restrict__ partial, int n_part, int stride,
+                                               __bf16 *__restrict__ out, int C, int accumulate) {
     __shared__ float red[8][32];
     const int col = threadIdx.x & 31, pl = threadIdx.x >> 5;
     const int c = blockIdx.x * 32 + col;
@@ -311,19 +310,47 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     }
 }
 
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial,
+                                                              int n_part, int stride,
+                                                              __bf16 *__restrict__ out, int C,
+                                                              int accumulate) {
+    reduce_columns(partial, n_part, stride, out, C, accumulate);
+}
+
+// the reductions of one block's backward pass in one launch: blockIdx.y picks the job
+__global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch b, int accumulate) {
+    const ReduceJob j = b.job[blockIdx.y];
+    if ((int)blockIdx.x * 32 >= j.C) return;
+    reduce_columns(j.partial, j.n_part, j.stride, (__bf16 *)j.out, j.C, accumulate);
+}
+
 // partial[blockIdx.y][c] = sum over the rows blockIdx.y, +gridDim.y, ... of in[row][c]
 __global__ __launch_bounds__(256) void colsum_kernel(const __bf16 *__restrict__ in, int T, int C,
                                                      int ld, float *__restrict__ partial) {
     const int c8 = blockIdx.x * 256 + threadIdx.x;  // 8-column vector index
     if (c8 * 8 >= C) return;
     float s[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (int row = blockIdx.y; row < T; row += gridDim.y) {
-        const bf16x8 t = *(const bf16x8 *)(in + (size_t)row * ld + c8 * 8);
+    const __bf16 *src = in + c8 * 8;
+    const int g = gridDim.y;
+    int row = blockIdx.y;
+    // four rows' loads in flight; the rows are added in the order they are walked
+    for (; row + 3 * g < T; row += 4 * g) {
+        bf16x8 t[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t[u] = *(const bf16x8 *)(src + (size_t)(row + u * g) * ld);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] += (float)t[u][e];
+    }
+    for (; row < T; row += g) {
+        const bf16x8 t = *(const bf16x8 *)(src + (size_t)row * ld);
 #pragma unroll
         for (int e = 0; e < 8; ++e) s[e] += (float)t[e];
     }
-#pragma unroll
-    for (int e = 0; e < 8; ++e) partial[(size_t)blockIdx.y * C + c8 * 8 + e] = s[e];
+    float *dst = partial + (size_t)blockIdx.y * C + c8 * 8;
+    *(f32x4 *)dst = f32x4{s[0], s[1], s[2], s[3]};
+    *(f32x4 *)(dst + 4) = f32x4{s[4], s[5], s[6], s[7]};
 }
 
 // segment index of token t: the j with cu[j] <= t < cu[j+1]
@@ -542,6 +569,18 @@ void launch_reduce_partials(const float *partial, int n_part, int stride, void *
     ProfScope prof(K_REDUCE, s, 4.0 * n_part * C);
     hipLaunchKernelGGL(reduce_partials_kernel, dim3((C + 31) / 32), dim3(256), 0, s, partial, n_part,
                        stride, (__bf16 *)out, C, accumulate);
+}
+
+void launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s) {
+    if (b.n == 0) return;
+    double work = 0.0;
+    int max_c = 0;
+    for (int i = 0; i < b.n; ++i) {
+        work += 4.0 * b.job[i].n_part * b.job[i].C;
+        if (b.job[i].C > max_c) max_c = b.job[i].C;
+    }
+    ProfScope prof(K_REDUCE, s, work);
+    hipLaunchKernelGGL(reduce_batch_kernel, dim3((max_c + 31) / 32, b.n), dim3(256), 0, s, b, accumulate);
 }
 
 int colsum_partials(int T) { return T < 256 ? T : 256; }

@@ -50,6 +50,15 @@ void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats
 // out[c] (bf16) = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]
 void launch_reduce_partials(const float *partial, int n_part, int stride, void *out, int C,
                             int accumulate, hipStream_t s);
+// several such reductions in one launch (they are latency-bound: few columns, a few hundred partials)
+struct ReduceJob { const float *partial; int n_part, stride; void *out; int C; };
+struct ReduceBatch {
+    static constexpr int MAX = 8;
+    ReduceJob job[MAX];
+    int n = 0;
+    void add(const float *partial, int n_part, int stride, void *out, int C) { job[n++] = ReduceJob{partial, n_part, stride, out, C}; }
+};
+void launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s);
 int colsum_partials(int T);
 void launch_colsum(const void *in, int T, int C, int ld, float *partial, hipStream_t s);
 void launch_rotary(void *qkv, int ld, int T, int n_heads_rot, int d, const int32_t *cu_dev,
