@@ -99,6 +99,75 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_fwd_kernel(
     }
 }
 
+// The same forward for narrow rows (H <= 2048): a workgroup per row would leave most lanes idle and
+// pay two workgroup barriers per row, so a wavefront owns a row (NV vectors of 8 per lane, row sums
+// by wave reduction), walks rows slot, slot + n_slots, ... with the next row's loads in flight, and
+// keeps gamma and beta in registers.
+template <bool LAYERNORM, int NV>
+__global__ __launch_bounds__(256) void norm_fwd_wave_kernel(
+    const __bf16 *__restrict__ x, const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ beta,
+    __bf16 *__restrict__ h, float *__restrict__ stats, int T, int H, float eps) {
+    const int nvec = H / 8, lane = threadIdx.x & 63;
+    const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), n_slots = gridDim.x * 4;
+    bf16x8 g[NV], b[NV], nx[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + 64 * i;
+        g[i] = c < nvec ? *(const bf16x8 *)(gamma + c * 8) : bf16x8{};
+        b[i] = LAYERNORM && beta && c < nvec ? *(const bf16x8 *)(beta + c * 8) : bf16x8{};
+        nx[i] = bf16x8{};
+    }
+    auto fetch = [&](int row) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i)
+            if (lane + 64 * i < nvec) nx[i] = *(const bf16x8 *)(x + (size_t)row * H + (lane + 64 * i) * 8);
+    };
+    if (slot < T) fetch(slot);
+    for (int row = slot; row < T; row += n_slots) {
+        float v[NV][8];
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i)      // lanes past the end of the row hold zeros
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                v[i][e] = (float)nx[i][e];
+                sum += LAYERNORM ? v[i][e] : v[i][e] * v[i][e];
+            }
+        if (row + n_slots < T) fetch(row + n_slots);
+        sum = wave_sum(sum);
+        float mean = 0.f, rstd;
+        if (LAYERNORM) {
+            mean = sum / H;
+            float q = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i)
+                if (lane + 64 * i < nvec)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float dlt = v[i][e] - mean;
+                        q += dlt * dlt;
+                    }
+            rstd = rsqrtf(wave_sum(q) / H + eps);
+        } else {
+            rstd = rsqrtf(sum / H + eps);
+        }
+        if (lane == 0) {
+            stats[2 * (size_t)row] = mean;
+            stats[2 * (size_t)row + 1] = rstd;
+        }
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nvec) {
+                bf16x8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = (__bf16)((v[i][e] - mean) * rstd * (float)g[i][e] + (float)b[i][e]);
+                *(bf16x8 *)(h + (size_t)row * H + c * 8) = o;
+            }
+        }
+    }
+}
+
 // dx = dres + rstd * (dxhat - mean(dxhat) [LayerNorm only] - xhat * mean(dxhat * xhat)),
 // dxhat = dh * gamma.  Each workgroup walks rows blockIdx.x, +gridDim.x, ... and keeps its
 // column sums of dh * xhat (dgamma) and dh (dbeta) in registers; they are written once to
@@ -517,9 +586,27 @@ __global__ __launch_bounds__(256) void mask_kernel(const int32_t *__restrict__ c
 
 }  // namespace
 
+template <int NV>
+static void launch_norm_fwd_wave(int norm, const void *x, const void *gamma, const void *beta, void *h, float *stats,
+                                 int T, int H, float eps, int groups, hipStream_t s) {
+    if (norm == OB_LAYERNORM)
+        hipLaunchKernelGGL((norm_fwd_wave_kernel<true, NV>), dim3(groups), dim3(256), 0, s, (const __bf16 *)x,
+                           (const __bf16 *)gamma, (const __bf16 *)beta, (__bf16 *)h, stats, T, H, eps);
+    else
+        hipLaunchKernelGGL((norm_fwd_wave_kernel<false, NV>), dim3(groups), dim3(256), 0, s, (const __bf16 *)x,
+                           (const __bf16 *)gamma, (const __bf16 *)nullptr, (__bf16 *)h, stats, T, H, eps);
+}
+
 void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *beta, void *h,
                      float *stats, int T, int H, float eps, hipStream_t s) {
     ProfScope prof(K_NORM_FWD, s, 4.0 * T * H);
+    if (H <= 2048) {
+        const int groups = (T + 3) / 4 < 1024 ? (T + 3) / 4 : 1024;      // 4 rows at a time per workgroup
+        if (H <= 512) launch_norm_fwd_wave<1>(norm, x, gamma, beta, h, stats, T, H, eps, groups, s);
+        else if (H <= 1024) launch_norm_fwd_wave<2>(norm, x, gamma, beta, h, stats, T, H, eps, groups, s);
+        else launch_norm_fwd_wave<4>(norm, x, gamma, beta, h, stats, T, H, eps, groups, s);
+        return;
+    }
     if (norm == OB_LAYERNORM)
         hipLaunchKernelGGL(norm_fwd_kernel<true>, dim3(T), dim3(NORM_THREADS), 0, s, (const __bf16 *)x,
                            (const __bf16 *)gamma, (const __bf16 *)beta, (__bf16 *)h, stats, T, H, eps);
