@@ -42,11 +42,17 @@ constexpr int ROW_BYTES = BK * 2;
 
 // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous range of the `count`
 // work items that the workgroups [first, first + count) of a launch stand for (first % 8 == 0).
-__device__ __forceinline__ int xcd_chunk(int pid, int count) {
+__device__ __forceinline__ int xcd_chunk(int pid, int count, bool interleave) {
     const int per = count >> 3, rem = count & 7;
     const int xcd = pid & 7, loc = pid >> 3;
+    // interleave: blocks of 32 consecutive items (what one XCD holds at a time) are dealt round-robin
+    // to the XCDs instead, so that at any time the 8 XCDs work on neighbouring blocks
+    if (interleave && (count & 255) == 0) return (((loc >> 5) << 3) + xcd) * 32 + (loc & 31);
     return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
 }
+#ifndef INTERLEAVE_MIN_K
+#define INTERLEAVE_MIN_K 8192
+#endif
 // tile id -> (tile_m, tile_n): ids walk groups of GM tile-rows column by column, so the tiles
 // resident on one XCD at a time share A and B panels in that XCD's L2.
 __device__ __forceinline__ void tile_of_id(int tile, int tiles_m, int tiles_n, int &tm, int &tn) {
@@ -325,9 +331,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const int pid = blockIdx.x, n_whole = ts.part ? ts.n_full : (int)gridDim.x;
     const bool sliced = pid >= n_whole;
     const int kz = sliced ? (pid - n_whole) / ts.n_tail : 0;
-    const int tail_tile = sliced ? xcd_chunk((pid - n_whole) % ts.n_tail, ts.n_tail) : 0;
+    const bool interleave = K >= INTERLEAVE_MIN_K;
+    const int tail_tile = sliced ? xcd_chunk((pid - n_whole) % ts.n_tail, ts.n_tail, interleave) : 0;
     int tile_m, tile_n;
-    tile_of_id(sliced ? n_whole + tail_tile : xcd_chunk(pid, n_whole), tiles_m, tiles_n, tile_m, tile_n);
+    tile_of_id(sliced ? n_whole + tail_tile : xcd_chunk(pid, n_whole, interleave), tiles_m, tiles_n, tile_m, tile_n);
     const int m0 = __builtin_amdgcn_readfirstlane(tile_m) * BM;
     const int n0 = __builtin_amdgcn_readfirstlane(tile_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
