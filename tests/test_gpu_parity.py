@@ -30,7 +30,8 @@ def _say(msg):
 
 @pytest.mark.parametrize("layout", [0, 1, 2])
 @pytest.mark.parametrize("M,N,K", [(300, 192, 128), (1, 64, 64), (4100, 8192, 256),
-                                   (1025, 3200, 448), (257, 256, 64), (130, 320, 192), (513, 512, 320)])
+                                   (1025, 3200, 448), (257, 256, 64), (130, 320, 192), (513, 512, 320),
+                                   (4096, 8192, 8192)])      # 512 tiles over a long contraction: the round-robin patch order
 def test_gemm_against_fp64_matmul(layout, M, N, K):
     if layout == 2 and M % 64:
         M = (M + 63) // 64 * 64          # the output rows of a weight gradient are a feature dim
