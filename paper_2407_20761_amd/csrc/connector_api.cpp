@@ -17,7 +17,7 @@ struct Bump {
     size_t take(size_t bytes) { const size_t o = off; off += align_up(bytes, 256); return o; }
 };
 struct CSaved { size_t un, h, a, stats, total; };
-struct CWork { size_t z, da, dh, dun, partial, total; };
+struct CWork { size_t z, da, dh, dun, partial, gemm, gemm_bytes, total; };
 
 CSaved saved_layout(const CDims &m) {
     Bump L; CSaved s; const size_t n = m.n_tok;
@@ -32,6 +32,15 @@ CWork work_layout(const CDims &m) {
     const size_t p_norm = (size_t)subsample_wgrad_partials(m.n_tok) * 2 * m.W * 4;
     const size_t p_bias = (size_t)colsum_partials(m.n_tok) * m.Ht * 4;
     w.partial = L.take(p_norm > p_bias ? p_norm : p_bias);
+    // slice sums of the GEMMs whose last round of tiles is split along K
+    size_t g = 0;
+    const int shapes[6][4] = {{0, m.n_tok, m.Ht, m.W}, {0, m.n_tok, m.Ht, m.Ht}, {2, m.Ht, m.Ht, m.n_tok},
+                              {1, m.n_tok, m.Ht, m.Ht}, {2, m.Ht, m.W, m.n_tok}, {1, m.n_tok, m.W, m.Ht}};
+    for (const auto &q : shapes) {
+        const size_t b = gemm_workspace_bytes(q[0], q[1], q[2], q[3]);
+        if (b > g) g = b;
+    }
+    w.gemm_bytes = g; w.gemm = L.take(g);
     w.total = L.off;
     return w;
 }
@@ -110,9 +119,10 @@ extern "C" int ob_connector_fwd(const ob_connector_desc *desc, const ob_connecto
     hipStream_t s = (hipStream_t)hip_stream;
     unsigned char *un = at(saved, sv.un), *h = at(saved, sv.h), *a = at(saved, sv.a), *z = at(ws, wk.z);
     launch_subsample_norm_fwd(v, w->n_g, w->n_b, un, (float *)at(saved, sv.stats), m.n_tok, m.g, m.Hv, desc->norm_eps, s);
-    launch_gemm_nt(m.n_tok, m.Ht, m.W, un, m.W, w->w1, m.W, h, m.Ht, w->b1, nullptr, 0, s);
+    void *gws = wk.gemm_bytes ? at(ws, wk.gemm) : nullptr;
+    launch_gemm_nt(m.n_tok, m.Ht, m.W, un, m.W, w->w1, m.W, h, m.Ht, w->b1, nullptr, 0, s, 0, gws);
     launch_act_fwd(OB_GELU, h, a, m.n_tok, m.Ht, s);
-    launch_gemm_nt(m.n_tok, m.Ht, m.Ht, a, m.Ht, w->w2, m.Ht, z, m.Ht, w->b2, nullptr, 0, s);
+    launch_gemm_nt(m.n_tok, m.Ht, m.Ht, a, m.Ht, w->w2, m.Ht, z, m.Ht, w->b2, nullptr, 0, s, 0, gws);
     launch_rows_scatter(z, x_llm, dst_rows_dev, m.n_tok, m.Ht, s);
     return check_launch(who);
 }
@@ -149,20 +159,21 @@ extern "C" int ob_connector_bwd(const ob_connector_desc *desc, const ob_connecto
     const float *stats = (const float *)at(saved, sv.stats);
     unsigned char *dz = at(ws, wk.z), *da = at(ws, wk.da), *dh = at(ws, wk.dh), *dun = at(ws, wk.dun);
     float *partial = (float *)at(ws, wk.partial);
+    void *gws = at(ws, wk.gemm);
     const int ncs = colsum_partials(m.n_tok);
     int rc;
     launch_rows_gather(dz, dx_llm, dst_rows_dev, m.n_tok, m.Ht, s);
     // z = a W2^T + b2
-    if ((rc = gemm_any(2, m.Ht, m.Ht, m.n_tok, dz, a, g->w2, nullptr, acc ? g->w2 : nullptr, nullptr, 0, s))) return rc;
+    if ((rc = gemm_any(2, m.Ht, m.Ht, m.n_tok, dz, a, g->w2, nullptr, acc ? g->w2 : nullptr, gws, wk.gemm_bytes, s))) return rc;
     launch_colsum(dz, m.n_tok, m.Ht, m.Ht, partial, s);
     launch_reduce_partials(partial, ncs, m.Ht, g->b2, m.Ht, acc, s);
-    if ((rc = gemm_any(1, m.n_tok, m.Ht, m.Ht, dz, w->w2, da, nullptr, nullptr, nullptr, 0, s))) return rc;
+    if ((rc = gemm_any(1, m.n_tok, m.Ht, m.Ht, dz, w->w2, da, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // a = GELU(h), h = un W1^T + b1
     launch_act_bwd(OB_GELU, da, h, dh, m.n_tok, m.Ht, s);
-    if ((rc = gemm_any(2, m.Ht, m.W, m.n_tok, dh, un, g->w1, nullptr, acc ? g->w1 : nullptr, nullptr, 0, s))) return rc;
+    if ((rc = gemm_any(2, m.Ht, m.W, m.n_tok, dh, un, g->w1, nullptr, acc ? g->w1 : nullptr, gws, wk.gemm_bytes, s))) return rc;
     launch_colsum(dh, m.n_tok, m.Ht, m.Ht, partial, s);
     launch_reduce_partials(partial, ncs, m.Ht, g->b1, m.Ht, acc, s);
-    if ((rc = gemm_any(1, m.n_tok, m.W, m.Ht, dh, w->w1, dun, nullptr, nullptr, nullptr, 0, s))) return rc;
+    if ((rc = gemm_any(1, m.n_tok, m.W, m.Ht, dh, w->w1, dun, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // un = LayerNorm(gather(v))
     launch_subsample_norm_bwd(dun, v, stats, w->n_g, dv, m.n_tok, m.n_tiles, m.g, m.Hv, s);
     launch_subsample_norm_wgrad(dun, v, stats, partial, m.n_tok, m.g, m.Hv, s);
