@@ -358,9 +358,11 @@ def _subset_cu(cfg, max_tokens, seed=0):
     return cu[:n + 1].copy()
 
 
-@pytest.mark.parametrize("cfg,max_tokens", [(2, 2100), (3, 2048), (4, 2100), (5, 1600)])
+@pytest.mark.parametrize("cfg,max_tokens", [(2, 2100), (3, 2048), (4, 2100), (5, 1600), (2, 12300)])
 def test_block_full_hidden_sizes_on_a_segment_subset(cfg, max_tokens):
-    """Configs 2-5 at their full hidden sizes, one block, whole segments of a balanced batch."""
+    """Configs 2-5 at their full hidden sizes, one block, whole segments of a balanced batch; the last
+    case is config 2's whole batch of 12 tiles, the launch configuration the bench times (weight
+    gradients with split contractions, the column reductions of four biases and two norms)."""
     shape = si.CONFIGS[cfg]
     cu = _subset_cu(cfg, max_tokens)
     _say(f"block config {cfg} ({shape.name}): T={int(cu[-1])} n_seg={len(cu) - 1}")
@@ -389,19 +391,25 @@ def test_block_is_bitwise_reproducible_and_accumulates():
                            run.g[n].view(torch.int16)), n
 
 
-def test_config3_full_batch_one_segment_against_oracle():
-    """The launch configuration the bench times (config 3, one full balanced 16K-token batch):
-    the packed result restricted to one sample must equal the oracle run on that sample alone,
-    and with dy zero outside the sample the weight gradients must equal the sample's own."""
-    shape = si.CONFIGS[3]
-    tiles, tok = si.synthetic_dataset(20000, 0)
-    groups, _, _ = ob.ob_pack_isf(tiles, tok, 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128, 10, 0)
-    cu, mx = ob.ob_build_cu_seqlens_llm(groups[0], tok)
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_full_batch_one_segment_against_oracle(cfg):
+    """The launch configurations the bench times (config 3: one full balanced 16K-token batch;
+    config 4: 16 tiles; config 5: 32K tokens): the packed result restricted to one segment must equal
+    the oracle run on that segment alone, and with dy zero outside the segment the weight gradients
+    must equal the segment's own."""
+    shape = si.CONFIGS[cfg]
+    if shape.kind == "vit":
+        cu = ob.ob_build_cu_seqlens_vit(shape.budget, si.VIT_TILE_TOKENS)
+        j = shape.budget // 2 - 1
+    else:
+        tiles, tok = si.synthetic_dataset(20000, 0)
+        groups, _, _ = ob.ob_pack_isf(tiles, tok, 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128, 10, 0)
+        cu, mx = ob.ob_build_cu_seqlens_llm(groups[0], tok)
+        j = int(np.argmin(np.abs(np.diff(cu) - 700)))     # a mid-sized sample, not tile aligned
     T = int(cu[-1])
     lens = np.diff(cu)
-    j = int(np.argmin(np.abs(lens - 700)))            # a mid-sized sample, not tile aligned
     a, b = int(cu[j]), int(cu[j + 1])
-    _say(f"config 3 full batch: T={T} n_seg={len(lens)} checking segment {j} [{a},{b})")
+    _say(f"config {cfg} full batch: T={T} n_seg={len(lens)} checking segment {j} [{a},{b})")
     w = si.block_weights(shape, seed=3)
     x, dy = si.activations(T, shape.hidden, seed=3)
     dy_masked = np.zeros_like(dy)
