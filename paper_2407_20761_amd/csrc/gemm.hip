@@ -517,43 +517,43 @@ struct Plan {
     size_t part_bytes() const { return splits > 1 ? (size_t)splits * n_tail * (big ? 256 * 256 : 128 * 128) * 4 : 0; }
 };
 
-// 256x256 tiles run one workgroup per CU, 128x128 tiles two; unsplit, take the shape whose last
-// round of tiles leaves fewer CUs idle.  Two small workgroups on a CU deliver about 0.72 of a big
-// one's rate (twice the fragment reads per MFMA); measured: 1024 x 4096 over 16325 tokens (a
-// quarter round of big tiles) 236 against 114 us.
-//
-// Tiles come in rounds of one per CU (two for small tiles), and the tiles of an incomplete last
-// round take as long as a full one: measured over 16325 tokens, 4096 x 12288 (3 rounds) runs at
-// 1409 TFLOP/s, 4096 x 14336 (3.5 rounds) at 1178, 4096 x 5120 (1.25 rounds) at 1008.  When the
-// caller has room for fp32 sums (`can_split`), the contraction of those last tiles is cut into as
-// many slices as fill the round, each slice a workgroup with a shorter K loop; a second kernel adds
-// the slices.  A GEMM of less than one round (the hidden x hidden weight gradients of a narrow
-// model over all tokens of the batch) is all tail.  Writing and re-reading the sums is dear (8 bytes
-// per element and slice), so the estimate has to promise a gain.  It counts microseconds as measured
-// on a mostly idle chip: a K step of a big tile 1.3, of a small tile 0.47 with a CU to itself and
-// 0.9 when it shares one; 3 K steps' worth of prologue and epilogue; the sums move at 4 TB/s; 3 for
-// the second launch.
+// 256x256 tiles run one workgroup per CU, 128x128 tiles two.  Both the tile size and the split are
+// chosen by an estimate of the launch's duration in microseconds, fitted to launches measured on a
+// mostly idle chip:
+//  * big tiles come in rounds of one per CU, and the tiles of an incomplete last round take as long
+//    as a full one (over 16325 tokens: 4096 x 12288, 3 rounds, 1409 TFLOP/s; 4096 x 14336, 3.5
+//    rounds, 1178; 4096 x 5120, 1.25 rounds, 1008); a K step takes 1.3, prologue and epilogue as
+//    much as 5 more (nothing else runs on the CU meanwhile);
+//  * a small tile with a CU to itself takes 0.47 per K step (+3); two to a CU 0.9 each (about 0.72
+//    of a big tile's rate: twice the fragment reads per MFMA), but the one's epilogue hides behind the
+//    other's K loop (+1) and, out of step as they are, they fill the last round gradually (0.4 of a
+//    round on top of tiles / 512).  Measured: 12300 x 4096 x 1024 (3.06 rounds of big tiles) 109
+//    against 118; 12300 x 1024 x 4096 (0.77 rounds) 112 against 86; 6144 x 4096 x 16325 808 against 712;
+//  * when the caller has room for fp32 sums (`can_split`), the contraction of the tiles of the last
+//    round can be cut into as many slices as fill the round, each slice a workgroup with a shorter K
+//    loop; a second kernel adds the slices.  A GEMM of less than one round (the hidden x hidden
+//    weight gradients of a narrow model over all tokens of the batch) is all tail.  The sums cost 4
+//    bytes per element and slice at 4 TB/s (measured: 14 us for 64 MiB) and 3 for the second launch;
+//    a split has to promise 7 %.
 double estimate_us(bool big, int nk, double n_full, double n_tail, int splits, int k_chunk) {
-    const double slots = big ? 256.0 : 512.0;
     const double area = big ? 65536.0 : 16384.0;
-    const bool roomy = !big && n_full == 0 && n_tail * splits <= 256.0;
-    const double step = big ? 1.3 : (roomy ? 0.47 : 0.9);
-    double t = n_full / slots * (nk + 3) * step;
-    if (splits > 1) t += ceil(n_tail * splits / slots) * (k_chunk + 3) * step + splits * n_tail * area * 8.0 / 4e6 + 3.0;
-    else t += ceil(n_tail / slots) * (nk + 3) * step;
-    return t;
+    const double sums = splits > 1 ? splits * n_tail * area * 4.0 / 4e6 + 3.0 : 0.0;
+    const int k_tail = splits > 1 ? k_chunk : nk;
+    if (big) return n_full / 256.0 * (nk + 5) * 1.3 + ceil(n_tail * splits / 256.0) * (k_tail + 5) * 1.3 + sums;
+    if (n_full == 0 && n_tail * splits <= 256.0) return (k_tail + 3) * 0.47 + sums;
+    if (splits == 1) return ((n_full + n_tail) / 512.0 + 0.4) * (nk + 1) * 0.9;
+    return n_full / 512.0 * (nk + 1) * 0.9 + ceil(n_tail * splits / 512.0) * (k_tail + 1) * 0.9 + sums;
 }
 
 Plan make_plan(int M, int N, int K, bool can_split) {
     const int big = ((M + 255) / 256) * ((N + 255) / 256);
     const int small = ((M + 127) / 128) * ((N + 127) / 128);
-    const double eff_big = big / (ceil(big / 256.0) * 256.0);
-    const double eff_small = 0.72 * small / (ceil(small / 512.0) * 512.0);
-    const bool use_big = eff_big >= eff_small;
-    Plan p{use_big, use_big ? big : small, 0, 1, 0};
     const int nk = (K + BK - 1) / BK;
+    const double t_big = estimate_us(true, nk, 0, big, 1, 0), t_small = estimate_us(false, nk, 0, small, 1, 0);
+    const bool use_big = t_big <= t_small;
+    Plan p{use_big, use_big ? big : small, 0, 1, 0};
     if (can_split && nk >= 16) {
-        double best = 0.93 * estimate_us(p.big, nk, 0, p.n_full, 1, 0);
+        double best = 0.93 * (use_big ? t_big : t_small);
         for (int tile_big = 0; tile_big < 2; ++tile_big) {
             const int tiles = tile_big ? big : small, slots = tile_big ? 256 : 512;
             const int n_tail = tiles % slots, n_full = tiles - n_tail;

@@ -110,7 +110,7 @@ def test_gemm_k_major_operand_larger_than_4_gib(layout):
     """A k-major operand of more than 2^32 bytes: the 32-bit range of a buffer descriptor must not
     cut the contraction short (sampled outputs against fp32 products of the same device tensors)."""
     if layout == 2:
-        M, N, K = 32768, 64, 98304 + 37          # A [K, M]: 6.4 GB
+        M, N, K = 16384, 64, 262144 + 37         # A [K, M]: 8.6 GB, contraction in two slices, the second from 4.3 GB on
     else:
         M, N, K = 64, 196608 + 64, 16384         # B [K, N]: 6.4 GB
     _say(f"gemm >4 GiB operand layout={layout} M={M} N={N} K={K}")
@@ -118,7 +118,8 @@ def test_gemm_k_major_operand_larger_than_4_gib(layout):
     a = torch.randn((K, M) if layout == 2 else (M, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     b = torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
     c = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
-    ws = bytes_buf(ob.ob_gemm_workspace_bytes(layout, M, N, K))    # layout 2 splits: the second slice starts past 4 GiB
+    ws = bytes_buf(ob.ob_gemm_workspace_bytes(layout, M, N, K))
+    assert layout != 2 or ob.ob_gemm_workspace_bytes(layout, M, N, K) > 0
     ob.ob_gemm_bf16(layout, M, N, K, a, b, c, None, None, ws)
     rows = torch.tensor([0, 1, M // 2 + 3, M - 1], device="cuda")
     cols = torch.tensor([0, 5, N // 2 + 1, N - 64, N - 1], device="cuda")
