@@ -150,11 +150,11 @@ size_t ob_block_saved_offset(const ob_block_desc *desc, int total_tokens, const 
  *   layout 2 ("TN"): A [K,M], B [K,N]        -- wgrad    dW = dy^T a   (K = tokens)
  * `R` may equal `C` (in-place accumulate).  N and the feature side of K must be multiples of 64.
  * All three layouts run natively (a K-major operand is transposed by the LDS read).
- * An output with too few tiles for the chip over a long contraction (the weight gradients of a
- * narrow model) is split along K: the slices leave fp32 sums in `ws` (device memory,
- * ob_gemm_workspace_bytes() bytes, 0 for a GEMM that is not split) and a second kernel adds them,
- * bias and R in a fixed order.  ws == NULL: the GEMM runs unsplit, whatever its shape; a non-NULL
- * ws of fewer bytes than that is OB_EWORKSPACE. */
+ * The output tiles of an incomplete last round of the chip (all tiles, for the weight gradients of
+ * a narrow model) may have their contraction split along K: the slices leave fp32 sums in `ws`
+ * (device memory, ob_gemm_workspace_bytes() bytes: 0 for a GEMM that is not split, never more than
+ * 510 MiB) and a second kernel adds them, bias and R in a fixed order.  ws == NULL: the GEMM runs
+ * unsplit, whatever its shape; a non-NULL ws of fewer bytes than that is OB_EWORKSPACE. */
 size_t ob_gemm_workspace_bytes(int layout, int M, int N, int K);
 int ob_gemm_bf16(int layout, int M, int N, int K, const void *A, const void *B, void *C,
                  const void *bias, const void *R, void *ws, size_t ws_bytes, void *hip_stream);

@@ -175,6 +175,20 @@ def test_gemm_argument_validation():
     assert ob.lib.ob_debug_materialize_mask(C.byref(_seg([0, 4]).c), 1, None, None) == ob.OB_EINVAL
 
 
+def test_gemm_workspace_is_bounded_and_tile_granular():
+    """The split planner on arbitrary shapes: scratch is a whole number of 128 x 128 fp32 tile sums,
+    never more than 8 slices of less than a round of 256 x 256 tiles, and a function of the shape only."""
+    rng = np.random.default_rng(5)
+    for _ in range(3000):
+        M = int(rng.choice([1, 64, 255, 256, 257, 4096, 12300, 16384, 1 << 20, int(rng.integers(1, 1 << 21))]))
+        N = 64 * int(rng.choice([1, 2, 16, 50, 64, 224, 448, int(rng.integers(1, 4096))]))
+        K = int(rng.choice([64, 1000, 1024, 4096, 8192, 12300, 16325, 1 << 20, int(rng.integers(1, 1 << 21))]))
+        layout = int(rng.integers(0, 3))
+        b = ob.ob_gemm_workspace_bytes(layout, M, N, K)
+        assert b % (128 * 128 * 4) == 0 and b <= 8 * 255 * 256 * 256 * 4, (layout, M, N, K, b)
+        assert b == ob.ob_gemm_workspace_bytes(layout, M, N, K)
+
+
 # ---- grouping arms, partition search and re-computation plan: library == oracle ----------------
 
 @pytest.mark.parametrize("seed", [0, 4])
