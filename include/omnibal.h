@@ -127,7 +127,9 @@ int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k, const void
  *                      (one buffer may serve every block); the forward is replayed from x into it
  *                      first (every step but the last GEMM), then the backward runs as usual, so
  *                      the results are bit-identical to the non-recomputed ones.
- * x/y and dy/dx may not alias each other or `saved`/`ws`. */
+ * x/y and dy/dx may not alias each other or `saved`/`ws`.  Besides the activations, `saved` holds
+ * the scratch of the forward GEMMs (the slice sums of split contractions, see ob_gemm_bf16), `ws`
+ * that of the backward GEMMs: both are counted in the two size functions. */
 enum { OB_BWD_ACCUMULATE = 1, OB_BWD_RECOMPUTE = 2 };
 size_t ob_block_saved_bytes(const ob_block_desc *desc, int total_tokens);
 size_t ob_block_workspace_bytes(const ob_block_desc *desc, int total_tokens);
