@@ -86,6 +86,44 @@ def test_gemm_split_contraction(layout, M, N, K):
     assert rel_err(to_np(c3), ref) < 5e-3
 
 
+def test_gemm_random_shapes():
+    """Forty seeded shapes across the planner's cases (tile size, whole and split tiles, patch order,
+    ragged edges), each with scratch (bias and in-place residual) and without (plain, unsplit)."""
+    rng = np.random.default_rng(2024)
+    done = split = 0
+    while done < 40:
+        layout = int(rng.integers(0, 3))
+        M = int(rng.choice([64, 128, 192, 256, 320, 1024, 2048, 3200, 4096, int(rng.integers(1, 5000))]))
+        N = 64 * int(rng.choice([1, 2, 3, 4, 8, 16, 20, 24, 32, 50, int(rng.integers(1, 64))]))
+        K = int(rng.choice([64, 128, 1024, 2048, 4096, 8192, 8256, 12300, int(rng.integers(1, 20000))]))
+        if layout == 2:
+            M = (M + 63) // 64 * 64
+        else:
+            K = (K + 63) // 64 * 64
+        if M * N * K > 3e10:
+            continue
+        A = si.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
+        B = si.round_to_bf16(rng.standard_normal((N, K), dtype=np.float32))
+        bias = si.round_to_bf16(rng.standard_normal((N,), dtype=np.float32))
+        R = si.round_to_bf16(rng.standard_normal((M, N), dtype=np.float32) * 4)
+        ref = A.astype(np.float64) @ B.astype(np.float64).T
+        a_dev = to_dev(A if layout != 2 else A.T.copy())
+        b_dev = to_dev(B if layout == 0 else B.T.copy())
+        need = ob.ob_gemm_workspace_bytes(layout, M, N, K)
+        _say(f"gemm random layout={layout} M={M} N={N} K={K} scratch={need}")
+        ws = bytes_buf(need)
+        ws.fill_(0x7F)
+        c = to_dev(R)
+        ob.ob_gemm_bf16(layout, M, N, K, a_dev, b_dev, c, to_dev(bias), c, ws)
+        assert rel_err(to_np(c), ref + bias + R) < 5e-3
+        c2 = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        ob.ob_gemm_bf16(layout, M, N, K, a_dev, b_dev, c2, None, None, None)
+        assert rel_err(to_np(c2), ref) < 5e-3
+        done += 1
+        split += need > 0
+    assert split >= 10          # the sweep does reach the split path
+
+
 @pytest.mark.parametrize("layout,M,N,K", [(0, 16384, 28672, 4096), (1, 16384, 4096, 14336), (2, 4096, 14336, 16325)])
 def test_gemm_full_size_sampled_outputs(layout, M, N, K):
     """Config 3's largest GEMMs in the launch shape the benchmark times (256x256 tiles, one per CU);
