@@ -181,10 +181,28 @@ ATTN_CASES = [
 
 @pytest.mark.parametrize("lens,nq,nkv,d,mask", ATTN_CASES)
 def test_varlen_attention_fwd_bwd(lens, nq, nkv, d, mask):
+    _check_attention(lens, nq, nkv, d, mask, seed=len(lens) + d)
+
+
+def test_varlen_attention_random_cases():
+    """Sixteen seeded cases: 1-8 segments of 1-900 tokens (half of them forced onto tile borders and
+    their neighbours), GQA groups 1, 2, 4, 6, both head sizes, both masks."""
+    rng = np.random.default_rng(77)
+    for case in range(16):
+        n = int(rng.integers(1, 9))
+        lens = [int(rng.choice([63, 64, 65, 127, 128, 129, 191, 192, 193, 256, 257, 512, 513]))
+                if rng.random() < 0.5 else int(rng.integers(1, 901)) for _ in range(n)]
+        group = int(rng.choice([1, 2, 4, 6]))
+        nkv = int(rng.integers(1, 3))
+        _check_attention(lens, nkv * group, nkv, int(rng.choice([64, 128])),
+                         orc.MASK_CAUSAL if case % 2 else orc.MASK_BIDIR, seed=100 + case)
+
+
+def _check_attention(lens, nq, nkv, d, mask, seed):
     _say(f"attention lens={lens} nq={nq} nkv={nkv} d={d} mask={mask}")
     cu = si.lengths_to_cu(lens)
     T = int(cu[-1])
-    q, k, v, d_o = si.qkv_tensors(T, nq, nkv, d, seed=len(lens) + d)
+    q, k, v, d_o = si.qkv_tensors(T, nq, nkv, d, seed=seed)
     scale = 1.0 / np.sqrt(d)
     o_ref, lse_ref = orc.attention_fwd(*(a.astype(np.float64) for a in (q, k, v)), cu, mask, scale)
     dq_ref, dk_ref, dv_ref = orc.attention_bwd(*(a.astype(np.float64) for a in (d_o, q, k, v)),
