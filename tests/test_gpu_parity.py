@@ -316,6 +316,27 @@ def test_block_small_variants(variant):
     _check_block(shape, si.lengths_to_cu(lens), seed=3)
 
 
+def test_block_random_compositions():
+    """Ten seeded blocks: every combination the descriptor allows is drawn from (norm, MLP, mask,
+    rotary, biases, GQA group, head size, hidden sizes that are and are not multiples of 256)."""
+    rng = np.random.default_rng(31)
+    for case in range(10):
+        d = int(rng.choice([64, 128]))
+        nkv = int(rng.integers(1, 3))
+        nq = nkv * int(rng.choice([1, 2, 4]))
+        norm = si.NORM_LAYERNORM if rng.random() < 0.5 else si.NORM_RMSNORM
+        shape = si.small_shape(hidden=64 * int(rng.integers(1, 13)), n_q_heads=nq, n_kv_heads=nkv, head_dim=d,
+                               mlp_dim=64 * int(rng.integers(1, 17)), norm=norm,
+                               mlp=si.MLP_GELU if rng.random() < 0.5 else si.MLP_SWIGLU,
+                               mask=si.MASK_CAUSAL if rng.random() < 0.5 else si.MASK_BIDIR,
+                               use_rotary=bool(rng.random() < 0.5), has_bias=bool(rng.random() < 0.5),
+                               norm_eps=1e-5 if norm == si.NORM_LAYERNORM else 1e-6)
+        lens = [int(rng.integers(1, 400)) for _ in range(int(rng.integers(1, 7)))]
+        _say(f"block random {case}: hidden={shape.hidden} nq={nq} nkv={nkv} d={d} mlp={shape.mlp_dim} "
+             f"norm={shape.norm} act={shape.mlp} mask={shape.mask} rotary={shape.use_rotary} bias={shape.has_bias} lens={lens}")
+        _check_block(shape, si.lengths_to_cu(lens), seed=40 + case)
+
+
 # ---- re-computation (Sec. 4.3): backward replays the forward into a scratch `saved` -----------
 
 @pytest.mark.parametrize("variant", ["config1", "llm-like"])
