@@ -316,10 +316,13 @@ def test_block_small_variants(variant):
     _check_block(shape, si.lengths_to_cu(lens), seed=3)
 
 
-def test_block_random_compositions():
+@pytest.mark.parametrize("dtype_name", ["bf16", "fp32"])
+def test_block_random_compositions(dtype_name):
     """Ten seeded blocks: every combination the descriptor allows is drawn from (norm, MLP, mask,
-    rotary, biases, GQA group, head size, hidden sizes that are and are not multiples of 256)."""
+    rotary, biases, GQA group, head size, hidden sizes that are and are not multiples of 256); once on
+    the bf16 path and once on the fp32 debug path at its own bar."""
     rng = np.random.default_rng(31)
+    fp32 = dtype_name == "fp32"
     for case in range(10):
         d = int(rng.choice([64, 128]))
         nkv = int(rng.integers(1, 3))
@@ -334,7 +337,8 @@ def test_block_random_compositions():
         lens = [int(rng.integers(1, 400)) for _ in range(int(rng.integers(1, 7)))]
         _say(f"block random {case}: hidden={shape.hidden} nq={nq} nkv={nkv} d={d} mlp={shape.mlp_dim} "
              f"norm={shape.norm} act={shape.mlp} mask={shape.mask} rotary={shape.use_rotary} bias={shape.has_bias} lens={lens}")
-        _check_block(shape, si.lengths_to_cu(lens), seed=40 + case)
+        _check_block(shape, si.lengths_to_cu(lens), seed=40 + case, dtype=torch.float32 if fp32 else None,
+                     tol=TOL_FP32 if fp32 else TOL)
 
 
 # ---- re-computation (Sec. 4.3): backward replays the forward into a scratch `saved` -----------
