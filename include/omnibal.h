@@ -197,8 +197,10 @@ int ob_connector_bwd(const ob_connector_desc *desc, const ob_connector_weights *
                      const int32_t *dst_rows_dev, int llm_tokens, const void *saved,
                      size_t saved_bytes, void *ws, size_t ws_bytes, void *hip_stream);
 
-/* T x T byte mask (1 = allowed) written by the same segment/causal predicate the attention
- * kernels use; for bit-exact mask tests, T <= 4096. */
+/* T x T byte mask (1 = allowed): allowed(i, j) <=> i and j lie in the same segment (and j <= i when
+ * causal), evaluated per entry from cu_seqlens by a small kernel of its own (the attention kernels
+ * never form the mask: they tile each segment separately and compare row indices inside the
+ * diagonal and ragged tiles).  For bit-exact tests of the segment layout, T <= 4096. */
 int ob_debug_materialize_mask(const ob_segments *seg, int mask, uint8_t *mask_dev, void *hip_stream);
 
 /* ---- host side: balanced dynamic mini-batches (Alg. 1, ISF) -----------------------------------

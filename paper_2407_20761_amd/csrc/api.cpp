@@ -425,7 +425,7 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
     // dx = dx1 + norm1_bwd(dh1)
     launch_norm_bwd(desc->norm, dh, x, (const float *)at(saved, sv.stat1), w->n1_g, dx1, dx, (float *)at(ws, wk.p_n1), m.T, m.H, s);
     norm_grads(wk.p_n1, g->n1_g, g->n1_b);
-    launch_reduce_batch(sums, acc, s);
+    if ((rc = launch_reduce_batch(sums, acc, s))) return rc;
     return check_launch("ob_block_bwd");
 }
 

@@ -658,8 +658,9 @@ void launch_reduce_partials(const float *partial, int n_part, int stride, void *
                        stride, (__bf16 *)out, C, accumulate);
 }
 
-void launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s) {
-    if (b.n == 0) return;
+int launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s) {
+    if (b.overflow) return fail(OB_EINVAL, "reduce batch: more than %d column reductions in one launch", ReduceBatch::MAX);
+    if (b.n == 0) return OB_OK;
     double work = 0.0;
     int max_c = 0;
     for (int i = 0; i < b.n; ++i) {
@@ -668,6 +669,7 @@ void launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s) {
     }
     ProfScope prof(K_REDUCE, s, work);
     hipLaunchKernelGGL(reduce_batch_kernel, dim3((max_c + 31) / 32, b.n), dim3(256), 0, s, b, accumulate);
+    return OB_OK;
 }
 
 int colsum_partials(int T) { return T < 256 ? T : 256; }

@@ -14,7 +14,9 @@
 // so the memory pipeline sees a steady stream (a burst of a K step's loads blocks the wave's
 // instruction issue, MFMAs included, until the cache has taken them) and no wait ever meets a
 // load in flight.  The hardware range check of the buffer descriptor turns every access past the end
-// of an operand (row tails of M / N, the ragged token tail of K) into zeros.  A K-contiguous operand
+// of an operand into zeros: whole rows beyond M / N of a K-contiguous operand, the ragged token tail
+// of K and K steps past the last.  (Columns beyond M / N of a K-major operand wrap into its next row
+// instead; they only feed outputs beyond M / N, which are never stored.)  A K-contiguous operand
 // is staged as [row][64 k] and a fragment is one 16-byte LDS read; a K-major operand is staged as
 // it lies in memory, [k][rows], and the fragment comes out of two transposing LDS reads, so dgrad
 // and wgrad need no re-layout pass.  16-byte chunks are XOR-swizzled on the way in (the global
@@ -23,7 +25,6 @@
 // consecutive output columns; the epilogue transposes them through LDS into full-row stores.
 #include <algorithm>
 #include <cmath>
-#include <cstdlib>
 
 #include "ob_internal.h"
 
@@ -50,9 +51,9 @@ __device__ __forceinline__ int xcd_chunk(int pid, int count, bool interleave) {
     if (interleave && (count & 255) == 0) return (((loc >> 5) << 3) + xcd) * 32 + (loc & 31);
     return (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
 }
-#ifndef INTERLEAVE_MIN_K
-#define INTERLEAVE_MIN_K 8192
-#endif
+// contractions at least this long deal their patches round-robin to the XCDs (measured: shorter ones
+// lose up to 1.8 %, longer ones gain 2.4 - 3.5 %)
+constexpr int INTERLEAVE_MIN_K = 8192;
 // tile id -> (tile_m, tile_n): ids walk groups of GM tile-rows column by column, so the tiles
 // resident on one XCD at a time share A and B panels in that XCD's L2.
 __device__ __forceinline__ void tile_of_id(int tile, int tiles_m, int tiles_n, int &tm, int &tn) {
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             const f32x4 lo = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32);
             const f32x4 hi = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32 + 16);
             const int m = m0 + wm * (BM / WM) + ii * 32 + row;
-            if (sliced) {   // the whole tile, also its rows and columns beyond M and N (zeros)
+            if (sliced) {   // the whole tile; sums beyond M and N are never read by tail_sum_kernel
                 float *dst = ts.part + ((size_t)(kz * ts.n_tail + tail_tile) * BM + (m - m0)) * BN + (n_out - n0);
                 *(f32x4 *)dst = lo;
                 *(f32x4 *)(dst + 4) = hi;
@@ -535,14 +536,29 @@ struct Plan {
 //    weight gradients of a narrow model over all tokens of the batch) is all tail.  The sums cost 4
 //    bytes per element and slice at 4 TB/s (measured: 14 us for 64 MiB) and 3 for the second launch;
 //    a split has to promise 7 %.
+// compute units of the current device, asked once (256 on MI355X, also when no device answers: the
+// size queries must work on a host without a GPU)
+int compute_units() {
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        (void)hipGetLastError();
+        return n;
+    }();
+    return cus;
+}
+
 double estimate_us(bool big, int nk, double n_full, double n_tail, int splits, int k_chunk) {
     const double area = big ? 65536.0 : 16384.0;
     const double sums = splits > 1 ? splits * n_tail * area * 4.0 / 4e6 + 3.0 : 0.0;
     const int k_tail = splits > 1 ? k_chunk : nk;
-    if (big) return n_full / 256.0 * (nk + 5) * 1.3 + ceil(n_tail * splits / 256.0) * (k_tail + 5) * 1.3 + sums;
-    if (n_full == 0 && n_tail * splits <= 256.0) return (k_tail + 3) * 0.47 + sums;
-    if (splits == 1) return ((n_full + n_tail) / 512.0 + 0.4) * (nk + 1) * 0.9;
-    return n_full / 512.0 * (nk + 1) * 0.9 + ceil(n_tail * splits / 512.0) * (k_tail + 1) * 0.9 + sums;
+    const double cus = compute_units(), slots2 = 2.0 * cus;
+    if (big) return n_full / cus * (nk + 5) * 1.3 + ceil(n_tail * splits / cus) * (k_tail + 5) * 1.3 + sums;
+    if (n_full == 0 && n_tail * splits <= cus) return (k_tail + 3) * 0.47 + sums;
+    if (splits == 1) return ((n_full + n_tail) / slots2 + 0.4) * (nk + 1) * 0.9;
+    return n_full / slots2 * (nk + 1) * 0.9 + ceil(n_tail * splits / slots2) * (k_tail + 1) * 0.9 + sums;
 }
 
 Plan make_plan(int M, int N, int K, bool can_split) {
@@ -555,7 +571,7 @@ Plan make_plan(int M, int N, int K, bool can_split) {
     if (can_split && nk >= 16) {
         double best = 0.93 * (use_big ? t_big : t_small);
         for (int tile_big = 0; tile_big < 2; ++tile_big) {
-            const int tiles = tile_big ? big : small, slots = tile_big ? 256 : 512;
+            const int tiles = tile_big ? big : small, slots = (tile_big ? 1 : 2) * compute_units();
             const int n_tail = tiles % slots, n_full = tiles - n_tail;
             if (n_tail == 0) continue;
             for (int z = 2; z <= 8 && nk / z >= 8; ++z) {
@@ -567,21 +583,6 @@ Plan make_plan(int M, int N, int K, bool can_split) {
             }
         }
     }
-#ifdef OB_GEMM_TUNE   // build-time hook of the tile / split sweeps: OB_TILE=big|small, OB_SPLIT=n
-    if (getenv("OB_TILE") || getenv("OB_SPLIT")) {
-        if (const char *e = getenv("OB_TILE")) p.big = e[0] == 'b';
-        const int tiles = p.big ? big : small, slots = p.big ? 256 : 512;
-        const int z = getenv("OB_SPLIT") ? std::min(atoi(getenv("OB_SPLIT")), nk / 2) : 1;
-        p = Plan{p.big, tiles, 0, 1, 0};
-        if (z > 1 && can_split && tiles % slots) {
-            p.n_tail = tiles % slots;
-            p.n_full = tiles - p.n_tail;
-            p.k_chunk = ((nk + z - 1) / z + 1) & ~1;
-            p.splits = (nk + p.k_chunk - 1) / p.k_chunk;
-            if (p.splits < 2) p = Plan{p.big, tiles, 0, 1, 0};
-        }
-    }
-#endif
     return p;
 }
 

@@ -56,9 +56,14 @@ struct ReduceBatch {
     static constexpr int MAX = 8;
     ReduceJob job[MAX];
     int n = 0;
-    void add(const float *partial, int n_part, int stride, void *out, int C) { job[n++] = ReduceJob{partial, n_part, stride, out, C}; }
+    bool overflow = false;   // a job did not fit: launch_reduce_batch refuses the whole batch
+    void add(const float *partial, int n_part, int stride, void *out, int C) {
+        if (n >= MAX) { overflow = true; return; }
+        job[n++] = ReduceJob{partial, n_part, stride, out, C};
+    }
 };
-void launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s);
+// OB_EINVAL (nothing launched) when a job was dropped by add()
+int launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s);
 int colsum_partials(int T);
 void launch_colsum(const void *in, int T, int C, int ld, float *partial, hipStream_t s);
 void launch_rotary(void *qkv, int ld, int T, int n_heads_rot, int d, const int32_t *cu_dev,

@@ -249,6 +249,59 @@ def test_block_backward_matches_central_differences(shape):
     assert worst < 1e-6
 
 
+@pytest.mark.parametrize("shape", _fd_shapes(), ids=["vit-like", "llm-like"])
+def test_stack_backward_matches_central_differences(shape):
+    """Three chained blocks (the block stack the benchmark metric is quoted on): the input gradient and
+    the gradients of each block's weights against central differences of <y, dy> through the whole
+    stack; a backward that walked the blocks in the wrong order, or paired a block with another
+    block's cache or weights, fails here."""
+    cu = si.lengths_to_cu([4, 2, 3])
+    T = int(cu[-1])
+    rng = np.random.default_rng(41)
+    ws = [{n: rng.standard_normal(sh) * 0.4 + (1.0 if n.endswith("_g") else 0.0)
+           for n, sh in si.weight_shapes(shape).items()} for _ in range(3)]
+    x = rng.standard_normal((T, shape.hidden))
+    dy = rng.standard_normal((T, shape.hidden))
+    y, dx, grads = ob.stack_fwd_bwd(shape, ws, x, dy, cu)
+    assert len(grads) == 3 and all(set(g) == set(ws[0]) for g in grads)
+
+    def loss(ws_, x_):
+        a = x_
+        for w_ in ws_:                       # the definition of a stack: block after block
+            a = ob.block_fwd(shape, w_, a, cu)[0]
+        return float((a * dy).sum())
+
+    np.testing.assert_array_equal(y, _chain(shape, ws, x, cu))
+    h, worst = 1e-5, 0.0
+    for idx in [(0, 0), (T - 1, shape.hidden - 1), (3, 2), (5, 1)]:
+        xp, xm = x.copy(), x.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        fd = (loss(ws, xp) - loss(ws, xm)) / (2 * h)
+        worst = max(worst, abs(fd - dx[idx]) / max(abs(fd), 1e-3))
+    for b in range(3):
+        for name in ws[b]:
+            flat = ws[b][name].reshape(-1)
+            for e in sorted(set([0, flat.size // 2, flat.size - 1])):
+                keep = flat[e]
+                flat[e] = keep + h
+                lp = loss(ws, x)
+                flat[e] = keep - h
+                lm = loss(ws, x)
+                flat[e] = keep
+                fd = (lp - lm) / (2 * h)
+                got = grads[b][name].reshape(-1)[e]
+                worst = max(worst, abs(fd - got) / max(abs(fd), 1e-3))
+    assert worst < 1e-6, worst
+
+
+def _chain(shape, ws, x, cu):
+    a = x
+    for w in ws:
+        a = ob.block_fwd(shape, w, a, cu)[0]
+    return a
+
+
 def test_attention_backward_matches_central_differences():
     cu = si.lengths_to_cu([4, 6])
     T, nq, nkv, d = 10, 4, 2, 4

@@ -130,7 +130,27 @@ def test_isf_on_the_synthetic_dataset_matches_the_papers_qualitative_claims():
     R, _ = op.random_groups(len(tiles), B, 0)
     r_totals = [sum(int(tokens[i]) for i in G) for G in R]
     assert op.dist_ratio(r_totals) > 10 * op.dist_ratio(totals)
-    assert Qv == round(Qt * tiles.sum() / tokens.sum())
+
+
+def test_budget_rule_hand_worked_and_the_papers_own_pair():
+    """Sec. 5.2: the image budget follows from the token budget through the dataset's tokens per image
+    (and the other way round).  Hand-worked: 6 images over 600 tokens is 100 tokens per image."""
+    img, tok = [1, 2, 3], [100, 200, 300]
+    assert op.choose_qv(img, tok, 1000) == 10                 # 1000 / 100
+    assert op.choose_qv(img, tok, 1050) == 11                 # 10.5 rounds half up
+    assert op.choose_qv(img, tok, 1049) == 10                 # 10.49 rounds down
+    assert op.choose_qv(img, tok, 10) == 1                    # 0.1 images: never below one
+    assert op.choose_qt(img, tok, 10) == 1000                 # 10 images x 100 tokens
+    assert op.choose_qt(img, tok, 1) == 100
+    assert op.choose_qt([3], [10], 1) == 3                    # 3.33 rounds down
+    assert op.choose_qt([2], [5], 1) == 3                     # 2.5 rounds half up
+    # a transposed ratio (tokens over images where images over tokens belongs) would give 100000 here
+    assert op.choose_qv(img, tok, 1000) != 100000
+    # the pair the paper prints for its own data (Sec. 5.2: Q_t = 4K, Q_v = 9): a dataset with 455 tokens
+    # per image maps one onto the other, both ways
+    img, tok = [1, 1, 2], [455, 455, 910]
+    assert op.choose_qv(img, tok, 4096) == 9
+    assert abs(op.choose_qt(img, tok, 9) - 4096) <= 1
 
 
 def test_cu_seqlens_builders():

@@ -2,6 +2,7 @@
 P = (5, 10, 15); 3^3 = 27 candidates for r = 1, N = 4), hand-worked Eq. 4 / Eq. 5 values, the
 exhaustive optimum on small cases, and closed forms of the Step-4 arithmetic (Sec. 4.3)."""
 import itertools
+import os
 import random
 
 import pytest
@@ -9,21 +10,38 @@ import pytest
 from oracle import planner as pl
 
 
+def _paper_example():
+    """The values the paper prints for its worked partition example (tests/golden/paper_bmp_example.txt)."""
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "paper_bmp_example.txt")) as f:
+        for ln in f:
+            if ln.strip() and not ln.startswith("#"):
+                key, val = [c.strip() for c in ln.split(";")]
+                rows[key] = [int(v) for v in val.split()]
+    return rows
+
+
 def test_paper_partition_example():
     # "The first partition consists of layers l1 .. l4 since P0 = 1, P1 = 5"
-    st = pl.stages((5, 10, 15), 20)
-    assert st[0] == [1, 2, 3, 4]
+    ex = _paper_example()
+    L, N, P = ex["L"][0], ex["N"][0], tuple(ex["P"])
+    assert (L, N, P) == (20, 4, (5, 10, 15))
+    st = pl.stages(P, L)
+    assert len(st) == N and st[0] == ex["first_stage_layers"]
     assert [len(s) for s in st] == [4, 5, 5, 6]
-    assert sorted(sum(st, [])) == list(range(1, 21))
-    assert pl.is_valid((5, 10, 15), 20) and not pl.is_valid((5, 5, 15), 20)
-    assert not pl.is_valid((1, 10, 15), 20) and not pl.is_valid((5, 10, 21), 20)
+    assert sorted(sum(st, [])) == list(range(1, L + 1))
+    assert pl.is_valid(P, L) and not pl.is_valid((5, 5, 15), L)
+    assert not pl.is_valid((1, 10, 15), L) and not pl.is_valid((5, 10, 21), L)
 
 
 def test_candidate_count_r1_n4_is_27():
-    a = pl.anchor([1.0] * 20, 4)
+    ex = _paper_example()
+    L, N, r, n_cand = ex["L"][0], ex["N"][0], ex["r"][0], ex["n_candidates"][0]
+    a = pl.anchor([1.0] * L, N)
     assert a == (6, 11, 16)                       # uniform layers: the equal split
-    cands = pl.candidates(a, 20, 1)
-    assert len(cands) == 27 and len(set(cands)) == 27
+    cands = pl.candidates(a, L, r)
+    assert n_cand == 27 and len(cands) == n_cand and len(set(cands)) == n_cand
+    assert len(pl.candidates(tuple(ex["P"]), L, r)) == n_cand      # around the printed partition too
     assert all(max(abs(p - q) for p, q in zip(P, a)) <= 1 for P in cands)
     # candidates that fall off an end or collide are dropped
     assert len(pl.candidates((2, 3, 4), 20, 1)) < 27
