@@ -146,7 +146,8 @@ def test_gemm_full_size_sampled_outputs(layout, M, N, K):
 @pytest.mark.parametrize("layout", [1, 2])
 def test_gemm_k_major_operand_larger_than_4_gib(layout):
     """A k-major operand of more than 2^32 bytes: the 32-bit range of a buffer descriptor must not
-    cut the contraction short (sampled outputs against fp32 products of the same device tensors)."""
+    cut the contraction short (sampled outputs against fp64 numpy products of the same operand values,
+    brought back to the host row by row)."""
     if layout == 2:
         M, N, K = 16384, 64, 262144 + 37         # A [K, M]: 8.6 GB, contraction in two slices, the second from 4.3 GB on
     else:
@@ -161,8 +162,9 @@ def test_gemm_k_major_operand_larger_than_4_gib(layout):
     ob.ob_gemm_bf16(layout, M, N, K, a, b, c, None, None, ws)
     rows = torch.tensor([0, 1, M // 2 + 3, M - 1], device="cuda")
     cols = torch.tensor([0, 5, N // 2 + 1, N - 64, N - 1], device="cuda")
-    a_rows = (a[:, rows].T if layout == 2 else a[rows]).float()              # [4, K]
-    ref = (a_rows.double() @ b[:, cols].double()).cpu().numpy()
+    a_rows = to_np(a[:, rows].T if layout == 2 else a[rows])                 # [4, K] on the host, float64
+    b_cols = to_np(b[:, cols])                                               # [K, 5]
+    ref = a_rows @ b_cols
     got = to_np(c[rows][:, cols])
     assert rel_err(got, ref) < 5e-3
 
@@ -198,15 +200,26 @@ def test_varlen_attention_random_cases():
                          orc.MASK_CAUSAL if case % 2 else orc.MASK_BIDIR, seed=100 + case)
 
 
-def _check_attention(lens, nq, nkv, d, mask, seed):
-    _say(f"attention lens={lens} nq={nq} nkv={nkv} d={d} mask={mask}")
+def _check_attention(lens, nq, nkv, d, mask, seed, per_segment=False):
+    _say(f"attention n_seg={len(lens)} lens={lens if len(lens) <= 40 else str(lens[:40]) + ' ...'} nq={nq} nkv={nkv} d={d} mask={mask}")
     cu = si.lengths_to_cu(lens)
     T = int(cu[-1])
     q, k, v, d_o = si.qkv_tensors(T, nq, nkv, d, seed=seed)
     scale = 1.0 / np.sqrt(d)
-    o_ref, lse_ref = orc.attention_fwd(*(a.astype(np.float64) for a in (q, k, v)), cu, mask, scale)
-    dq_ref, dk_ref, dv_ref = orc.attention_bwd(*(a.astype(np.float64) for a in (d_o, q, k, v)),
-                                               cu, mask, scale)
+    if per_segment:
+        # large batches: the oracle's per-segment form (pinned equal to the masked form), printing as it goes
+        o_ref, lse_ref = np.empty((T, nq, d)), np.empty((nq, T))
+        dq_ref, dk_ref, dv_ref = np.empty((T, nq, d)), np.empty((T, nkv, d)), np.empty((T, nkv, d))
+        for j in range(len(lens)):
+            a, b = int(cu[j]), int(cu[j + 1])
+            sub = [t[a:b].astype(np.float64) for t in (d_o, q, k, v)]
+            o_ref[a:b], lse_ref[:, a:b] = orc.attention_fwd_masked(sub[1], sub[2], sub[3], [0, b - a], mask, scale)
+            dq_ref[a:b], dk_ref[a:b], dv_ref[a:b] = orc.attention_bwd_masked(*sub, [0, b - a], mask, scale)
+            _say(f"    oracle segment {j} [{a},{b}) done")
+    else:
+        o_ref, lse_ref = orc.attention_fwd(*(a.astype(np.float64) for a in (q, k, v)), cu, mask, scale)
+        dq_ref, dk_ref, dv_ref = orc.attention_bwd(*(a.astype(np.float64) for a in (d_o, q, k, v)),
+                                                   cu, mask, scale)
     # q, k, v live as column slices of one [T, (nq + 2 nkv) d] buffer, as inside the block
     Dq = (nq + 2 * nkv) * d
     qkv = to_dev(np.concatenate([q.reshape(T, -1), k.reshape(T, -1), v.reshape(T, -1)], axis=1))
@@ -507,6 +520,177 @@ def test_full_batch_one_segment_against_oracle(cfg):
     outside = np.ones(T, bool)
     outside[a:b] = False
     assert np.abs(dx[outside]).max() == 0.0
+
+
+def _bench_batch_cu(cfg, batch=0, seed=0):
+    """Segment offsets of balanced mini-batch `batch` of config `cfg`, built the way bench.py builds them."""
+    shape = si.CONFIGS[cfg]
+    if shape.kind == "vit":
+        return ob.ob_build_cu_seqlens_vit(shape.budget, si.VIT_TILE_TOKENS)
+    tiles, tok = si.synthetic_dataset(20000, seed)
+    groups, _, _ = ob.ob_pack_isf(tiles, tok, 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128, 10, seed)
+    return ob.ob_build_cu_seqlens_llm(groups[batch], tok)[0]
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("cfg", [3, 4, 5])
+def test_full_batch_every_row_and_gradient_against_oracle(cfg):
+    """The launch configurations the bench times, compared whole: one full balanced batch (config 3:
+    16K tokens, config 4: 16 tiles, config 5: 32K tokens), real dy on every row; every row of y and dx
+    and every weight gradient against the oracle.  The oracle runs segment by segment (a packed batch
+    is its segments run alone: pinned on the CPU) and its weight gradients are summed over the
+    segments.  Config 5's oracle runs in fp32 (77 TFLOP of host work; fp32 and fp64 oracle agree to
+    1e-5, pinned on the CPU), the others in fp64."""
+    shape = si.CONFIGS[cfg]
+    cu = _bench_batch_cu(cfg)
+    T, lens = int(cu[-1]), np.diff(cu)
+    odt = np.float32 if cfg == 5 else np.float64
+    _say(f"config {cfg} whole batch: T={T} n_seg={len(lens)} lens={lens.tolist()} oracle dtype={odt.__name__}")
+    w = si.block_weights(shape, seed=5)
+    x, dy = si.activations(T, shape.hidden, seed=5)
+    run, y, dx, g = run_block(shape, w, x, dy, cu)
+    _say("  HIP path done; oracle, segment by segment:")
+    w_o = {n: a.astype(odt) for n, a in w.items()}            # cast once, not per segment
+    y_ref, dx_ref = np.empty((T, shape.hidden), odt), np.empty((T, shape.hidden), odt)
+    g_ref = None
+    for j in range(len(lens)):
+        a, b = int(cu[j]), int(cu[j + 1])
+        yj, cache = orc.block_fwd(shape, w_o, x[a:b], [0, b - a], dtype=odt)
+        dxj, gj, _ = orc.block_bwd(shape, w_o, cache, dy[a:b], [0, b - a], dtype=odt)
+        y_ref[a:b], dx_ref[a:b] = yj, dxj
+        if g_ref is None:
+            g_ref = {n: v.astype(np.float64) for n, v in gj.items()}
+        else:
+            for n, v in gj.items():
+                g_ref[n] += v
+        _say(f"    segment {j} [{a},{b}) done")
+    errs = {"y": rel_err(y, y_ref), "dx": rel_err(dx, dx_ref)}
+    for n in g_ref:
+        errs["d" + n] = rel_err(g[n], g_ref[n])
+    _say("  " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    assert set(g_ref) == set(w)
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
+    # no row may hide behind the largest one: every segment's rows on their own scale too
+    for j in range(len(lens)):
+        a, b = int(cu[j]), int(cu[j + 1])
+        assert rel_err(y[a:b], y_ref[a:b]) <= TOL and rel_err(dx[a:b], dx_ref[a:b]) <= TOL, j
+
+
+@pytest.mark.parametrize("variant", ["llm-like", "vit-like"])
+def test_block_stack_of_three_against_oracle(variant):
+    """Three blocks of one kind chained forward and then backward, as the bench chains them (each
+    block with its own weights, `saved` and gradient buffers; activations handed from block to block,
+    gradients alternating between two buffers), against the oracle's stack: y of the last block, dx of
+    the first, and every block's weight gradients."""
+    if variant == "llm-like":
+        shape = si.small_shape(hidden=512, n_q_heads=8, n_kv_heads=2, head_dim=64, mlp_dim=704,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
+                               use_rotary=True, has_bias=False, norm_eps=1e-6)
+        lens = [300, 1, 140, 259, 77]
+    else:
+        shape = si.small_shape(hidden=384, n_q_heads=6, n_kv_heads=6, head_dim=64, mlp_dim=1536,
+                               norm=si.NORM_LAYERNORM, mlp=si.MLP_GELU, mask=si.MASK_BIDIR,
+                               use_rotary=False, has_bias=True)
+        lens = [257, 257, 257]
+    cu = si.lengths_to_cu(lens)
+    T, L = int(cu[-1]), 3
+    _say(f"stack {variant}: L={L} T={T} lens={lens}")
+    ws = [si.block_weights(shape, seed=21, block=i) for i in range(L)]
+    # activations of unit scale so that the three residual branches matter against the input
+    x_np, dy_np = si.activations(T, shape.hidden, seed=21, std=1.0)
+    y_ref, dx_ref, g_ref = orc.stack_fwd_bwd(shape, ws, x_np, dy_np, cu)
+
+    seg = ob.Segments(cu)
+    runs = [BlockRun(shape, w, T) for w in ws]
+    acts = [to_dev(x_np)]
+    for r in runs:
+        acts.append(r.fwd(acts[-1], seg))
+    gbuf = [torch.empty_like(acts[0]) for _ in range(2)]
+    g_in = to_dev(dy_np)
+    for i in reversed(range(L)):
+        g_out = gbuf[i & 1]
+        ob.ob_block_bwd(runs[i].desc, runs[i].w, runs[i].g, 0, acts[i], g_in, g_out, runs[i].saved, seg, runs[i].ws)
+        g_in = g_out
+    torch.cuda.synchronize()
+    errs = {"y": rel_err(to_np(acts[-1]), y_ref), "dx": rel_err(to_np(g_in), dx_ref)}
+    for i in range(L):
+        assert set(g_ref[i]) == set(ws[i])
+        for n in g_ref[i]:
+            errs[f"block{i}.d{n}"] = rel_err(to_np(runs[i].g[n]), g_ref[i][n])
+    _say("  " + ", ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_attention_alone_at_full_size_on_the_bench_batch(cfg):
+    """Varlen attention forward and backward alone at the full token count and head counts of the LLM
+    configurations (32 / 8 and 48 / 8 heads of 128, causal), on the segment layout of the bench's first
+    balanced batch; every segment, every head, against the oracle."""
+    shape = si.CONFIGS[cfg]
+    cu = _bench_batch_cu(cfg)
+    _check_attention(np.diff(cu).tolist(), shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.mask, seed=cfg,
+                     per_segment=True)
+
+
+@pytest.mark.parametrize("d,mask", [(64, orc.MASK_BIDIR), (64, orc.MASK_CAUSAL), (128, orc.MASK_BIDIR),
+                                    (128, orc.MASK_CAUSAL)])
+def test_attention_packed_equals_each_segment_alone_bit_for_bit(d, mask):
+    """What "samples stay whole" means for the kernels (Sec. 3, Sec. 4.1): tiles are aligned to segments,
+    so running the packed batch and running every segment as a batch of its own must give the same
+    bits, for o, lse, dq, dk and dv, for both masks and both head sizes.  This pins the masking of the
+    product kernels themselves at bit level."""
+    lens = [130, 1, 64, 257, 63, 200, 1025]
+    nq, nkv = 4, 2
+    cu = si.lengths_to_cu(lens)
+    T = int(cu[-1])
+    _say(f"packed vs alone d={d} mask={mask} lens={lens}")
+    q, k, v, d_o = si.qkv_tensors(T, nq, nkv, d, seed=d + mask)
+    scale = 1.0 / np.sqrt(d)
+    qd, kd, vd, dod = (to_dev(a.reshape(T, -1)) for a in (q, k, v, d_o))
+
+    def run(qs, ks, vs, dos, cu_):
+        t = qs.shape[0]
+        seg = ob.Segments(cu_)
+        o = torch.empty((t, nq * d), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((nq, t), dtype=torch.float32, device="cuda")
+        ob.ob_varlen_attn_fwd(qs, ks, vs, o, lse, nq * d, nkv * d, nq * d, seg, nq, nkv, d, scale, mask)
+        dq, dk, dv = torch.empty_like(qs), torch.empty_like(ks), torch.empty_like(vs)
+        ws = bytes_buf(ob.ob_varlen_attn_bwd_workspace_bytes(t, nq, nkv, d))
+        ob.ob_varlen_attn_bwd(dos, qs, ks, vs, o, lse, dq, dk, dv, nq * d, nkv * d, nq * d, seg, nq, nkv, d,
+                              scale, mask, ws)
+        torch.cuda.synchronize()
+        return o, lse, dq, dk, dv
+
+    o, lse, dq, dk, dv = run(qd, kd, vd, dod, cu)
+    for j in range(len(lens)):
+        a, b = int(cu[j]), int(cu[j + 1])
+        oj, lsej, dqj, dkj, dvj = run(qd[a:b], kd[a:b], vd[a:b], dod[a:b], np.array([0, b - a], dtype=np.int32))
+        for name, whole, alone in (("o", o[a:b], oj), ("dq", dq[a:b], dqj), ("dk", dk[a:b], dkj), ("dv", dv[a:b], dvj)):
+            assert torch.equal(whole.view(torch.int16), alone.view(torch.int16)), (name, j)
+        assert torch.equal(lse[:, a:b].contiguous().view(torch.int32), lsej.view(torch.int32)), ("lse", j)
+
+
+@pytest.mark.parametrize("n_seg", [257, 300, 520, 600])
+def test_attention_with_hundreds_of_segments(n_seg):
+    """More segments than one round of the kernels' in-workgroup segment scan covers (256), and more
+    than two rounds: segments of 1-70 tokens, against the oracle."""
+    rng = np.random.default_rng(n_seg)
+    lens = rng.integers(1, 71, n_seg).tolist()
+    _check_attention(lens, 4, 2, 64 if n_seg % 2 else 128, orc.MASK_CAUSAL if n_seg % 3 else orc.MASK_BIDIR, seed=n_seg)
+
+
+def test_block_with_hundreds_of_segments():
+    """The block's segment lookups (rotary positions, attention tiles) past 256 and past 512 segments."""
+    shape = si.small_shape(hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=64, mlp_dim=256,
+                           norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
+                           use_rotary=True, has_bias=False, norm_eps=1e-6)
+    rng = np.random.default_rng(9)
+    lens = rng.integers(1, 40, 530).tolist()
+    _say(f"block with {len(lens)} segments, T={sum(lens)}")
+    _check_block(shape, si.lengths_to_cu(lens), seed=8)
 
 
 # ---- ViT -> LLM hand-over: sub-sampling + connector ---------------------------------------------
