@@ -118,6 +118,20 @@ int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k, const void
                        const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
                        int dtype, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* The same backward for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Its scratch is a static
+ * device array of OB_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the
+ * process ends); the call allocates and frees nothing.  Limit: total_tokens * n_q_heads * 8 bytes
+ * (rounded up to 512) must fit the array (4 Mi query-head rows: e.g. 32768 tokens x 128 heads);
+ * beyond it the call returns OB_EWORKSPACE without launching anything.  Inputs, outputs and results
+ * are those of ob_varlen_attn_bwd.  All calls on one GPU share that GPU's array: calls that overlap
+ * in time on one GPU (different streams or threads) race; serialise them. */
+#define OB_STATIC_SCRATCH_BYTES (32u << 20)
+int ob_varlen_attn_bwd_static(const void *d_o, const void *q, const void *k, const void *v, const void *o,
+                              const float *lse, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
+                              const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
+                              int dtype, void *hip_stream);
+
 /* ---- one transformer block (steps a1..a9 / b9..b1) -------------------------------------------
  * ob_block_fwd:  y = Block(x); keeps in `saved` (ob_block_saved_bytes) what the backward needs.
  * ob_block_bwd:  given dy, the same x, weights and `saved`, writes dx and every weight gradient

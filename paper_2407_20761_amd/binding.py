@@ -93,6 +93,7 @@ _SIGNATURES = {
     "ob_varlen_attn_fwd": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _SEG, _I, _I, _I, _F, _I, _I, _P]),
     "ob_varlen_attn_bwd_workspace_bytes": (_Z, [_I, _I, _I, _I]),
     "ob_varlen_attn_bwd": (_I, [_P] * 9 + [_I, _I, _I, _SEG, _I, _I, _I, _F, _I, _I, _P, _Z, _P]),
+    "ob_varlen_attn_bwd_static": (_I, [_P] * 9 + [_I, _I, _I, _SEG, _I, _I, _I, _F, _I, _I, _P]),
     "ob_block_saved_bytes": (_Z, [_DESC, _I]),
     "ob_block_workspace_bytes": (_Z, [_DESC, _I]),
     "ob_block_saved_offset": (_Z, [_DESC, _I, C.c_char_p]),
@@ -212,6 +213,13 @@ def ob_varlen_attn_bwd(d_o, q, k, v, o, lse, dq, dk, dv, ldq, ldkv, ldo, seg: Se
                                   nq, nkv, d, scale, mask, dtype, _ptr(ws),
                                   0 if ws is None else ws.numel() * ws.element_size(),
                                   _stream(stream)))
+
+
+def ob_varlen_attn_bwd_static(d_o, q, k, v, o, lse, dq, dk, dv, ldq, ldkv, ldo, seg: Segments, nq, nkv,
+                              d, scale, mask, dtype=OB_BF16, stream=None):
+    _check(lib.ob_varlen_attn_bwd_static(_ptr(d_o), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                                         _ptr(dq), _ptr(dk), _ptr(dv), ldq, ldkv, ldo, C.byref(seg.c),
+                                         nq, nkv, d, scale, mask, dtype, _stream(stream)))
 
 
 def ob_block_saved_bytes(desc, total_tokens) -> int:

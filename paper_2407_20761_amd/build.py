@@ -12,7 +12,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libomnibal.so")
-SOURCES = ["api.cpp", "connector_api.cpp", "packer.cpp", "planner.cpp", "connector.hip", "gemm.hip", "elementwise.hip", "attention.hip", "debug_fp32.hip"]
+SOURCES = ["api.cpp", "connector_api.cpp", "packer.cpp", "planner.cpp", "connector.hip", "gemm.hip", "elementwise.hip", "attention.hip", "debug_fp32.hip", "noalloc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

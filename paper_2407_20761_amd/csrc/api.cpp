@@ -80,6 +80,8 @@ int validate_segments(const ob_segments *seg, const char *who) {
     return OB_OK;
 }
 
+}  // namespace
+
 int validate_attn(const ob_segments *seg, int nq, int nkv, int d, int ldq, int ldkv, int ldo,
                   int mask, int dtype, const char *who) {
     if (nq < 1 || nkv < 1 || nq % nkv != 0)
@@ -91,6 +93,8 @@ int validate_attn(const ob_segments *seg, int nq, int nkv, int d, int ldq, int l
         return fail(OB_EINVAL, "%s: row strides must cover the heads and be multiples of 8 elements", who);
     return validate_segments(seg, who);
 }
+
+namespace {
 
 int validate_desc(const ob_block_desc *dsc, const char *who) {
     if (!dsc) return fail(OB_EINVAL, "%s: desc is null", who);

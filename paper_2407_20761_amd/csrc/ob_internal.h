@@ -14,6 +14,10 @@ int check_launch(const char *what);
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// host-side checks shared by the attention entry points (api.cpp); OB_OK or a status with the text set
+int validate_attn(const ob_segments *seg, int nq, int nkv, int d, int ldq, int ldkv, int ldo,
+                  int mask, int dtype, const char *who);
+
 // ---- opt-in per-kernel-class timing (ob_prof_begin / ob_prof_end) --------------------------
 enum KClass {
     K_GEMM = 0, K_ATTN_FWD, K_ATTN_BWD_DQ, K_ATTN_BWD_DKV, K_ATTN_DELTA, K_NORM_FWD,

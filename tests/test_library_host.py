@@ -109,6 +109,17 @@ def test_attention_argument_validation():
     st = ob.lib.ob_varlen_attn_bwd(p, p, p, p, p, p, p, p, p, 256, 128, 256, C.byref(good.c),
                                    4, 2, 64, 0.125, 1, 0, p, 16, None)
     assert st == ob.OB_EWORKSPACE
+    # the variant with the library's static scratch: same checks, and sizes beyond its array are refused
+    st = ob.lib.ob_varlen_attn_bwd_static(p, p, p, p, p, p, p, p, p, 256, 128, 256, C.byref(_seg([0, 7, 5, 9]).c),
+                                          4, 2, 64, 0.125, 1, 0, None)
+    assert st == ob.OB_ESEGMENTS
+    st = ob.lib.ob_varlen_attn_bwd_static(None, p, p, p, p, p, p, p, p, 256, 128, 256, C.byref(good.c),
+                                          4, 2, 64, 0.125, 1, 0, None)
+    assert st == ob.OB_EINVAL
+    big = _seg([0, 1 << 20])
+    st = ob.lib.ob_varlen_attn_bwd_static(p, p, p, p, p, p, p, p, p, 512, 512, 512, C.byref(big.c),
+                                          8, 8, 64, 0.125, 1, 0, None)
+    assert st == ob.OB_EWORKSPACE and "static" in ob.ob_last_error()
 
 
 def test_block_argument_validation_and_sizes():
