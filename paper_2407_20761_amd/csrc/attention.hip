@@ -20,6 +20,7 @@
 // read 16-byte fragments; products that contract over the streamed rows read the same tile with
 // the transposing LDS read (ds_read_b64_tr_b16), so no tile is ever stored twice.  16-byte chunks
 // are XOR-swizzled by the row so that both kinds of read are free of bank conflicts.
+#include <algorithm>
 #include <type_traits>
 
 #include "ob_internal.h"
@@ -126,13 +127,36 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
     return o;
 }
 
-// Which segment-aligned tile (of `tile_rows` rows) is blockIdx.x: tiles are numbered segment by
-// segment.  Thread j looks at segment j (256 segments per round), an inclusive scan over the
-// workgroup gives each segment's first tile number, and the thread whose range holds blockIdx.x
+// Which workgroup does which tile.  The launch is one-dimensional: workgroup b works on tile
+// b / heads for head slot b % heads, so all heads of a tile are dispatched together, and (workgroups
+// being dealt round-robin to the 8 XCDs) head slot hs runs on XCD hs % 8: with a head count that is a
+// multiple of 8 the slots are renumbered so that an XCD only ever sees heads [x heads/8, (x+1) heads/8),
+// i.e. the query heads of one key/value group (and that group's K and V) stay in one XCD's L2.
+__device__ __forceinline__ int head_of_slot(int hs, int heads) {
+    return (heads & 7) == 0 ? (hs & 7) * (heads >> 3) + (hs >> 3) : hs;
+}
+
+// Order of the tiles: heaviest first.  The work of a tile is the number of streamed tiles it walks;
+// in a causal batch that differs by an order of magnitude between the first and the last tile of a
+// long segment, and a launch that hands out the tiles segment by segment ends with a few workgroups
+// on the heaviest tiles of the last segment while the rest of the chip idles (simulated on the
+// benchmark's batches: 20 % of the forward's and 40 % of the dK/dV kernel's duration).  The host
+// sorts the tiles by work (ties: natural order) and passes the order as a kernel argument:
+// entry = segment << 16 | tile in segment.  n == 0 (more tiles than the table holds, or a segment or
+// tile number beyond 16 bits): natural order, found by find_tile.
+struct TileOrder {
+    static constexpr int CAP = 896;
+    int n;
+    uint32_t e[CAP];
+};
+
+// Which segment-aligned tile (of `tile_rows` rows) has number `tile` when tiles are numbered segment
+// by segment.  Thread j looks at segment j (256 segments per round), an inclusive scan over the
+// workgroup gives each segment's first tile number, and the thread whose range holds `tile`
 // publishes the answer -- one global-memory round trip instead of a serial walk over cu.
 struct TileInfo { int seg_start, seg_end, row0; };
 __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, int n_seg, int tile_rows,
-                                              int *sh /* >= 8 ints */) {
+                                              int *sh /* >= 8 ints */, int tile) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const bool scans = tid < 256;  // waves past the fourth only take part in the barriers
     if (tid == 0) sh[2] = -1;
@@ -157,10 +181,10 @@ __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, in
         int before = base;
         for (int w = 0; w < (wave & 3); ++w) before += sh[4 + w];
         const int first = before + incl - nt;  // number of this segment's first tile
-        if (scans && nt > 0 && (int)blockIdx.x >= first && (int)blockIdx.x < first + nt) {
+        if (scans && nt > 0 && tile >= first && tile < first + nt) {
             sh[0] = a;
             sh[1] = b;
-            sh[2] = a + ((int)blockIdx.x - first) * tile_rows;
+            sh[2] = a + (tile - first) * tile_rows;
         }
         base += sh[4] + sh[5] + sh[6] + sh[7];
     }
@@ -169,6 +193,19 @@ __device__ __forceinline__ TileInfo find_tile(const int32_t *__restrict__ cu, in
     t.seg_start = __builtin_amdgcn_readfirstlane(sh[0]);
     t.seg_end = __builtin_amdgcn_readfirstlane(sh[1]);
     t.row0 = __builtin_amdgcn_readfirstlane(sh[2]);
+    return t;
+}
+
+// tile number `rank` in the order of work
+__device__ __forceinline__ TileInfo pick_tile(const TileOrder &ord, int rank, const int32_t *__restrict__ cu,
+                                              int n_seg, int tile_rows, int *sh) {
+    if (ord.n == 0) return find_tile(cu, n_seg, tile_rows, sh, rank);
+    const uint32_t e = ord.e[rank];
+    const int seg = (int)(e >> 16);
+    TileInfo t;
+    t.seg_start = __builtin_amdgcn_readfirstlane(cu[seg]);
+    t.seg_end = __builtin_amdgcn_readfirstlane(cu[seg + 1]);
+    t.row0 = t.seg_start + (int)(e & 0xFFFFu) * tile_rows;
     return t;
 }
 
@@ -284,15 +321,16 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
     __bf16 *__restrict__ o, float *__restrict__ lse, int ldq, int ldkv, int ldo,
-    const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale) {
+    const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale, int heads, TileOrder ord) {
     __shared__ __attribute__((aligned(1024))) unsigned char k_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char v_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char k_s1[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char v_s1[Tile<D>::BYTES];
     __shared__ int sh[8];
-    const TileInfo ti = find_tile(cu, n_seg, QT, sh);
+    const int rank = blockIdx.x / heads;
+    const TileInfo ti = pick_tile(ord, rank, cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
-    const int head = blockIdx.y, kvh = head / group;
+    const int head = head_of_slot(blockIdx.x - rank * heads, heads), kvh = head / group;
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q_row = min(ti.row0 + wave * 32 + lx, ti.seg_end - 1);
@@ -457,13 +495,14 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo, const int32_t *__restrict__ cu, int n_seg,
-    int T, int group, float scale) {
+    int T, int group, float scale, int heads, TileOrder ord) {
     // stages 0 / 1 of the K and V tiles; after the last tile the same bytes carry the dQ partials
     __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * Tile<D>::BYTES];
     __shared__ int sh[8];
-    const TileInfo ti = find_tile(cu, n_seg, QT_DQ, sh);
+    const int rank = blockIdx.x / heads;
+    const TileInfo ti = pick_tile(ord, rank, cu, n_seg, QT_DQ, sh);
     if (ti.row0 < 0) return;
-    const int head = blockIdx.y, kvh = head / group;
+    const int head = head_of_slot(blockIdx.x - rank * heads, heads), kvh = head / group;
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int pair = wave & 1, half = wave >> 1;
@@ -686,16 +725,18 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int ldq, int ldkv, int ldo,
-    const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale) {
+    const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale, int heads, TileOrder ord) {
     // three stages of the streamed Q and dO tiles (the dK side works one tile behind the dV side, see
     // below), two buffers for the probabilities on their way from one to the other, row statistics
     __shared__ __attribute__((aligned(1024))) unsigned char tiles_s[6 * Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char p_s[2 * 4 * 4096];  // [buffer][pair]: 4 x 64 lanes x 16 B
     __shared__ __attribute__((aligned(256))) float stat_s[6 * ST];              // lse2 x 3 stages, Delta x 3 stages
     __shared__ int sh[8];
-    const TileInfo ti = find_tile(cu, n_seg, QT, sh);
+    const int rank = blockIdx.x / heads;
+    const TileInfo ti = pick_tile(ord, rank, cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
-    const int kvh = blockIdx.y;  // one workgroup per key/value head: the group's query heads run one after another
+    // one workgroup per key/value head: the group's query heads run one after another
+    const int kvh = head_of_slot(blockIdx.x - rank * heads, heads);
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int pair = wave & 3;
@@ -886,19 +927,48 @@ int count_tiles(const ob_segments *seg, int tile_rows) {
     return (int)n;
 }
 
+// Order of work of a launch whose workgroups own `tile_rows` rows of a segment and stream 64-row
+// tiles of the other side: descending number of streamed tiles, ties in natural order.  `kv_side`:
+// the workgroup owns key rows and streams query tiles (from its diagonal on when causal); otherwise
+// it owns query rows and streams key tiles (up to its diagonal when causal).  No heap memory.
+void make_order(const ob_segments *seg, int tile_rows, bool causal, bool kv_side, int n_tiles, TileOrder &ord) {
+    ord.n = 0;
+    if (n_tiles > TileOrder::CAP || seg->n_seg > 0xFFFF) return;
+    uint64_t key[TileOrder::CAP];
+    int n = 0;
+    for (int j = 0; j < seg->n_seg; ++j) {
+        const int a = seg->cu_host[j], len = seg->cu_host[j + 1] - a;
+        const int nt = (len + tile_rows - 1) / tile_rows;
+        if (nt > 0xFFFF) return;
+        for (int t = 0; t < nt; ++t) {
+            int rows = len;                                            // streamed rows
+            if (causal && kv_side) rows = len - (t * tile_rows) / ST * ST;
+            else if (causal) rows = std::min(len, (t + 1) * tile_rows);
+            const uint32_t w = (uint32_t)((rows + ST - 1) / ST);
+            // ascending sort of (~work, natural index); the entry rides in the low half
+            key[n] = ((uint64_t)(0xFFFFFu - w) << 44) | ((uint64_t)n << 32) | ((uint32_t)j << 16) | (uint32_t)t;
+            ++n;
+        }
+    }
+    std::sort(key, key + n);
+    for (int i = 0; i < n; ++i) ord.e[i] = (uint32_t)key[i];
+    ord.n = n;
+}
+
 // explicit instantiations (the host pass otherwise drops launch stubs of kernels reached only
 // through the dispatch macro below)
 #define OB_ATTN_INSTANCES(D, C)                                                                               \
     template __global__ void attn_fwd_kernel<D, C>(const __bf16 *, const __bf16 *, const __bf16 *, __bf16 *,  \
                                                    float *, int, int, int, const int32_t *, int, int, int,    \
-                                                   float);                                                    \
+                                                   float, int, TileOrder);                                    \
     template __global__ void attn_bwd_dq_kernel<D, C>(const __bf16 *, const __bf16 *, const __bf16 *,         \
                                                       const __bf16 *, const float *, const float *, __bf16 *, \
-                                                      int, int, int, const int32_t *, int, int, int, float);  \
+                                                      int, int, int, const int32_t *, int, int, int, float,   \
+                                                      int, TileOrder);                                        \
     template __global__ void attn_bwd_dkv_kernel<D, C>(const __bf16 *, const __bf16 *, const __bf16 *,        \
                                                        const __bf16 *, const float *, const float *,          \
                                                        __bf16 *, __bf16 *, int, int, int,                     \
-                                                       const int32_t *, int, int, int, float);
+                                                       const int32_t *, int, int, int, float, int, TileOrder);
 OB_ATTN_INSTANCES(64, true)
 OB_ATTN_INSTANCES(64, false)
 OB_ATTN_INSTANCES(128, true)
@@ -924,10 +994,13 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
                      int mask, hipStream_t s) {
     const bool causal = mask == OB_MASK_SEG_CAUSAL;
     ProfScope prof(K_ATTN_FWD, s, attn_flops(seg, nq, d, causal));
-    const dim3 grid(count_tiles(seg, QT), nq);
+    const int tiles = count_tiles(seg, QT);
+    TileOrder ord;
+    make_order(seg, QT, causal, false, tiles, ord);
+    const dim3 grid((unsigned)tiles * nq);
     OB_ATTN_DISPATCH(attn_fwd_kernel, grid, 256, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
                      (__bf16 *)o, lse, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, seg->total_tokens,
-                     nq / nkv, scale);
+                     nq / nkv, scale, nq, ord);
 }
 
 void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse2,
@@ -939,16 +1012,21 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     const int T = seg->total_tokens, group = nq / nkv;
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
-        const dim3 grid_q(count_tiles(seg, QT_DQ), nq);
+        const int tiles_q = count_tiles(seg, QT_DQ);
+        TileOrder ord;
+        make_order(seg, QT_DQ, causal, false, tiles_q, ord);
+        const dim3 grid_q((unsigned)tiles_q * nq);
         OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 256, (const __bf16 *)d_o, (const __bf16 *)q,
                          (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
-                         seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale);
+                         seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale, nq, ord);
     }
     ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
-    const dim3 grid_kv(tiles, nkv);
+    TileOrder ord;
+    make_order(seg, QT, causal, true, tiles, ord);
+    const dim3 grid_kv((unsigned)tiles * nkv);
     OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_kv, 512, (const __bf16 *)d_o, (const __bf16 *)q,
                      (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dk, (__bf16 *)dv, ldq, ldkv,
-                     ldo, seg->cu_dev, seg->n_seg, T, group, scale);
+                     ldo, seg->cu_dev, seg->n_seg, T, group, scale, nkv, ord);
 }
 
 }  // namespace ob
