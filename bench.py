@@ -3,7 +3,12 @@
 variable-length mini-batches on ONE MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config {2,3,4,5}] [--seed S]
-                    [--spread-batches N] [--skip-cpu-baseline]
+                    [--spread-batches N] [--skip-cpu-baseline] [--also [CFG ...]] [--also-steps K2]
+
+The line's headline (value, roofline, kernels, spread, cpu_baseline) is --config (default 3, the
+7B-shaped stack); its "configs" object carries the other configurations (default 2, 4 and 5, K2 steps
+each: ms, TFLOP/s, % of peak, tokens/s, kernel classes; config 5 with the balanced-versus-random
+spread over 50 + 50 mini-batches).  `--also` with no value runs the headline configuration only.
 
 A step = build the segment offsets of the next balanced mini-batch (host), upload them, run all L
 blocks forward and then backward (every row of the hot path).  Inputs (weights, activations) are
@@ -283,78 +288,75 @@ def mixed_report(seed, n_vit=4, n_llm=4, steps=3):
             "activation_mb_after_connector": info[-1]["tiles"] * si.LLM_TOKENS_PER_TILE * ts.hidden * 2 / 1e6}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5])
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--spread-batches", type=int, default=50)
-    ap.add_argument("--skip-cpu-baseline", action="store_true")
-    ap.add_argument("--report", choices=["packer", "bmp", "mixed"], default=None,
-                    help="instead of the step benchmark print one JSON line of a host-side report: "
-                         "'packer' = grouping arms, ISF convergence and Q' ablation on the synthetic "
-                         "dataset (no GPU needed); 'bmp' = model-partition search fed by measured "
-                         "per-block forward times; 'mixed' = a pipeline stage holding ViT blocks, the "
-                         "token sub-sampling + connector and LLM blocks, run on one mini-batch")
-    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
-                    help="before the warm-up, copy this many MiB device-to-device three times: a "
-                         "kernel of known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
-              "--gpus N with N > 1 is not supported", file=sys.stderr)
-        sys.exit(2)
+def git_describe(path):
+    """Commit and date of the last change to `path` (for figures read from committed summaries)."""
+    import subprocess
+    try:
+        r = subprocess.run(["git", "log", "-1", "--format=%h %cs", "--", path], cwd=ROOT, capture_output=True,
+                           text=True, timeout=10)
+        return r.stdout.strip() or None
+    except Exception:
+        return None
 
-    if args.report == "packer":
-        print(json.dumps(packer_report(args.seed)))
-        return
-    if args.report == "bmp":
-        print(json.dumps(bmp_report(args.seed)))
-        return
-    if args.report == "mixed":
-        print(json.dumps(mixed_report(args.seed)))
-        return
+
+def bench_config(config, steps, warmup, seed, spread_batches, full, cpu_baseline, calibrate_copy_mib=0):
+    """One configuration on cuda:0.  full = True: the whole report (per-kernel HIP-event timing, roofline,
+    re-computation, spread, oracle timing); False: the timed steps, the kernel classes and, when
+    spread_batches > 0, the spread."""
+    import gc
 
     import torch
 
     import paper_2407_20761_amd as ob
     import synth_inputs as si
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    shape = si.CONFIGS[args.config]
+    shape = si.CONFIGS[config]
     L = shape.n_blocks
     desc = ob.make_desc(shape)
 
     # ---- host side: synthetic dataset -> balanced groups (Alg. 1) and the random baseline ----
-    tiles, tok = si.synthetic_dataset(20000, args.seed)
+    tiles, tok = si.synthetic_dataset(20000, seed)
     t0 = time.perf_counter()
     if shape.kind == "llm":        # token budget closes the groups
         Qv, Qt, Qvm, Qtm = 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128
     else:                          # tile budget closes the groups
         Qv, Qt, Qvm, Qtm = shape.budget, 10 ** 9, shape.budget, 10 ** 9
-    groups, leftover, per_iter = ob.ob_pack_isf(tiles, tok, Qv, Qt, Qvm, Qtm, 10, args.seed)
+    groups, leftover, per_iter = ob.ob_pack_isf(tiles, tok, Qv, Qt, Qvm, Qtm, 10, seed)
     packer_ms = (time.perf_counter() - t0) * 1e3
     B = max(1, int(round(float(np.mean([len(g) for g in groups])))))
-    rgroups, _ = ob.ob_pack_random(len(tiles), B, args.seed)
+    rgroups, _ = ob.ob_pack_random(len(tiles), B, seed)
+    # the whole dataset as mini-batches: the accepted groups plus what Alg. 1 left in D after its last
+    # iteration, grouped by one more sampling pass that keeps every candidate (filter thresholds 0),
+    # in a seeded random order
+    everything = list(groups)
+    if len(leftover):
+        more, _, _ = ob.ob_pack_isf(tiles[leftover], tok[leftover], Qv, Qt, 0, 0, 1, seed)
+        everything += [leftover[g] for g in more]
+    order = np.random.default_rng(seed).permutation(len(everything))
+    everything = [everything[i] for i in order]
+    size_of = (lambda g: int(tok[g].sum())) if shape.kind == "llm" else (lambda g: int(tiles[g].sum()))
+
+    def step_dist_ratio(gs, n_dev=8):          # Eq. 2 over the n_dev mini-batches of a step, averaged over steps
+        gs = gs[:len(gs) // n_dev * n_dev]
+        return float(np.mean([ob.ob_dist_ratio([size_of(g) for g in gs[k:k + n_dev]])
+                              for k in range(0, len(gs), n_dev)])) if gs else None
 
     def cu_of(group):
         if shape.kind == "llm":
             return ob.ob_build_cu_seqlens_llm(group, tok)[0]
         return ob.ob_build_cu_seqlens_vit(int(tiles[group].sum()), si.VIT_TILE_TOKENS)
 
-    n_spread = min(args.spread_batches, len(groups), len(rgroups))
-    n_used = max(args.steps + args.warmup, n_spread, 1)
+    n_spread = min(spread_batches, len(groups), len(rgroups))
+    n_used = max(steps + warmup, n_spread, 1)
     bal = [groups[i % len(groups)] for i in range(n_used)]
     rnd = rgroups[:n_spread]
-    Tmax = max(int(cu_of(g)[-1]) for g in bal + rnd)
+    allb = everything[:n_spread] if full else []
+    Tmax = max(int(cu_of(g)[-1]) for g in bal + rnd + allb)
 
     # ---- device state, resident before the timed region ---------------------------------------
     gen = torch.Generator(device=dev)
-    gen.manual_seed(args.seed)
+    gen.manual_seed(seed)
     weights, grads = [], []
     for _ in range(L):
         w = {}
@@ -389,20 +391,20 @@ def main():
             g_in = g_out
         return cu
 
-    if args.calibrate_copy_mib > 0:
-        src = torch.empty(args.calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
+    if calibrate_copy_mib > 0:
+        src = torch.empty(calibrate_copy_mib << 20, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(bal[i])
     torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps ----------------------------------------------------------
-    timed = bal[args.warmup:args.warmup + args.steps]
+    timed = bal[warmup:warmup + steps]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     flops = 0.0
@@ -413,7 +415,7 @@ def main():
         tokens += int(cu[-1])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
+    ms_per_step = elapsed * 1e3 / steps
     tflops = flops / elapsed / 1e12
 
     # ---- same K steps again with every kernel bracketed by HIP events on its stream -----------
@@ -431,62 +433,17 @@ def main():
             continue
         mfma = name in ("gemm", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv")
         rate = work / (ms * 1e-3) / (1e12 if mfma else 1e9) if ms > 0 else 0.0
-        kernels[name] = {"ms_per_step": ms / args.steps, "launches_per_step": cnt / args.steps,
+        kernels[name] = {"ms_per_step": ms / steps, "launches_per_step": cnt / steps,
                          "avg_us": 1e3 * ms / cnt, "bound": "mfma" if mfma else "hbm",
                          "achieved": rate, "unit": "TFLOP/s" if mfma else "GB/s",
                          "frac": rate / (PEAK_BF16_TFLOPS if mfma else PEAK_HBM_GBS)}
-    gms, gcnt, gwork = prof["gemm"]
-    g_ach = gwork / (gms * 1e-3) / 1e12
-    # compulsory HBM bytes of the 12 GEMMs of a block (operands once, result once, residual once)
-    T_avg = tokens / args.steps
-    Dq, HD, upF, F = shape.d_qkv, shape.n_q_heads * shape.head_dim, shape.up_rows, shape.mlp_dim
-    mnk = [(T_avg, Dq, H), (T_avg, H, HD), (T_avg, upF, H), (T_avg, H, F),      # forward
-           (T_avg, H, Dq), (T_avg, HD, H), (T_avg, H, upF), (T_avg, F, H),      # dgrad
-           (Dq, H, T_avg), (H, HD, T_avg), (upF, H, T_avg), (H, F, T_avg)]      # wgrad
-    alg_bytes = sum(2.0 * (m * k + n * k + m * n) for m, n, k in mnk) + 2 * 2.0 * T_avg * H
-    roofline = {"kernel": "gemm_kernel (bf16 MFMA 16x16x32; NT, NN and TN instances)", "bound": "mfma",
-                "achieved": g_ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": g_ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.config, "gemm"),
-                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
-                "algorithmic_bytes_per_launch": alg_bytes / 12.0,
-                "avg_launch_us": 1e3 * gms / gcnt, "launches": gcnt,
-                "flops_per_launch_avg": gwork / gcnt,
-                "share_of_step_time": gms / (prof_elapsed * 1e3)}
-
-    # ---- re-computation (Sec. 4.3): every block replays its forward; one saved buffer serves all --
-    def step_recompute(group):
-        cu = cu_of(group)
-        seg = ob.Segments(cu, device=dev)
-        T = int(cu[-1])
-        for i in range(L):
-            ob.ob_block_fwd(desc, weights[i], acts[i][:T], acts[i + 1][:T], saved[0], seg, ws, stream)
-        g_in = dy[:T]
-        for i in reversed(range(L)):
-            g_out = gbuf[i & 1][:T]
-            ob.ob_block_bwd(desc, weights[i], grads[i], ob.OB_BWD_RECOMPUTE, acts[i][:T], g_in, g_out,
-                            saved[0], seg, ws, stream)
-            g_in = g_out
-
-    n_rc = min(3, args.steps)
-    step_recompute(timed[0])
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for g in timed[:n_rc]:
-        step_recompute(g)
-    torch.cuda.synchronize()
-    rc_ms = (time.perf_counter() - t0) * 1e3 / n_rc
-    base_ms = ms_per_step
-    per_block = ob.ob_block_saved_bytes(desc, Tmax)
-    free_now, total_mem = torch.cuda.mem_get_info()
-    m_r = free_now + (L - 1) * per_block           # what would be free with re-computation everywhere
-    fwd_ms_block = max(rc_ms - base_ms, 0.0) / L   # replay cost of one block
-    kinds = (0, 1, 0.0, L, per_block, fwd_ms_block) if shape.kind == "llm" else (L, per_block, fwd_ms_block, 0, 1, 0.0)
-    keep_v, keep_t = ob.ob_recompute_plan(m_r, *kinds)
-    recompute = {"ms_per_step_all_blocks_recomputed": rc_ms, "ms_per_step_none_recomputed": base_ms,
-                 "replay_ms_per_block": fwd_ms_block, "saved_bytes_per_block": int(per_block),
-                 "bytes_freed_by_recomputing_all": int((L - 1) * per_block),
-                 "free_bytes_with_all_recomputed": int(m_r), "hbm_bytes": int(total_mem),
-                 "blocks_that_may_skip_recomputation": int(keep_v + keep_t), "n_blocks": L}
+    workload = (f"config {config}: {shape.name}, {L} blocks, hidden {H}, "
+                f"{shape.n_q_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, mlp {shape.mlp_dim}, "
+                f"balanced packed batches of {shape.budget} {'tokens' if shape.kind == 'llm' else 'tiles x 1025 tokens'}")
+    res = {"workload": workload, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step, "tflops": tflops,
+           "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "tokens_per_s": tokens / elapsed,
+           "tokens_per_step": tokens / steps, "flops_per_step": flops / steps,
+           "ms_per_step_with_event_profiling": prof_elapsed * 1e3 / steps}
 
     # ---- step-time spread: balanced vs random grouping ----------------------------------------
     spread = None
@@ -518,58 +475,206 @@ def main():
         pad = float(np.mean([ob.ob_pad_ratio(tok[g].astype(np.int64)) for g in rnd]))
         spread = {"balanced": stats(bms, btok), "random": stats(rms, rtok),
                   "random_group_size": B, "random_pad_ratio_if_padded": pad,
-                  "balanced_pad_ratio": 0.0}
+                  "balanced_pad_ratio": 0.0,
+                  # which statistic the "below 5 %" target is read on: the population CV of the step
+                  # time over the accepted balanced mini-batches (the paper's STD divides by N: Fig. 2)
+                  "target": {"statistic": "balanced.cv", "bar": 0.05, "met": bool(bms.std() / bms.mean() < 0.05)},
+                  "note": "balanced = groups Alg. 1 accepted; balanced_all_samples (headline config only) = "
+                          "the whole dataset, the samples Alg. 1 left over grouped by one unfiltered pass"}
+        if allb:
+            ams, atok = time_batches(allb)
+            spread["balanced_all_samples"] = stats(ams, atok)
+    res["spread"] = spread
+    res["packer"] = {"ms": packer_ms, "samples": int(len(tiles)), "groups": len(groups),
+                     "leftover": int(len(leftover)), "groups_per_iter": [int(a) for a in per_iter],
+                     "mini_batches_whole_dataset": len(everything),
+                     "dist_ratio_8_devices_accepted_groups": step_dist_ratio(list(groups)),
+                     "dist_ratio_8_devices_whole_dataset": step_dist_ratio(everything),
+                     "dist_ratio_8_devices_random": step_dist_ratio(list(rgroups)),
+                     "dist_ratio_unit": "tokens" if shape.kind == "llm" else "tiles"}
+    res["kernels"] = kernels
+    if not full:
+        del weights, grads, acts, dy, gbuf, saved, ws
+        gc.collect()
+        torch.cuda.empty_cache()
+        return res
+
+    gms, gcnt, gwork = prof["gemm"]
+    g_ach = gwork / (gms * 1e-3) / 1e12
+    # compulsory HBM bytes of the 12 GEMMs of a block (operands once, result once, residual once)
+    T_avg = tokens / steps
+    Dq, HD, upF, F = shape.d_qkv, shape.n_q_heads * shape.head_dim, shape.up_rows, shape.mlp_dim
+    mnk = [(T_avg, Dq, H), (T_avg, H, HD), (T_avg, upF, H), (T_avg, H, F),      # forward
+           (T_avg, H, Dq), (T_avg, HD, H), (T_avg, H, upF), (T_avg, F, H),      # dgrad
+           (Dq, H, T_avg), (H, HD, T_avg), (upF, H, T_avg), (H, F, T_avg)]      # wgrad
+    alg_bytes = sum(2.0 * (m * k + n * k + m * n) for m, n, k in mnk) + 2 * 2.0 * T_avg * H
+    roofline = {"kernel": "gemm_kernel (bf16 MFMA 16x16x32; NT, NN and TN instances)", "bound": "mfma",
+                "achieved": g_ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": g_ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(config, "gemm"),
+                "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
+                "traffic_source": "profiles/hbm_traffic.txt, last changed at commit " +
+                                  str(git_describe("profiles/hbm_traffic.txt")),
+                "algorithmic_bytes_per_launch": alg_bytes / 12.0,
+                "avg_launch_us": 1e3 * gms / gcnt, "launches": gcnt,
+                "flops_per_launch_avg": gwork / gcnt,
+                "share_of_step_time": gms / (prof_elapsed * 1e3)}
+
+    # ---- re-computation (Sec. 4.3): every block replays its forward; one saved buffer serves all --
+    def step_recompute(group):
+        cu = cu_of(group)
+        seg = ob.Segments(cu, device=dev)
+        T = int(cu[-1])
+        for i in range(L):
+            ob.ob_block_fwd(desc, weights[i], acts[i][:T], acts[i + 1][:T], saved[0], seg, ws, stream)
+        g_in = dy[:T]
+        for i in reversed(range(L)):
+            g_out = gbuf[i & 1][:T]
+            ob.ob_block_bwd(desc, weights[i], grads[i], ob.OB_BWD_RECOMPUTE, acts[i][:T], g_in, g_out,
+                            saved[0], seg, ws, stream)
+            g_in = g_out
+
+    n_rc = min(3, steps)
+    step_recompute(timed[0])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for g in timed[:n_rc]:
+        step_recompute(g)
+    torch.cuda.synchronize()
+    rc_ms = (time.perf_counter() - t0) * 1e3 / n_rc
+    base_ms = ms_per_step
+    per_block = ob.ob_block_saved_bytes(desc, Tmax)
+    free_now, total_mem = torch.cuda.mem_get_info()
+    m_r = free_now + (L - 1) * per_block           # what would be free with re-computation everywhere
+    fwd_ms_block = max(rc_ms - base_ms, 0.0) / L   # replay cost of one block
+    kinds = (0, 1, 0.0, L, per_block, fwd_ms_block) if shape.kind == "llm" else (L, per_block, fwd_ms_block, 0, 1, 0.0)
+    keep_v, keep_t = ob.ob_recompute_plan(m_r, *kinds)
+    recompute = {"ms_per_step_all_blocks_recomputed": rc_ms, "ms_per_step_none_recomputed": base_ms,
+                 "replay_ms_per_block": fwd_ms_block, "saved_bytes_per_block": int(per_block),
+                 "bytes_freed_by_recomputing_all": int((L - 1) * per_block),
+                 "free_bytes_with_all_recomputed": int(m_r), "hbm_bytes": int(total_mem),
+                 "blocks_that_may_skip_recomputation": int(keep_v + keep_t), "n_blocks": L}
+
+    first_cu = cu_of(bal[0])
+    del weights, grads, acts, dy, gbuf, saved, ws
+    gc.collect()
+    torch.cuda.empty_cache()
 
     # ---- the oracle on the host cores, bounded sample -----------------------------------------
     cpu = None
-    if not args.skip_cpu_baseline:
+    if cpu_baseline:
         from oracle import block as orc
-        cu = cu_of(bal[0])
+        cu = first_cu
         # about 8 TFLOP of oracle work (10-30 s on the host cores), in whole segments
         per_token = step_flops(shape, np.array([0, 1]), 1)
         n = max(1, int(np.searchsorted(cu, 8e12 / per_token, side="right")) - 1)
         cu_s = cu[:n + 1].astype(np.int64)
         Ts = int(cu_s[-1])
-        w_np = si.block_weights(shape, seed=args.seed)
-        x_np, dy_np = si.activations(Ts, H, seed=args.seed)
+        w_np = si.block_weights(shape, seed=seed)
+        x_np, dy_np = si.activations(Ts, H, seed=seed)
         try:
             from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+            pools = threadpool_info()
+            cores = max([p.get("num_threads", 1) for p in pools] + [1])
+            blas = ", ".join(sorted({f"{p.get('internal_api')} {p.get('num_threads')} threads" for p in pools
+                                     if p.get("user_api") == "blas"})) or "unknown"
         except Exception:
-            cores = os.cpu_count()
-        t0 = time.perf_counter()
-        y_ref, cache = orc.block_fwd(shape, w_np, x_np, cu_s)
-        orc.block_bwd(shape, w_np, cache, dy_np, cu_s)
-        cpu_s = time.perf_counter() - t0
+            cores, blas = os.cpu_count(), "unknown"
         cpu_flops = step_flops(shape, cu_s, 1)
-        cpu = {"value": cpu_flops / cpu_s / 1e12, "unit": "TFLOP/s", "cores": int(cores),
+
+        def time_oracle(dtype):
+            t0 = time.perf_counter()
+            y_ref, cache = orc.block_fwd(shape, w_np, x_np, cu_s, dtype=dtype)
+            orc.block_bwd(shape, w_np, cache, dy_np, cu_s, dtype=dtype)
+            return time.perf_counter() - t0
+
+        s64 = time_oracle(np.float64)
+        s32 = time_oracle(np.float32)
+        cpu = {"value": cpu_flops / s64 / 1e12, "unit": "TFLOP/s", "cores": int(cores),
                "kind": "oracle",
                "sample": f"1 of {L} blocks fwd+bwd, first {n} whole segments ({Ts} tokens) of "
-                         f"balanced batch 0, fp64 numpy, {cpu_s:.1f} s",
-               "full_step_extrapolated_s": step_flops(shape, cu_of(bal[0]), L) / (cpu_flops / cpu_s)}
+                         f"balanced batch 0, fp64 numpy, {s64:.1f} s",
+               "blas": blas,
+               "fp32": {"value": cpu_flops / s32 / 1e12, "unit": "TFLOP/s", "seconds": s32,
+                        "note": "the same oracle and sample with dtype float32"},
+               "full_step_extrapolated_s": step_flops(shape, first_cu, L) / (cpu_flops / s64)}
 
     out = {
         "metric": "block_stack_fwd_bwd_tflops", "value": tflops, "unit": "TFLOP/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"config {args.config}: {shape.name}, {L} blocks, hidden {H}, "
-                               f"{shape.n_q_heads}/{shape.n_kv_heads} heads x {shape.head_dim}, "
-                               f"mlp {shape.mlp_dim}, balanced packed batches of "
-                               f"{shape.budget} {'tokens' if shape.kind == 'llm' else 'tiles x 1025 tokens'}",
-                   "n_blocks": L, "tokens_per_step": tokens / args.steps, "seed": args.seed,
+        "config": {"workload": workload,
+                   "n_blocks": L, "tokens_per_step": tokens / steps, "seed": seed,
                    "grouping": "ISF, 10 iterations, Q' = Q - 128 tokens" if shape.kind == "llm"
                    else "ISF, 10 iterations, tile budget"},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / PEAK_BF16_TFLOPS, "peak_tflops": PEAK_BF16_TFLOPS,
         "tokens_per_s": tokens / elapsed,
-        "flops_per_step": flops / args.steps,
-        "ms_per_step_with_event_profiling": prof_elapsed * 1e3 / args.steps,
-        "packer": {"ms": packer_ms, "samples": int(len(tiles)), "groups": len(groups),
-                   "leftover": int(len(leftover)), "groups_per_iter": [int(a) for a in per_iter]},
+        "flops_per_step": flops / steps,
+        "ms_per_step_with_event_profiling": prof_elapsed * 1e3 / steps,
+        "packer": res["packer"],
         "roofline": roofline, "kernels": kernels, "spread": spread, "recompute": recompute,
         "cpu_baseline": cpu,
         "context": PAPER_CONTEXT,
     }
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--spread-batches", type=int, default=50)
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--also", type=int, nargs="*", default=[2, 4, 5], choices=[2, 3, 4, 5],
+                    help="configurations reported besides --config in the same JSON line ('configs' object: "
+                         "a few steps each; config 5 with its balanced-versus-random spread); "
+                         "'--also' alone: none")
+    ap.add_argument("--also-steps", type=int, default=3)
+    ap.add_argument("--report", choices=["packer", "bmp", "mixed"], default=None,
+                    help="instead of the step benchmark print one JSON line of a host-side report: "
+                         "'packer' = grouping arms, ISF convergence and Q' ablation on the synthetic "
+                         "dataset (no GPU needed); 'bmp' = model-partition search fed by measured "
+                         "per-block forward times; 'mixed' = a pipeline stage holding ViT blocks, the "
+                         "token sub-sampling + connector and LLM blocks, run on one mini-batch")
+    ap.add_argument("--calibrate-copy-mib", type=int, default=0,
+                    help="before the warm-up, copy this many MiB device-to-device three times: a "
+                         "kernel of known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    if args.report == "packer":
+        print(json.dumps(packer_report(args.seed)))
+        return
+    if args.report == "bmp":
+        print(json.dumps(bmp_report(args.seed)))
+        return
+    if args.report == "mixed":
+        print(json.dumps(mixed_report(args.seed)))
+        return
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    out = bench_config(args.config, args.steps, args.warmup, args.seed, args.spread_batches,
+                       full=True, cpu_baseline=not args.skip_cpu_baseline,
+                       calibrate_copy_mib=args.calibrate_copy_mib)
+    # the other configurations, a few steps each, on the same line (the headline stays the one above);
+    # config 5 also carries the balanced-versus-random spread over 50 + 50 mini-batches
+    others = {}
+    for cfg in args.also:
+        if cfg == args.config:
+            continue
+        others[str(cfg)] = bench_config(cfg, args.also_steps, 1, args.seed,
+                                        args.spread_batches if cfg == 5 else 0, full=False, cpu_baseline=False)
+    if others:
+        out["configs"] = others
     print(json.dumps(out))
 
 
