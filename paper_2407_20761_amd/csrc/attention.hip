@@ -39,8 +39,8 @@ namespace {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float NEG_BIG = -1.0e30f;
+constexpr float RESCALE_LOG2 = 8.0f;  // the forward's reference maximum may lag the row maximum by this much (base-2 log)
 constexpr int QT = 128;  // rows owned by a workgroup (4 waves x 32)
-constexpr int QT_DQ = 64;  // the dQ kernel: 2 pairs of waves x 32 rows, two workgroups per CU
 constexpr int ST = 64;   // rows of a streamed tile
 constexpr int WAIT_VM0 = 0x0F70;  // s_waitcnt vmcnt(0) only
 
@@ -281,19 +281,13 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[mt][r]);
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float c = m_new * sl2;
-    float psum = 0.f;
-#pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const float p = fast_exp2(acc_s[mt][r] * sl2 - c);
-            acc_s[mt][r] = p;
-            psum += p;
-        }
-    // the running maximum rarely moves after the first tiles: rescale only when some lane needs it
-    if (__any(m_new > m_run)) {
+    // The reference maximum m_run of a row only has to keep the exponentials in range, it need not be
+    // the true maximum: it follows the row maximum when that has outgrown it by more than 2^RESCALE_LOG2
+    // in some row of the wave (probabilities then reach at most 2^RESCALE_LOG2, harmless in fp32 sums
+    // and in bf16 operands), so the accumulators are rescaled a few times per row instead of at almost
+    // every tile (with random scores some row of 32 finds a new maximum in nearly every tile).
+    if (__any((mx - m_run) * sl2 > RESCALE_LOG2)) {
+        const float m_new = fmaxf(m_run, mx);
         const float alpha = fast_exp2((m_run - m_new) * sl2);
         l_run *= alpha;
 #pragma unroll
@@ -302,19 +296,48 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
             for (int r = 0; r < 16; ++r) acc_o[i][r] *= alpha;
         m_run = m_new;
     }
-    l_run += psum;
+    const float c = m_run * sl2;
+    float psum = 0.f;
+    // The exponentials of contraction step u + 1 (8 per lane, then their rounding to bf16) are issued
+    // between the MFMAs of step u, one MFMA to a few vector instructions: a wave's own element-wise
+    // work then runs in the shadow of its own matrix instructions.
+    auto probs = [&](int u) {
+        bf16x8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float p = fast_exp2(acc_s[u >> 1][8 * (u & 1) + e] * sl2 - c);
+            psum += p;
+            o[e] = (__bf16)p;
+        }
+        return o;
+    };
+    bf16x8 pb = probs(0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < ST / 16; ++u) {
+        bf16x8 pn = pb;
         if (u + 1 < ST / 16) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) fb[(u + 1) & 1][dt] = tl.frag_tr(vs, dt, u + 1);
+            pn = probs(u + 1);
         }
-        const bf16x8 pb = pack8(acc_s[u >> 1], 8 * (u & 1));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
             acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[u & 1][dt], pb, acc_o[dt], 0, 0, 0);
-        if (u + 1 < ST / 16) OB_SCHED_READS_THEN_MFMA(2 * DT, DT); else OB_SCHED_READS_THEN_MFMA(0, DT);
+        if (u + 1 < ST / 16) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * DT, 0);        // next step's V fragments
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, (28 + DT - 1) / DT, 0);   // its share of 28 vector instructions
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        } else {
+            OB_SCHED_READS_THEN_MFMA(0, DT);
+        }
+        pb = pn;
     }
+    l_run += psum;
 }
 
 template <int D, bool CAUSAL>
@@ -414,17 +437,17 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-// backward, part 1: dQ.  A workgroup owns 64 query rows of one head and streams the segment's
-// 64-row key/value tiles (up to the diagonal when causal); P is rebuilt from the saved
-// log-sum-exp.  Four wavefronts form two pairs, one pair per 32 query rows; the two waves of a
-// pair each take one 32-row half of every streamed tile through all three products
+// backward, part 1: dQ.  A workgroup owns 128 query rows of one head (four wavefronts, 32 rows
+// each) and streams the segment's 64-row key/value tiles (up to the diagonal when causal); P is
+// rebuilt from the saved log-sum-exp.  A wave takes the two 32-row halves of a streamed tile one
+// after the other through the three products
 //   S^T = K Q^T,  P = 2^(scale log2(e) S - lse2),  dP^T = V dO^T,  dS^T = P (dP^T - Delta),
 //   dQ^T += K^T dS^T
-// and keep their own dQ partial, which the pair adds once at the end through LDS.  Half the
-// per-wave state of a single-wave design, so two waves fit on a SIMD and hide each other's
-// element-wise work and LDS waits; two workgroups share a CU, and as nothing synchronises them
-// their MFMA and element-wise phases drift apart (one eight-wave workgroup, whose per-tile barrier
-// kept the two waves of every SIMD in step, was 10 % slower; without its barriers, 12 % faster).
+// so its state between the products is that of a 32 x 32 block (two such waves fit on a SIMD; two
+// workgroups share a CU and, as nothing synchronises them, their phases drift apart).  Every K / V
+// tile a workgroup copies serves 128 query rows: the first layout, two waves per 32 query rows each
+// on one half of the tile with their partial dQ added at the end, asked the L2 for twice the bytes
+// per MFMA (4.7 GB per launch on the 7B-shaped batch, 10 TB/s) and had a barrier per 24 MFMAs.
 // ------------------------------------------------------------------------------------------------
 template <int D, bool CAUSAL, bool MASK>
 __device__ __forceinline__ void dq_half(const unsigned char OB_LDS *__restrict__ ks,
@@ -432,7 +455,7 @@ __device__ __forceinline__ void dq_half(const unsigned char OB_LDS *__restrict__
                                         const bf16x8 (&qf)[D / 16], const bf16x8 (&dof)[D / 16],
                                         f32x16 (&acc_dq)[D / 32], float lse2, float dlt, int kv_first,
                                         int seg_end, int q_row, float sl2) {
-    // ks / vs point at this wave's 32-row half of the K / V tile; kv_first is its first key row
+    // ks / vs point at a 32-row half of the K / V tile; kv_first is its first key row
     const int lh = (threadIdx.x & 63) >> 5;
     constexpr int HB = 2;             // D-steps per batch (a batch reads HB fragments of K and HB of V)
     constexpr int NB = (D / 16) / HB;
@@ -466,28 +489,42 @@ __device__ __forceinline__ void dq_half(const unsigned char OB_LDS *__restrict__
         }
         if (b + 1 < NB) OB_SCHED_READS_THEN_MFMA(2 * HB, 2 * HB); else OB_SCHED_READS_THEN_MFMA(2 * DT, 2 * HB);
     }
+    // dS of contraction step h (8 values per lane, rounded to bf16); step 1's are worked out between the
+    // MFMAs of step 0, so the wave's own element-wise work runs in the shadow of its matrix instructions
+    auto dscores = [&](int h) {
+        bf16x8 o;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        bool ok = true;
-        if (MASK) {
-            const int kv = kv_first + 8 * (r >> 2) + 4 * lh + (r & 3);
-            ok = kv < seg_end && (!CAUSAL || kv <= q_row);
+        for (int e = 0; e < 8; ++e) {
+            const int r = 8 * h + e;
+            bool ok = true;
+            if (MASK) {
+                const int kv = kv_first + 8 * (r >> 2) + 4 * lh + (r & 3);
+                ok = kv < seg_end && (!CAUSAL || kv <= q_row);
+            }
+            const float p = ok ? fast_exp2(acc_s[r] * sl2 - lse2) : 0.f;
+            o[e] = (__bf16)(p * (acc_dp[r] - dlt));
         }
-        const float p = ok ? fast_exp2(acc_s[r] * sl2 - lse2) : 0.f;
-        acc_s[r] = p * (acc_dp[r] - dlt);
+        return o;
+    };
+    const bf16x8 ds0 = dscores(0);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) fb[1][dt] = tl.frag_tr(ks, dt, 1);
+    const bf16x8 ds1 = dscores(1);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+        acc_dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[0][dt], ds0, acc_dq[dt], 0, 0, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * DT, 0);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, (MASK ? 60 : 36) / DT, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        if (h == 0) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) fb[1][dt] = tl.frag_tr(ks, dt, 1);
-        }
-        const bf16x8 dsb = pack8(acc_s, 8 * h);
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-            acc_dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[h][dt], dsb, acc_dq[dt], 0, 0, 0);
-        if (h == 0) OB_SCHED_READS_THEN_MFMA(2 * DT, DT); else OB_SCHED_READS_THEN_MFMA(0, DT);
-    }
+    for (int dt = 0; dt < DT; ++dt)
+        acc_dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[1][dt], ds1, acc_dq[dt], 0, 0, 0);
+    OB_SCHED_READS_THEN_MFMA(0, DT);
 }
 
 template <int D, bool CAUSAL>
@@ -496,28 +533,29 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo, const int32_t *__restrict__ cu, int n_seg,
     int T, int group, float scale, int heads, TileOrder ord) {
-    // stages 0 / 1 of the K and V tiles; after the last tile the same bytes carry the dQ partials
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * Tile<D>::BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char k_s0[Tile<D>::BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_s0[Tile<D>::BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char k_s1[Tile<D>::BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char v_s1[Tile<D>::BYTES];
     __shared__ int sh[8];
     const int rank = blockIdx.x / heads;
-    const TileInfo ti = pick_tile(ord, rank, cu, n_seg, QT_DQ, sh);
+    const TileInfo ti = pick_tile(ord, rank, cu, n_seg, QT, sh);
     if (ti.row0 < 0) return;
     const int head = head_of_slot(blockIdx.x - rank * heads, heads), kvh = head / group;
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int pair = wave & 1, half = wave >> 1;
-    const int q_row = min(ti.row0 + pair * 32 + lx, ti.seg_end - 1);
-    const bool q_live = ti.row0 + pair * 32 + lx < ti.seg_end;
-    const int pair_q_last = min(ti.row0 + pair * 32 + 31, ti.seg_end - 1);
+    const int q_row = min(ti.row0 + wave * 32 + lx, ti.seg_end - 1);
+    const bool q_live = ti.row0 + wave * 32 + lx < ti.seg_end;
+    const int wave_q_last = min(ti.row0 + wave * 32 + 31, ti.seg_end - 1);
+    const bool wave_live = ti.row0 + wave * 32 < ti.seg_end;   // a wave past the segment's end only copies
     const float sl2 = scale * LOG2E;
-    constexpr int BYTES = Tile<D>::BYTES, DT = D / 32;
+    constexpr int DT = D / 32, HALF = 32 * Tile<D>::RB;
 
-    // waves 0-1 copy the K tiles, waves 2-3 the V tiles: two quarters of a tile each
-    Tile<D> tl, tl2;
-    tl.init(ldkv, pair, lane);
-    tl2.init(ldkv, pair + 2, lane);
-    const unsigned char *const own_base = (const unsigned char *)((half ? v : k) + kvh * D);
-    const long own_bytes = (long)T * ldkv * 2 - (long)kvh * D * 2;
+    Tile<D> tl;
+    tl.init(ldkv, wave, lane);
+    const unsigned char *kbase = (const unsigned char *)(k + kvh * D);
+    const unsigned char *vbase = (const unsigned char *)(v + kvh * D);
+    const long kv_bytes = (long)T * ldkv * 2 - (long)kvh * D * 2;
 
     bf16x8 qf[D / 16], dof[D / 16];
 #pragma unroll
@@ -533,68 +571,56 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc_dq[i][r] = 0.f;
 
-    const int kv_end = CAUSAL ? min(ti.seg_end, ti.row0 + QT_DQ) : ti.seg_end;
+    const int kv_end = CAUSAL ? min(ti.seg_end, ti.row0 + QT) : ti.seg_end;
     const int n_tiles = (kv_end - ti.seg_start + ST - 1) / ST;
-    unsigned char OB_LDS *const sm = (unsigned char OB_LDS *)smem;  // [stage][K | V][BYTES]
+    unsigned char OB_LDS *const ks0 = (unsigned char OB_LDS *)k_s0, *const ks1 = (unsigned char OB_LDS *)k_s1;
+    unsigned char OB_LDS *const vs0 = (unsigned char OB_LDS *)v_s0, *const vs1 = (unsigned char OB_LDS *)v_s1;
     {
         const long off = (long)ti.seg_start * ldkv * 2;
-        tl.issue(own_base + off, own_bytes - off, sm + half * BYTES, pair);
-        tl2.issue(own_base + off, own_bytes - off, sm + half * BYTES, pair + 2);
+        tl.issue(kbase + off, kv_bytes - off, ks0, wave);
+        tl.issue(vbase + off, kv_bytes - off, vs0, wave);
     }
     const int n_main = CAUSAL ? (ti.row0 - ti.seg_start) / ST : (ti.seg_end - ti.seg_start) / ST;
     int j = 0;
-#define OB_DQ_ITER(MASKED, STAGE)                                                                            \
-    {                                                                                                       \
-        const int kv0 = ti.seg_start + j * ST;                                                              \
-        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                               \
-        __syncthreads();                                                                                    \
-        if (j + 1 < n_tiles) {                                                                              \
-            const long off = (long)(kv0 + ST) * ldkv * 2;                                                   \
-            tl.issue(own_base + off, own_bytes - off, sm + (1 - (STAGE)) * 2 * BYTES + half * BYTES, pair); \
-            tl2.issue(own_base + off, own_bytes - off, sm + (1 - (STAGE)) * 2 * BYTES + half * BYTES, pair + 2); \
-        }                                                                                                   \
-        const unsigned char OB_LDS *const ks = sm + (STAGE) * 2 * BYTES + half * 32 * Tile<D>::RB;          \
-        const unsigned char OB_LDS *const vs = ks + BYTES;                                                  \
-        const int kv_first = kv0 + half * 32;                                                               \
-        if (!(MASKED))                                                                                      \
-            dq_half<D, CAUSAL, false>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv_first, ti.seg_end, q_row,   \
-                                      sl2);                                                                 \
-        else if (kv_first < ti.seg_end && !(CAUSAL && kv_first > pair_q_last))                              \
-            dq_half<D, CAUSAL, true>(ks, vs, tl, qf, dof, acc_dq, lse2, dlt, kv_first, ti.seg_end, q_row,    \
-                                     sl2);                                                                  \
-        ++j;                                                                                                \
+#define OB_DQ_ITER(MASKED, KS, VS, KS_NEXT, VS_NEXT)                                                          \
+    {                                                                                                        \
+        const int kv0 = ti.seg_start + j * ST;                                                               \
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);                                                                \
+        __syncthreads();                                                                                     \
+        if (j + 1 < n_tiles) {                                                                               \
+            const long off = (long)(kv0 + ST) * ldkv * 2;                                                    \
+            tl.issue(kbase + off, kv_bytes - off, (KS_NEXT), wave);                                          \
+            tl.issue(vbase + off, kv_bytes - off, (VS_NEXT), wave);                                          \
+        }                                                                                                    \
+        _Pragma("unroll") for (int hf = 0; hf < 2; ++hf) {                                                   \
+            const int kv_first = kv0 + 32 * hf;                                                              \
+            if (!(MASKED)) {                                                                                 \
+                if (wave_live)                                                                               \
+                    dq_half<D, CAUSAL, false>((KS) + hf * HALF, (VS) + hf * HALF, tl, qf, dof, acc_dq, lse2,  \
+                                              dlt, kv_first, ti.seg_end, q_row, sl2);                        \
+            } else if (wave_live && kv_first < ti.seg_end && !(CAUSAL && kv_first > wave_q_last))            \
+                dq_half<D, CAUSAL, true>((KS) + hf * HALF, (VS) + hf * HALF, tl, qf, dof, acc_dq, lse2, dlt,  \
+                                         kv_first, ti.seg_end, q_row, sl2);                                  \
+        }                                                                                                    \
+        ++j;                                                                                                 \
     }
-    while (j + 1 < n_main) {  // two tiles per trip: the stage is a compile-time constant
-        OB_DQ_ITER(false, 0)
-        OB_DQ_ITER(false, 1)
+    while (j + 1 < n_main) {  // two tiles per trip: the stage buffers are compile-time constants
+        OB_DQ_ITER(false, ks0, vs0, ks1, vs1)
+        OB_DQ_ITER(false, ks1, vs1, ks0, vs0)
     }
-    while (j < n_main) OB_DQ_ITER(false, j & 1)
-    while (j < n_tiles) OB_DQ_ITER(true, j & 1)
+#define OB_DQ_ANY(MASKED) OB_DQ_ITER(MASKED, (j & 1) ? ks1 : ks0, (j & 1) ? vs1 : vs0, (j & 1) ? ks0 : ks1, (j & 1) ? vs0 : vs1)
+    while (j < n_main) OB_DQ_ANY(false)
+    while (j < n_tiles) OB_DQ_ANY(true)
+#undef OB_DQ_ANY
 #undef OB_DQ_ITER
-    // the pair's second wave hands its partial over: [pair][register quad][lane] 16-byte slots
-    __syncthreads();  // every wave is done reading the tiles
-    f32x4 OB_LDS *const slot = (f32x4 OB_LDS *)sm + (size_t)pair * (DT * 4 * 64) + lane;
-    if (half) {
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                f32x4 t4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) t4[e] = acc_dq[dt][4 * g + e];
-                slot[(dt * 4 + g) * 64] = t4;
-            }
-    }
-    __syncthreads();
-    if (half || !q_live) return;
+    if (!q_live) return;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const f32x4 t4 = slot[(dt * 4 + g) * 64];
             bf16x4 ov;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) ov[e] = (__bf16)((acc_dq[dt][4 * g + e] + t4[e]) * scale);
+            for (int e = 0; e < 4; ++e) ov[e] = (__bf16)(acc_dq[dt][4 * g + e] * scale);
             *(bf16x4 *)(dq + (size_t)q_row * ldq + head * D + dt * 32 + g * 8 + lh * 4) = ov;
         }
 }
@@ -998,7 +1024,7 @@ void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float
     TileOrder ord;
     make_order(seg, QT, causal, false, tiles, ord);
     const dim3 grid((unsigned)tiles * nq);
-    OB_ATTN_DISPATCH(attn_fwd_kernel, grid, 256, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
+OB_ATTN_DISPATCH(attn_fwd_kernel, grid, 256, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
                      (__bf16 *)o, lse, ldq, ldkv, ldo, seg->cu_dev, seg->n_seg, seg->total_tokens,
                      nq / nkv, scale, nq, ord);
 }
@@ -1012,9 +1038,9 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     const int T = seg->total_tokens, group = nq / nkv;
     {
         ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
-        const int tiles_q = count_tiles(seg, QT_DQ);
+        const int tiles_q = tiles;
         TileOrder ord;
-        make_order(seg, QT_DQ, causal, false, tiles_q, ord);
+        make_order(seg, QT, causal, false, tiles_q, ord);
         const dim3 grid_q((unsigned)tiles_q * nq);
         OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 256, (const __bf16 *)d_o, (const __bf16 *)q,
                          (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
