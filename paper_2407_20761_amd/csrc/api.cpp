@@ -37,7 +37,7 @@ struct ProfState {
 };
 ProfState g_prof;
 const char *const kClassNames[K_COUNT] = {
-    "gemm", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "attn_delta", "norm_fwd",
+    "gemm", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "norm_fwd",
     "norm_bwd", "rotary", "act_fwd", "act_bwd", "colsum", "reduce_partials",
     "subsample_norm_fwd", "subsample_norm_bwd", "rows_copy"};
 }  // namespace
@@ -260,8 +260,7 @@ extern "C" int ob_varlen_attn_bwd(const void *d_o, const void *q, const void *k,
     }
     const size_t rows = align_up((size_t)seg->total_tokens * nq * 4, 256);
     float *delta = (float *)ws, *lse2 = (float *)((unsigned char *)ws + rows);
-    launch_attn_delta(d_o, o, ldo, lse, delta, lse2, seg->total_tokens, nq, d, s);
-    launch_attn_bwd(d_o, q, k, v, lse2, delta, dq, dk, dv, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, s);
+    launch_attn_bwd(d_o, q, k, v, o, lse, lse2, delta, dq, dk, dv, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, 0.f, s);
     return check_launch("ob_varlen_attn_bwd");
 }
 
@@ -415,13 +414,11 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
     if ((rc = gemm_any(1, m.T, m.HD, m.H, dx1, w->w_o, d_o, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // attention
     float *lse2 = (float *)at(ws, wk.lse2);
-    launch_attn_delta(d_o, o, m.HD, lse, delta, lse2, m.T, m.nq, m.d, s);
-    launch_attn_bwd(d_o, qkv, qkv + (size_t)m.nq * m.d * 2, qkv + (size_t)(m.nq + m.nkv) * m.d * 2, lse2, delta, dqkv,
-                    dqkv + (size_t)m.nq * m.d * 2, dqkv + (size_t)(m.nq + m.nkv) * m.d * 2,
-                    m.Dqkv, m.Dqkv, m.HD, seg,
-                    m.nq, m.nkv, m.d, scale, desc->mask, s);
-    if (desc->use_rotary)
-        launch_rotary(dqkv, m.Dqkv, m.T, m.nq + m.nkv, m.d, seg->cu_dev, seg->n_seg, desc->rotary_base, -1.0f, s);
+    // (the rotary backward of dq and dk happens in the attention kernels' epilogues)
+    launch_attn_bwd(d_o, qkv, qkv + (size_t)m.nq * m.d * 2, qkv + (size_t)(m.nq + m.nkv) * m.d * 2, o, lse, lse2, delta,
+                    dqkv, dqkv + (size_t)m.nq * m.d * 2, dqkv + (size_t)(m.nq + m.nkv) * m.d * 2,
+                    m.Dqkv, m.Dqkv, m.HD, seg, m.nq, m.nkv, m.d, scale, desc->mask,
+                    desc->use_rotary ? desc->rotary_base : 0.f, s);
     // qkv = h1 W_qkv^T + b_qkv
     if ((rc = gemm_any(2, m.Dqkv, m.H, m.T, dqkv, h1, g->w_qkv, nullptr, acc ? g->w_qkv : nullptr, gws, wk.gemm_bytes, s))) return rc;
     if (bias) bias_grad(dqkv, m.Dqkv, wk.p_qkv, g->b_qkv);

@@ -127,6 +127,31 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int base) {
     return o;
 }
 
+// Rotary backward folded into the epilogues of the backward kernels.  A lane holds, of one token's head
+// row, accumulator (dt, r) = column 32 dt + 8 (r / 4) + 4 lh + r % 4: the rotary pair (i, i + D/2) is
+// (dt, r) and (dt + D/64, r) of the same lane.  The gradient is rotated by minus the token's angle
+// pos * base^(-2 i / D), pos = distance to the segment's first token (log2_base <= 0: no rotary).
+// Sine and cosine come from the hardware's functions of the angle in revolutions, reduced to [0, 1)
+// first: an absolute error of a few 1e-4 rad at positions in the thousands, an order of magnitude
+// below the bf16 rounding of the result.
+template <int D>
+__device__ __forceinline__ void rotary_bwd_row(f32x16 (&acc)[D / 32], int pos, float log2_base, int lh) {
+    constexpr int H = D / 64;   // accumulator tiles per half of the head dimension
+#pragma unroll
+    for (int dt = 0; dt < H; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int i = 32 * dt + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const float theta = __builtin_amdgcn_exp2f(-2.0f * (float)i / (float)D * log2_base);
+            float rev = (float)pos * theta * 0.15915494309189535f;
+            rev -= floorf(rev);
+            const float sn = __builtin_amdgcn_sinf(rev), cs = __builtin_amdgcn_cosf(rev);
+            const float x1 = acc[dt][r], x2 = acc[dt + H][r];
+            acc[dt][r] = x1 * cs + x2 * sn;
+            acc[dt + H][r] = x2 * cs - x1 * sn;
+        }
+}
+
 // Which workgroup does which tile.  The launch is one-dimensional: workgroup b works on tile
 // b / heads for head slot b % heads, so all heads of a tile are dispatched together, and (workgroups
 // being dealt round-robin to the 8 XCDs) head slot hs runs on XCD hs % 8: with a head count that is a
@@ -530,9 +555,10 @@ __device__ __forceinline__ void dq_half(const unsigned char OB_LDS *__restrict__
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
-    const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
-    __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo, const int32_t *__restrict__ cu, int n_seg,
-    int T, int group, float scale, int heads, TileOrder ord) {
+    const __bf16 *__restrict__ v, const __bf16 *__restrict__ o, const float *__restrict__ lse,
+    float *__restrict__ lse2_all, float *__restrict__ delta, __bf16 *__restrict__ dq, int ldq, int ldkv, int ldo,
+    const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale, float rot_log2_base, int heads,
+    TileOrder ord) {
     __shared__ __attribute__((aligned(1024))) unsigned char k_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char v_s0[Tile<D>::BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char k_s1[Tile<D>::BYTES];
@@ -563,8 +589,22 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         qf[t] = *(const bf16x8 *)(q + (size_t)q_row * ldq + head * D + 16 * t + 8 * lh);
         dof[t] = *(const bf16x8 *)(d_o + (size_t)q_row * ldo + head * D + 16 * t + 8 * lh);
     }
-    const float lse2 = lse2_all[(size_t)head * T + q_row];
-    const float dlt = delta[(size_t)head * T + q_row];
+    // The row statistics of the backward: Delta = sum_d dO O and the log-sum-exp in base-2 units.  The
+    // wave holds its rows of dO already; each lane adds its half of the row, the other half sits 32
+    // lanes away.  Both are also written out: the dK / dV kernel, launched behind this one, reads them.
+    const float lse2 = lse[(size_t)head * T + q_row] * LOG2E;
+    float dlt = 0.f;
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) {
+        const bf16x8 of = *(const bf16x8 *)(o + (size_t)q_row * ldo + head * D + 16 * t + 8 * lh);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dlt += (float)dof[t][e] * (float)of[e];
+    }
+    dlt += __shfl_xor(dlt, 32);
+    if (q_live && lh == 0) {
+        lse2_all[(size_t)head * T + q_row] = lse2;
+        delta[(size_t)head * T + q_row] = dlt;
+    }
     f32x16 acc_dq[DT];
 #pragma unroll
     for (int i = 0; i < DT; ++i)
@@ -614,6 +654,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 #undef OB_DQ_ANY
 #undef OB_DQ_ITER
     if (!q_live) return;
+    if (rot_log2_base > 0.f) rotary_bwd_row<D>(acc_dq, q_row - ti.seg_start, rot_log2_base, lh);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -751,7 +792,8 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int ldq, int ldkv, int ldo,
-    const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale, int heads, TileOrder ord) {
+    const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale, float rot_log2_base, int heads,
+    TileOrder ord) {
     // three stages of the streamed Q and dO tiles (the dK side works one tile behind the dV side, see
     // below), two buffers for the probabilities on their way from one to the other, row statistics
     __shared__ __attribute__((aligned(1024))) unsigned char tiles_s[6 * Tile<D>::BYTES];
@@ -925,6 +967,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     // dV^T / dK^T of the whole group of query heads sit in the accumulators: one rounding to bf16
     const float out_scale = role_g ? scale : 1.0f;
     __bf16 *const dst = role_g ? dk : dv;
+    if (role_g && rot_log2_base > 0.f) rotary_bwd_row<D>(acc_out, kv_row - ti.seg_start, rot_log2_base, lh);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -988,13 +1031,14 @@ void make_order(const ob_segments *seg, int tile_rows, bool causal, bool kv_side
                                                    float *, int, int, int, const int32_t *, int, int, int,    \
                                                    float, int, TileOrder);                                    \
     template __global__ void attn_bwd_dq_kernel<D, C>(const __bf16 *, const __bf16 *, const __bf16 *,         \
-                                                      const __bf16 *, const float *, const float *, __bf16 *, \
-                                                      int, int, int, const int32_t *, int, int, int, float,   \
-                                                      int, TileOrder);                                        \
+                                                      const __bf16 *, const __bf16 *, const float *, float *, \
+                                                      float *, __bf16 *, int, int, int, const int32_t *, int, \
+                                                      int, int, float, float, int, TileOrder);                \
     template __global__ void attn_bwd_dkv_kernel<D, C>(const __bf16 *, const __bf16 *, const __bf16 *,        \
                                                        const __bf16 *, const float *, const float *,          \
                                                        __bf16 *, __bf16 *, int, int, int,                     \
-                                                       const int32_t *, int, int, int, float, int, TileOrder);
+                                                       const int32_t *, int, int, int, float, float, int,     \
+                                                       TileOrder);
 OB_ATTN_INSTANCES(64, true)
 OB_ATTN_INSTANCES(64, false)
 OB_ATTN_INSTANCES(128, true)
@@ -1029,22 +1073,23 @@ OB_ATTN_DISPATCH(attn_fwd_kernel, grid, 256, (const __bf16 *)q, (const __bf16 *)
                      nq / nkv, scale, nq, ord);
 }
 
-void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse2,
-                     const float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv,
-                     int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
+void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const void *o, const float *lse,
+                     float *lse2, float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
+                     const ob_segments *seg, int nq, int nkv, int d, float scale, int mask, float rotary_base,
                      hipStream_t s) {
     const bool causal = mask == OB_MASK_SEG_CAUSAL;
     const int tiles = count_tiles(seg, QT);
     const int T = seg->total_tokens, group = nq / nkv;
+    const float rot = rotary_base > 1.f ? log2f(rotary_base) : 0.f;
     {
-        ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));  // dQ = dS K: 1 of the 4 bwd products
-        const int tiles_q = tiles;
+        // dQ = dS K: 1 of the 4 backward products; the kernel also forms Delta and the base-2 log-sum-exp
+        ProfScope prof(K_ATTN_BWD_DQ, s, 0.5 * attn_flops(seg, nq, d, causal));
         TileOrder ord;
-        make_order(seg, QT, causal, false, tiles_q, ord);
-        const dim3 grid_q((unsigned)tiles_q * nq);
+        make_order(seg, QT, causal, false, tiles, ord);
+        const dim3 grid_q((unsigned)tiles * nq);
         OB_ATTN_DISPATCH(attn_bwd_dq_kernel, grid_q, 256, (const __bf16 *)d_o, (const __bf16 *)q,
-                         (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dq, ldq, ldkv, ldo,
-                         seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale, nq, ord);
+                         (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)o, lse, lse2, delta, (__bf16 *)dq, ldq,
+                         ldkv, ldo, seg->cu_dev, seg->n_seg, seg->total_tokens, nq / nkv, scale, rot, nq, ord);
     }
     ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
     TileOrder ord;
@@ -1052,7 +1097,7 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     const dim3 grid_kv((unsigned)tiles * nkv);
     OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_kv, 512, (const __bf16 *)d_o, (const __bf16 *)q,
                      (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dk, (__bf16 *)dv, ldq, ldkv,
-                     ldo, seg->cu_dev, seg->n_seg, T, group, scale, nkv, ord);
+                     ldo, seg->cu_dev, seg->n_seg, T, group, scale, rot, nkv, ord);
 }
 
 }  // namespace ob

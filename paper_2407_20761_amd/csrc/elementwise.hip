@@ -1,5 +1,5 @@
 // HBM-bound row-wise and elementwise kernels of the block (steps a1, a3, a6, a8 and their
-// backward counterparts b1, b3, b6, b8, bias-gradient column sums, the attention Delta pre-pass).
+// backward counterparts b1, b3, b6, b8, bias-gradient column sums).
 // bf16 in / out, fp32 arithmetic, 16-byte loads and stores; one workgroup per token row for the
 // row-wise ones so every byte is read once and written once.
 #include "ob_internal.h"
@@ -544,38 +544,6 @@ __global__ __launch_bounds__(256) void act_bwd_kernel(const __bf16 *__restrict__
     }
 }
 
-// delta[head][t] = sum_d dO[t, head, d] * O[t, head, d]; 8 lanes (d = 64) or 16 lanes (d = 128)
-// share one (t, head) row.  The same pass rewrites the row's log-sum-exp in base-2 units
-// (lse2 = lse * log2 e), the form the backward kernels feed to the hardware's 2^x.
-__global__ __launch_bounds__(256) void attn_delta_kernel(const __bf16 *__restrict__ d_o,
-                                                         const __bf16 *__restrict__ o, int ldo,
-                                                         const float *__restrict__ lse,
-                                                         float *__restrict__ delta,
-                                                         float *__restrict__ lse2, int T, int nq,
-                                                         int d) {
-    const int lanes = d / 8;
-    const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-    const long pair = gid / lanes;
-    const int part = (int)(gid % lanes);
-    const bool live = pair < (long)T * nq;
-    float s = 0.f;
-    long t = 0;
-    int head = 0;
-    if (live) {
-        t = pair / nq;
-        head = (int)(pair % nq);
-        const size_t off = (size_t)t * ldo + head * d + part * 8;
-        const bf16x8 a = *(const bf16x8 *)(d_o + off), b = *(const bf16x8 *)(o + off);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) s += (float)a[e] * (float)b[e];
-    }
-    for (int off = lanes >> 1; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-    if (live && part == 0) {
-        delta[(size_t)head * T + t] = s;
-        lse2[(size_t)head * T + t] = lse[(size_t)head * T + t] * 1.4426950408889634f;
-    }
-}
-
 __global__ __launch_bounds__(256) void mask_kernel(const int32_t *__restrict__ cu, int n_seg, int T,
                                                    int causal, uint8_t *__restrict__ out) {
     const int i = blockIdx.x;
@@ -709,14 +677,6 @@ void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T,
     else
         hipLaunchKernelGGL(act_bwd_kernel<false>, dim3(blocks), dim3(256), 0, s, (const __bf16 *)dact,
                            (const __bf16 *)up, (__bf16 *)dup, n_vec, F);
-}
-
-void launch_attn_delta(const void *d_o, const void *o, int ldo, const float *lse, float *delta,
-                       float *lse2, int T, int nq, int d, hipStream_t s) {
-    ProfScope prof(K_ATTN_DELTA, s, 4.0 * T * nq * d + 12.0 * T * nq);
-    const long threads = (long)T * nq * (d / 8);
-    hipLaunchKernelGGL(attn_delta_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
-                       (const __bf16 *)d_o, (const __bf16 *)o, ldo, lse, delta, lse2, T, nq, d);
 }
 
 void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out, hipStream_t s) {

@@ -59,10 +59,9 @@ extern "C" int ob_varlen_attn_bwd_static(const void *d_o, const void *q, const v
         f32::attn_bwd(d_o, q, k, v, o, lse, dq, dk, dv, (float *)base, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, s);
         return check_launch("ob_varlen_attn_bwd_static");
     }
-    // both halves are written in full by the Delta pass before the backward kernels read them:
-    // nothing of an earlier call's contents is ever read
+    // both halves are written (by the dQ kernel, for every row of every head) before the dK / dV kernel
+    // reads them: nothing of an earlier call's contents is ever read
     float *delta = (float *)base, *lse2 = (float *)((unsigned char *)base + rows);
-    launch_attn_delta(d_o, o, ldo, lse, delta, lse2, seg->total_tokens, nq, d, s);
-    launch_attn_bwd(d_o, q, k, v, lse2, delta, dq, dk, dv, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, s);
+    launch_attn_bwd(d_o, q, k, v, o, lse, lse2, delta, dq, dk, dv, ldq, ldkv, ldo, seg, nq, nkv, d, scale, mask, 0.f, s);
     return check_launch("ob_varlen_attn_bwd_static");
 }

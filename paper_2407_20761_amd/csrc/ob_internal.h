@@ -20,7 +20,7 @@ int validate_attn(const ob_segments *seg, int nq, int nkv, int d, int ldq, int l
 
 // ---- opt-in per-kernel-class timing (ob_prof_begin / ob_prof_end) --------------------------
 enum KClass {
-    K_GEMM = 0, K_ATTN_FWD, K_ATTN_BWD_DQ, K_ATTN_BWD_DKV, K_ATTN_DELTA, K_NORM_FWD,
+    K_GEMM = 0, K_ATTN_FWD, K_ATTN_BWD_DQ, K_ATTN_BWD_DKV, K_NORM_FWD,
     K_NORM_BWD, K_ROTARY, K_ACT_FWD, K_ACT_BWD, K_COLSUM, K_REDUCE, K_CONN_FWD, K_CONN_BWD, K_ROWS, K_COUNT
 };
 // Brackets one kernel launch with a pair of events on its stream while profiling is on;
@@ -75,9 +75,6 @@ void launch_rotary(void *qkv, int ld, int T, int n_heads_rot, int d, const int32
 void launch_act_fwd(int mlp, const void *up, void *act, int T, int F, hipStream_t s);
 void launch_act_bwd(int mlp, const void *dact, const void *up, void *dup, int T, int F,
                     hipStream_t s);
-// delta and lse2 (= lse * log2 e): [nq][T] floats each
-void launch_attn_delta(const void *d_o, const void *o, int ldo, const float *lse, float *delta,
-                       float *lse2, int T, int nq, int d, hipStream_t s);
 void launch_mask(const int32_t *cu_dev, int n_seg, int T, int mask, uint8_t *out, hipStream_t s);
 
 // ---- ViT -> LLM hand-over (connector.hip) ------------------------------------------------------
@@ -100,9 +97,12 @@ void launch_rows_gather(void *small, const void *big, const int32_t *rows_dev, i
 void launch_attn_fwd(const void *q, const void *k, const void *v, void *o, float *lse, int ldq,
                      int ldkv, int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale,
                      int mask, hipStream_t s);
-void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const float *lse2,
-                     const float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv,
-                     int ldo, const ob_segments *seg, int nq, int nkv, int d, float scale, int mask,
+// o, lse (natural log): the forward's results; lse2, delta: [nq][T] floats of scratch each, written by the
+// dQ kernel (base-2 log-sum-exp, Delta = sum_d dO O) and read by the dK / dV kernel behind it.
+// rotary_base > 1: dq and dk leave the kernels already rotated back by the tokens' rotary angles.
+void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *v, const void *o, const float *lse,
+                     float *lse2, float *delta, void *dq, void *dk, void *dv, int ldq, int ldkv, int ldo,
+                     const ob_segments *seg, int nq, int nkv, int d, float scale, int mask, float rotary_base,
                      hipStream_t s);
 
 // ---- fp32 debug path (debug_fp32.hip): every tensor fp32, plain FMA kernels --------------------

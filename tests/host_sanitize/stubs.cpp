@@ -30,7 +30,6 @@ void launch_colsum(const void *, int, int, int, float *, hipStream_t) { OB_STUB(
 void launch_rotary(void *, int, int, int, int, const int32_t *, int, float, float, hipStream_t) { OB_STUB("launch_rotary"); }
 void launch_act_fwd(int, const void *, void *, int, int, hipStream_t) { OB_STUB("launch_act_fwd"); }
 void launch_act_bwd(int, const void *, const void *, void *, int, int, hipStream_t) { OB_STUB("launch_act_bwd"); }
-void launch_attn_delta(const void *, const void *, int, const float *, float *, float *, int, int, int, hipStream_t) { OB_STUB("launch_attn_delta"); }
 void launch_mask(const int32_t *, int, int, int, uint8_t *, hipStream_t) { OB_STUB("launch_mask"); }
 int subsample_max_width() { return 16384; }
 void launch_subsample_norm_fwd(const void *, const void *, const void *, void *, float *, int, int, int, float, hipStream_t) { OB_STUB("launch_subsample_norm_fwd"); }
@@ -41,8 +40,9 @@ void launch_rows_scatter(const void *, void *, const int32_t *, int, int, hipStr
 void launch_rows_gather(void *, const void *, const int32_t *, int, int, hipStream_t) { OB_STUB("launch_rows_gather"); }
 void launch_attn_fwd(const void *, const void *, const void *, void *, float *, int, int, int, const ob_segments *, int,
                      int, int, float, int, hipStream_t) { OB_STUB("launch_attn_fwd"); }
-void launch_attn_bwd(const void *, const void *, const void *, const void *, const float *, const float *, void *,
-                     void *, void *, int, int, int, const ob_segments *, int, int, int, float, int, hipStream_t) { OB_STUB("launch_attn_bwd"); }
+void launch_attn_bwd(const void *, const void *, const void *, const void *, const void *, const float *, float *,
+                     float *, void *, void *, void *, int, int, int, const ob_segments *, int, int, int, float, int,
+                     float, hipStream_t) { OB_STUB("launch_attn_bwd"); }
 
 namespace f32 {
 SavedF32 saved_layout(const ob_block_desc *d, int T) {
