@@ -288,6 +288,62 @@ def mixed_report(seed, n_vit=4, n_llm=4, steps=3):
             "activation_mb_after_connector": info[-1]["tiles"] * si.LLM_TOKENS_PER_TILE * ts.hidden * 2 / 1e6}
 
 
+def gemm_report(config, seed, iters=20):
+    """The twelve GEMMs of one block of `config` (forward, data gradient, weight gradient of the four
+    linears), each timed alone in a loop of `iters` launches, once on N(0, 1) operands and once on
+    zeros: the same instruction stream, different switching activity in the matrix pipes.  On this
+    chip the two differ by a quarter (the sustained rate on real data is set by the power limit, not by
+    the kernel's cycle count); with `rocprofv3 --pmc GRBM_GUI_ACTIVE SQ_VALU_MFMA_BUSY_CYCLES` around
+    this report the clock each variant ran at and the busy share of the matrix pipe can be read off."""
+    import torch
+    import paper_2407_20761_amd as ob
+    import synth_inputs as si
+    shape = si.CONFIGS[config]
+    tiles, tok = si.synthetic_dataset(20000, seed)
+    if shape.kind == "llm":
+        groups, _, _ = ob.ob_pack_isf(tiles, tok, 10 ** 9, shape.budget, 10 ** 9, shape.budget - 128, 10, seed)
+        T = int(np.mean([int(tok[g].sum()) for g in groups[:50]]))
+    else:
+        T = shape.budget * si.VIT_TILE_TOKENS
+    H, Dq, HD, upF, F = shape.hidden, shape.d_qkv, shape.n_q_heads * shape.head_dim, shape.up_rows, shape.mlp_dim
+    gemms = [("qkv fwd", 0, T, Dq, H), ("out fwd", 0, T, H, HD), ("up fwd", 0, T, upF, H), ("down fwd", 0, T, H, F),
+             ("d act", 1, T, F, H), ("d h2", 1, T, H, upF), ("d o", 1, T, HD, H), ("d h1", 1, T, H, Dq),
+             ("dW down", 2, H, F, T), ("dW up", 2, upF, H, T), ("dW out", 2, H, HD, T), ("dW qkv", 2, Dq, H, T)]
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    rows, totals = [], {}
+    for data in ("normal", "zeros"):
+        t_sum = f_sum = 0.0
+        for name, layout, M, N, K in gemms:
+            def mk(*shp):
+                if data == "zeros":
+                    return torch.zeros(shp, device="cuda", dtype=torch.bfloat16)
+                return torch.randn(shp, generator=gen, device="cuda").to(torch.bfloat16)
+            A = mk(K, M) if layout == 2 else mk(M, K)
+            B = mk(N, K) if layout == 0 else mk(K, N)
+            C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+            ws = torch.empty(max(ob.ob_gemm_workspace_bytes(layout, M, N, K), 256), dtype=torch.uint8, device="cuda")
+            for _ in range(5):
+                ob.ob_gemm_bf16(layout, M, N, K, A, B, C, None, None, ws)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                ob.ob_gemm_bf16(layout, M, N, K, A, B, C, None, None, ws)
+            e1.record()
+            e1.synchronize()
+            us = e0.elapsed_time(e1) / iters * 1e3
+            fl = 2.0 * M * N * K
+            rows.append({"gemm": name, "layout": ("NT", "NN", "TN")[layout], "M": M, "N": N, "K": K, "data": data,
+                         "us": us, "tflops": fl / us / 1e6})
+            t_sum += us
+            f_sum += fl
+            del A, B, C, ws
+        totals[data] = {"us_per_block": t_sum, "tflops": f_sum / t_sum / 1e6,
+                        "pct_of_bf16_mfma_peak": 100.0 * f_sum / t_sum / 1e6 / PEAK_BF16_TFLOPS}
+    return {"report": "gemm", "config": config, "tokens": T, "iters": iters, "gemms": rows, "totals": totals,
+            "zeros_over_normal": totals["zeros"]["tflops"] / totals["normal"]["tflops"]}
+
+
 def git_describe(path):
     """Commit and date of the last change to `path` (for figures read from committed summaries)."""
     import subprocess
@@ -633,12 +689,13 @@ def main():
                          "a few steps each; config 5 with its balanced-versus-random spread); "
                          "'--also' alone: none")
     ap.add_argument("--also-steps", type=int, default=3)
-    ap.add_argument("--report", choices=["packer", "bmp", "mixed"], default=None,
+    ap.add_argument("--report", choices=["packer", "bmp", "mixed", "gemm"], default=None,
                     help="instead of the step benchmark print one JSON line of a host-side report: "
                          "'packer' = grouping arms, ISF convergence and Q' ablation on the synthetic "
                          "dataset (no GPU needed); 'bmp' = model-partition search fed by measured "
                          "per-block forward times; 'mixed' = a pipeline stage holding ViT blocks, the "
-                         "token sub-sampling + connector and LLM blocks, run on one mini-batch")
+                         "token sub-sampling + connector and LLM blocks, run on one mini-batch; 'gemm' = the "
+                         "twelve GEMMs of one block of --config, each alone, on N(0,1) operands and on zeros")
     ap.add_argument("--calibrate-copy-mib", type=int, default=0,
                     help="before the warm-up, copy this many MiB device-to-device three times: a "
                          "kernel of known traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE")
@@ -656,6 +713,9 @@ def main():
         return
     if args.report == "mixed":
         print(json.dumps(mixed_report(args.seed)))
+        return
+    if args.report == "gemm":
+        print(json.dumps(gemm_report(args.config, args.seed)))
         return
 
     import torch
