@@ -156,7 +156,8 @@ Work work_layout(const Dims &m) {
     // fp32 partial sums of the column reductions, one region each: they are all summed by one
     // launch at the end of the backward pass
     const size_t ncs = colsum_partials(m.T), nnb = norm_bwd_partials(m.T);
-    w.p_down = L.take(ncs * m.H * 4); w.p_up = L.take(ncs * m.upF * 4); w.p_o = L.take(ncs * m.H * 4);
+    // (b_down and b_o: column sums of dy and dx1, left by the second norm's backward next to its own partials)
+    w.p_down = L.take(nnb * 2 * m.H * 4); w.p_up = L.take(ncs * m.upF * 4); w.p_o = 0;
     w.p_qkv = L.take(ncs * m.Dqkv * 4); w.p_n2 = L.take(nnb * 2 * m.H * 4); w.p_n1 = L.take(nnb * 2 * m.H * 4);
     size_t g = 0;
     auto upd = [&](int layout, int M, int N, int K) { const size_t b = gemm_workspace_bytes(layout, M, N, K); if (b > g) g = b; };
@@ -400,17 +401,21 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
     // y = x1 + act W_down^T + b_down
     if ((rc = gemm_any(1, m.T, m.F, m.H, dy, w->w_down, dact, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     if ((rc = gemm_any(2, m.H, m.F, m.T, dy, act, g->w_down, nullptr, acc ? g->w_down : nullptr, gws, wk.gemm_bytes, s))) return rc;
-    if (bias) bias_grad(dy, m.H, wk.p_down, g->b_down);
     launch_act_bwd(desc->mlp, dact, up, dup, m.T, m.F, s);
     if ((rc = gemm_any(2, m.upF, m.H, m.T, dup, h2, g->w_up, nullptr, acc ? g->w_up : nullptr, gws, wk.gemm_bytes, s))) return rc;
     if (bias) bias_grad(dup, m.upF, wk.p_up, g->b_up);
     if ((rc = gemm_any(1, m.T, m.H, m.upF, dup, w->w_up, dh, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // dx1 = dy + norm2_bwd(dh2)
-    launch_norm_bwd(desc->norm, dh, x1, (const float *)at(saved, sv.stat2), w->n2_g, dy, dx1, (float *)at(ws, wk.p_n2), m.T, m.H, s);
+    // (with biases the same pass leaves the column sums of dy and of dx1: the gradients of b_down and b_o)
+    float *csum = bias ? (float *)at(ws, wk.p_down) : nullptr;
+    launch_norm_bwd(desc->norm, dh, x1, (const float *)at(saved, sv.stat2), w->n2_g, dy, dx1, (float *)at(ws, wk.p_n2), m.T, m.H, s, csum);
     norm_grads(wk.p_n2, g->n2_g, g->n2_b);
+    if (bias) {
+        sums.add(csum, nnb, 2 * m.H, g->b_down, m.H);
+        sums.add(csum + m.H, nnb, 2 * m.H, g->b_o, m.H);
+    }
     // x1 = x + o W_o^T + b_o
     if ((rc = gemm_any(2, m.H, m.HD, m.T, dx1, o, g->w_o, nullptr, acc ? g->w_o : nullptr, gws, wk.gemm_bytes, s))) return rc;
-    if (bias) bias_grad(dx1, m.H, wk.p_o, g->b_o);
     if ((rc = gemm_any(1, m.T, m.HD, m.H, dx1, w->w_o, d_o, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // attention
     float *lse2 = (float *)at(ws, wk.lse2);

@@ -172,14 +172,22 @@ __global__ __launch_bounds__(256) void norm_fwd_wave_kernel(
 // dxhat = dh * gamma.  Each workgroup walks rows blockIdx.x, +gridDim.x, ... and keeps its
 // column sums of dh * xhat (dgamma) and dh (dbeta) in registers; they are written once to
 // partial[blockIdx.x][2][H] and summed by reduce_partials_kernel.
-template <bool LAYERNORM>
+// CSUM: the kernel also leaves the column sums of dres and of its output dx (as stored, after rounding) in
+// csum[blockIdx.x][2][H]: the bias gradients of the two linears around the norm, which would otherwise
+// each take a pass of their own over a [T, H] tensor the kernel has in registers anyway.
+template <bool LAYERNORM, bool CSUM>
 __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
     const __bf16 *__restrict__ dh, const __bf16 *__restrict__ x, const float *__restrict__ stats,
     const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ dres, __bf16 *__restrict__ dx,
-    float *__restrict__ partial, int T, int H) {
+    float *__restrict__ partial, float *__restrict__ csum, int T, int H) {
     __shared__ float red[NORM_THREADS / 64];
     const int nvec = H / 8;
     float g[MAX_VEC][8], dg[MAX_VEC][8], db[MAX_VEC][8];
+    float sr[CSUM ? MAX_VEC : 1][8], sx[CSUM ? MAX_VEC : 1][8];
+#pragma unroll
+    for (int i = 0; i < (CSUM ? MAX_VEC : 1); ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sr[i][e] = sx[i][e] = 0.f;
 #pragma unroll
     for (int i = 0; i < MAX_VEC; ++i) {
         const int c = threadIdx.x + i * NORM_THREADS;
@@ -243,6 +251,13 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
                 for (int e = 0; e < 8; ++e)
                     o[e] = (__bf16)((float)tr[i][e] + rstd * (dxh[i][e] - s1 - xh[i][e] * s2));
                 *(bf16x8 *)(dx + (size_t)row * H + c * 8) = o;
+                if (CSUM) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        sr[i][e] += (float)tr[i][e];
+                        sx[i][e] += (float)o[e];
+                    }
+                }
             }
         }
     }
@@ -256,6 +271,14 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
                 pg[c * 8 + e] = dg[i][e];
                 pb[c * 8 + e] = db[i][e];
             }
+            if (CSUM) {
+                float *cr = csum + (size_t)blockIdx.x * 2 * H, *cx = cr + H;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    cr[c * 8 + e] = sr[i][e];
+                    cx[c * 8 + e] = sx[i][e];
+                }
+            }
         }
     }
 }
@@ -264,15 +287,20 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
 // row sums are wave reductions, and the next row's loads are in flight while the current row is
 // worked on (one wave per SIMD, 24 KB per wave in flight at H = 4096).  Every wave keeps its own
 // column sums and writes its own partial: partial[(blockIdx.x * 4 + wave)][2][H].
-template <bool LAYERNORM, int NV>
+template <bool LAYERNORM, int NV, bool CSUM>
 __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
     const __bf16 *__restrict__ dh, const __bf16 *__restrict__ x, const float *__restrict__ stats,
     const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ dres, __bf16 *__restrict__ dx,
-    float *__restrict__ partial, int T, int H) {
+    float *__restrict__ partial, float *__restrict__ csum, int T, int H) {
     const int nvec = H / 8, lane = threadIdx.x & 63;
     const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), n_slots = gridDim.x * 4;
     bf16x8 g[NV];
     float dg[NV][8], db[NV][8];
+    float sr[CSUM ? NV : 1][8], sx[CSUM ? NV : 1][8];   // column sums of dres and of dx (see norm_bwd_kernel)
+#pragma unroll
+    for (int i = 0; i < (CSUM ? NV : 1); ++i)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sr[i][e] = sx[i][e] = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int c = lane + 64 * i;
@@ -332,6 +360,13 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
                     o[e] = (__bf16)((float)cr[i][e] + rstd * (dxh - s1 - xh * s2));
                 }
                 *(bf16x8 *)(dx + (size_t)row * H + c * 8) = o;
+                if (CSUM) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        sr[i][e] += (float)cr[i][e];
+                        sx[i][e] += (float)o[e];
+                    }
+                }
             }
         }
     }
@@ -344,6 +379,14 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
             for (int e = 0; e < 8; ++e) {
                 pg[c * 8 + e] = dg[i][e];
                 pb[c * 8 + e] = db[i][e];
+            }
+            if (CSUM) {
+                float *pr = csum + (size_t)slot * 2 * H, *px = pr + H;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    pr[c * 8 + e] = sr[i][e];
+                    px[c * 8 + e] = sx[i][e];
+                }
             }
         }
     }
@@ -587,36 +630,36 @@ int norm_bwd_partials(int T) { return T < 1024 ? T : 1024; }
 
 template <int NV>
 static void launch_norm_bwd_wave(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
-                                 const void *dres, void *dx, float *partial, int T, int H, int nb, hipStream_t s) {
-    if (norm == OB_LAYERNORM)
-        hipLaunchKernelGGL((norm_bwd_wave_kernel<true, NV>), dim3(nb / 4), dim3(256), 0, s, (const __bf16 *)dh,
-                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
-                           (__bf16 *)dx, partial, T, H);
-    else
-        hipLaunchKernelGGL((norm_bwd_wave_kernel<false, NV>), dim3(nb / 4), dim3(256), 0, s, (const __bf16 *)dh,
-                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
-                           (__bf16 *)dx, partial, T, H);
+                                 const void *dres, void *dx, float *partial, float *csum, int T, int H, int nb,
+                                 hipStream_t s) {
+#define OB_NBW(LN, CS)                                                                                          \
+    hipLaunchKernelGGL((norm_bwd_wave_kernel<LN, NV, CS>), dim3(nb / 4), dim3(256), 0, s, (const __bf16 *)dh,    \
+                       (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres, (__bf16 *)dx,     \
+                       partial, csum, T, H)
+    if (norm == OB_LAYERNORM) { if (csum) OB_NBW(true, true); else OB_NBW(true, false); }
+    else { if (csum) OB_NBW(false, true); else OB_NBW(false, false); }
+#undef OB_NBW
 }
 
+// csum (may be null): [norm_bwd_partials(T)][2][H] fp32, column sums of dres and of dx per partial
 void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
-                     const void *dres, void *dx, float *partial, int T, int H, hipStream_t s) {
+                     const void *dres, void *dx, float *partial, int T, int H, hipStream_t s, float *csum) {
     ProfScope prof(K_NORM_BWD, s, 8.0 * T * H);
     const int nb = norm_bwd_partials(T);
     // a wave per row while a row fits 8 vectors per lane and there are whole workgroups of rows
     if (H <= 4096 && nb % 4 == 0) {
-        if (H <= 1024) launch_norm_bwd_wave<2>(norm, dh, x, stats, gamma, dres, dx, partial, T, H, nb, s);
-        else if (H <= 2048) launch_norm_bwd_wave<4>(norm, dh, x, stats, gamma, dres, dx, partial, T, H, nb, s);
-        else launch_norm_bwd_wave<8>(norm, dh, x, stats, gamma, dres, dx, partial, T, H, nb, s);
+        if (H <= 1024) launch_norm_bwd_wave<2>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb, s);
+        else if (H <= 2048) launch_norm_bwd_wave<4>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb, s);
+        else launch_norm_bwd_wave<8>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb, s);
         return;
     }
-    if (norm == OB_LAYERNORM)
-        hipLaunchKernelGGL(norm_bwd_kernel<true>, dim3(nb), dim3(NORM_THREADS), 0, s, (const __bf16 *)dh,
-                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
-                           (__bf16 *)dx, partial, T, H);
-    else
-        hipLaunchKernelGGL(norm_bwd_kernel<false>, dim3(nb), dim3(NORM_THREADS), 0, s, (const __bf16 *)dh,
-                           (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres,
-                           (__bf16 *)dx, partial, T, H);
+#define OB_NB(LN, CS)                                                                                          \
+    hipLaunchKernelGGL((norm_bwd_kernel<LN, CS>), dim3(nb), dim3(NORM_THREADS), 0, s, (const __bf16 *)dh,       \
+                       (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres, (__bf16 *)dx,    \
+                       partial, csum, T, H)
+    if (norm == OB_LAYERNORM) { if (csum) OB_NB(true, true); else OB_NB(true, false); }
+    else { if (csum) OB_NB(false, true); else OB_NB(false, false); }
+#undef OB_NB
 }
 
 void launch_reduce_partials(const float *partial, int n_part, int stride, void *out, int C,

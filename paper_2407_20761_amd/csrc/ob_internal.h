@@ -49,8 +49,11 @@ void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *bet
                      float *stats, int T, int H, float eps, hipStream_t s);
 // dx = dres + norm_bwd(dh); partial [n_part, 2, H] fp32 sums of dgamma / dbeta
 int norm_bwd_partials(int T);
+// csum (may be null): [norm_bwd_partials(T)][2][H] fp32 column sums of dres and of dx (the bias gradients
+// of the linears on either side of the norm), formed in the same pass
 void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
-                     const void *dres, void *dx, float *partial, int T, int H, hipStream_t s);
+                     const void *dres, void *dx, float *partial, int T, int H, hipStream_t s,
+                     float *csum = nullptr);
 // out[c] (bf16) = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]
 void launch_reduce_partials(const float *partial, int n_part, int stride, void *out, int C,
                             int accumulate, hipStream_t s);

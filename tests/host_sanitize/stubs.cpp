@@ -22,7 +22,7 @@ int gemm_any(int, int, int, int, const void *, const void *, void *, const void 
 void launch_norm_fwd(int, const void *, const void *, const void *, void *, float *, int, int, float, hipStream_t) { OB_STUB("launch_norm_fwd"); }
 int norm_bwd_partials(int T) { return T < 1024 ? T : 1024; }
 void launch_norm_bwd(int, const void *, const void *, const float *, const void *, const void *, void *, float *, int,
-                     int, hipStream_t) { OB_STUB("launch_norm_bwd"); }
+                     int, hipStream_t, float *) { OB_STUB("launch_norm_bwd"); }
 void launch_reduce_partials(const float *, int, int, void *, int, int, hipStream_t) { OB_STUB("launch_reduce_partials"); }
 int launch_reduce_batch(const ReduceBatch &, int, hipStream_t) { OB_STUB("launch_reduce_batch"); }
 int colsum_partials(int T) { return T < 256 ? T : 256; }
