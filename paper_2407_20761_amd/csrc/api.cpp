@@ -162,12 +162,12 @@ Work work_layout(const Dims &m) {
     size_t g = 0;
     auto upd = [&](int layout, int M, int N, int K) { const size_t b = gemm_workspace_bytes(layout, M, N, K); if (b > g) g = b; };
     upd(1, m.T, m.F, m.H);      // dact  = dy W_down
-    upd(2, m.H, m.F, m.T);      // dW_down = dy^T act
-    upd(2, m.upF, m.H, m.T);    // dW_up = dup^T h2
+    // the four weight gradients (dy^T act, dup^T h2, dx1^T o, dqkv^T h1) go out as one group
+    const GemmTN wg[4] = {{m.H, m.F, nullptr, nullptr, nullptr, nullptr}, {m.upF, m.H, nullptr, nullptr, nullptr, nullptr},
+                          {m.H, m.HD, nullptr, nullptr, nullptr, nullptr}, {m.Dqkv, m.H, nullptr, nullptr, nullptr, nullptr}};
+    { const size_t b = gemm_tn_group_workspace_bytes(4, wg, m.T); if (b > g) g = b; }
     upd(1, m.T, m.H, m.upF);    // dh2 = dup W_up
-    upd(2, m.H, m.HD, m.T);     // dW_o = dx1^T o
     upd(1, m.T, m.HD, m.H);     // d_o = dx1 W_o
-    upd(2, m.Dqkv, m.H, m.T);   // dW_qkv = dqkv^T h1
     upd(1, m.T, m.H, m.Dqkv);   // dh1 = dqkv W_qkv
     w.gemm_bytes = g; w.gemm = L.take(g);
     w.total = L.off;
@@ -400,9 +400,7 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
 
     // y = x1 + act W_down^T + b_down
     if ((rc = gemm_any(1, m.T, m.F, m.H, dy, w->w_down, dact, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
-    if ((rc = gemm_any(2, m.H, m.F, m.T, dy, act, g->w_down, nullptr, acc ? g->w_down : nullptr, gws, wk.gemm_bytes, s))) return rc;
     launch_act_bwd(desc->mlp, dact, up, dup, m.T, m.F, s);
-    if ((rc = gemm_any(2, m.upF, m.H, m.T, dup, h2, g->w_up, nullptr, acc ? g->w_up : nullptr, gws, wk.gemm_bytes, s))) return rc;
     if (bias) bias_grad(dup, m.upF, wk.p_up, g->b_up);
     if ((rc = gemm_any(1, m.T, m.H, m.upF, dup, w->w_up, dh, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // dx1 = dy + norm2_bwd(dh2)
@@ -415,7 +413,6 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
         sums.add(csum + m.H, nnb, 2 * m.H, g->b_o, m.H);
     }
     // x1 = x + o W_o^T + b_o
-    if ((rc = gemm_any(2, m.H, m.HD, m.T, dx1, o, g->w_o, nullptr, acc ? g->w_o : nullptr, gws, wk.gemm_bytes, s))) return rc;
     if ((rc = gemm_any(1, m.T, m.HD, m.H, dx1, w->w_o, d_o, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // attention
     float *lse2 = (float *)at(ws, wk.lse2);
@@ -425,12 +422,19 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
                     m.Dqkv, m.Dqkv, m.HD, seg, m.nq, m.nkv, m.d, scale, desc->mask,
                     desc->use_rotary ? desc->rotary_base : 0.f, s);
     // qkv = h1 W_qkv^T + b_qkv
-    if ((rc = gemm_any(2, m.Dqkv, m.H, m.T, dqkv, h1, g->w_qkv, nullptr, acc ? g->w_qkv : nullptr, gws, wk.gemm_bytes, s))) return rc;
     if (bias) bias_grad(dqkv, m.Dqkv, wk.p_qkv, g->b_qkv);
     if ((rc = gemm_any(1, m.T, m.H, m.Dqkv, dqkv, w->w_qkv, dh, nullptr, nullptr, gws, wk.gemm_bytes, s))) return rc;
     // dx = dx1 + norm1_bwd(dh1)
     launch_norm_bwd(desc->norm, dh, x, (const float *)at(saved, sv.stat1), w->n1_g, dx1, dx, (float *)at(ws, wk.p_n1), m.T, m.H, s);
     norm_grads(wk.p_n1, g->n1_g, g->n1_b);
+    // The four weight gradients, dW = (upstream gradient)^T (layer input) over all tokens, in one launch:
+    // their operands are all still in place (dy, the workspace members, `saved`), and dealt to the chip as
+    // one list of tiles they leave one incomplete round instead of four.
+    const GemmTN wgrads[4] = {{m.H, m.F, dy, act, g->w_down, acc ? g->w_down : nullptr},
+                              {m.upF, m.H, dup, h2, g->w_up, acc ? g->w_up : nullptr},
+                              {m.H, m.HD, dx1, o, g->w_o, acc ? g->w_o : nullptr},
+                              {m.Dqkv, m.H, dqkv, h1, g->w_qkv, acc ? g->w_qkv : nullptr}};
+    if ((rc = gemm_tn_group(4, wgrads, m.T, gws, wk.gemm_bytes, s))) return rc;
     if ((rc = launch_reduce_batch(sums, acc, s))) return rc;
     return check_launch("ob_block_bwd");
 }

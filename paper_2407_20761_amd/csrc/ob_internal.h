@@ -43,6 +43,12 @@ size_t gemm_workspace_bytes(int layout, int M, int N, int K);
 int gemm_any(int layout, int M, int N, int K, const void *A, const void *B, void *C,
              const void *bias, const void *R, void *ws, size_t ws_bytes, hipStream_t s);
 
+// C[M, N] = A[K, M]^T B[K, N] (+ R): one weight gradient; up to 4 of them over the same K go out as one
+// launch (gemm_tn_group), with ws of gemm_tn_group_workspace_bytes() bytes
+struct GemmTN { int M, N; const void *A, *B; void *C; const void *R; };
+size_t gemm_tn_group_workspace_bytes(int count, const GemmTN *g, int K);
+int gemm_tn_group(int count, const GemmTN *g, int K, void *ws, size_t ws_bytes, hipStream_t s);
+
 // ---- elementwise (elementwise.hip) -----------------------------------------------------------
 // stats: LayerNorm [T,2] = (mean, rstd); RMSNorm [T,2] = (unused, rstd)
 void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *beta, void *h,

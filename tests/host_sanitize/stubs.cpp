@@ -17,6 +17,8 @@ namespace ob {
 void launch_gemm_nt(int, int, int, const void *, int, const void *, int, void *, int, const void *, const void *, int,
                     hipStream_t, int, void *) { OB_STUB("launch_gemm_nt"); }
 size_t gemm_workspace_bytes(int, int, int, int) { return 0; }
+size_t gemm_tn_group_workspace_bytes(int, const GemmTN *, int) { return 0; }
+int gemm_tn_group(int, const GemmTN *, int, void *, size_t, hipStream_t) { OB_STUB("gemm_tn_group"); }
 int gemm_any(int, int, int, int, const void *, const void *, void *, const void *, const void *, void *, size_t,
              hipStream_t) { OB_STUB("gemm_any"); }
 void launch_norm_fwd(int, const void *, const void *, const void *, void *, float *, int, int, float, hipStream_t) { OB_STUB("launch_norm_fwd"); }

@@ -486,6 +486,34 @@ def test_block_is_bitwise_reproducible_and_accumulates():
                            run.g[n].view(torch.int16)), n
 
 
+def test_grouped_weight_gradients_of_a_narrow_block():
+    """The 300M-class ViT block over its full batch of 12 tiles: its four weight gradients are less than a
+    round of tiles each and go out as ONE grouped launch (9 GEMM launches per forward + backward instead of
+    12).  Gradients against the oracle (in test_block_full_hidden_sizes_on_a_segment_subset); here: the
+    launch count, bitwise reproducibility, and the accumulate flag through the grouped path."""
+    shape = si.CONFIGS[2]
+    cu = ob.ob_build_cu_seqlens_vit(shape.budget, si.VIT_TILE_TOKENS)
+    T = int(cu[-1])
+    w = si.block_weights(shape, seed=2)
+    x_np, dy_np = si.activations(T, shape.hidden, seed=2)
+    seg = ob.Segments(cu)
+    run = BlockRun(shape, w, T)
+    x, dy = to_dev(x_np), to_dev(dy_np)
+    ob.ob_prof_begin(1000)
+    run.fwd(x, seg)
+    dx1 = run.bwd(x, dy, seg).clone()
+    torch.cuda.synchronize()
+    prof = ob.ob_prof_end()
+    _say(f"grouped wgrad: gemm launches per fwd+bwd = {prof['gemm'][1]}")
+    assert prof["gemm"][1] == 9
+    g1 = {n: t.clone() for n, t in run.g.items()}
+    dx2 = run.bwd(x, dy, seg, accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dx1.view(torch.int16), dx2.view(torch.int16))
+    for n in g1:
+        assert torch.equal((2 * g1[n].float()).to(torch.bfloat16).view(torch.int16), run.g[n].view(torch.int16)), n
+
+
 @pytest.mark.parametrize("cfg", [3, 4, 5])
 def test_full_batch_one_segment_against_oracle(cfg):
     """The launch configurations the bench times (config 3: one full balanced 16K-token batch;
