@@ -570,7 +570,9 @@ def bench_config(config, steps, warmup, seed, spread_batches, full, cpu_baseline
                 "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
                 "traffic_source": "profiles/hbm_traffic.txt, last changed at commit " +
                                   str(git_describe("profiles/hbm_traffic.txt")),
-                "algorithmic_bytes_per_launch": alg_bytes / 12.0,
+                # the 12 GEMMs of a block go out as 12 launches, or fewer when weight gradients are grouped
+                "algorithmic_bytes_per_launch": alg_bytes / (gcnt / (steps * L)),
+                "launches_per_block": gcnt / (steps * L),
                 "avg_launch_us": 1e3 * gms / gcnt, "launches": gcnt,
                 "flops_per_launch_avg": gwork / gcnt,
                 "share_of_step_time": gms / (prof_elapsed * 1e3)}
