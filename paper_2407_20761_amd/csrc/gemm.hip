@@ -4,23 +4,30 @@
 //   "NT" A[M,K] B[N,K] (forward)   "NN" A[M,K] B[K,N] (dgrad)   "TN" A[K,M] B[K,N] (wgrad, K = tokens)
 //
 // One workgroup (4 wavefronts, each a 128x128 block of 8x8 MFMA 16x16x32 tiles, 256 accumulator
-// registers) owns a 256x256 tile of C and walks K in steps of 64 over two LDS stages.  The 16x16x32
-// shape reads and writes half the accumulator registers per FLOP of the 32x32x16 one; under
+// registers) owns a 256x256 tile of C and walks K in steps of 32 over a ring of four LDS slots.  The
+// 16x16x32 shape reads and writes half the accumulator registers per FLOP of the 32x32x16 one; under
 // sustained load the chip is power-limited, and a register-fed loop of it sustains 2010 against
 // 1725-1790 TFLOP/s on random data.
 //
-// Tiles go global -> registers -> LDS: every wave issues one 16-byte-per-lane buffer load per run of
-// 8 MFMAs, all K step long, and writes each vector to LDS one whole K step after it was requested,
-// so the memory pipeline sees a steady stream (a burst of a K step's loads blocks the wave's
-// instruction issue, MFMAs included, until the cache has taken them) and no wait ever meets a
-// load in flight.  The hardware range check of the buffer descriptor turns every access past the end
-// of an operand into zeros: whole rows beyond M / N of a K-contiguous operand, the ragged token tail
-// of K and K steps past the last.  (Columns beyond M / N of a K-major operand wrap into its next row
-// instead; they only feed outputs beyond M / N, which are never stored.)  A K-contiguous operand
-// is staged as [row][64 k] and a fragment is one 16-byte LDS read; a K-major operand is staged as
-// it lies in memory, [k][rows], and the fragment comes out of two transposing LDS reads, so dgrad
-// and wgrad need no re-layout pass.  16-byte chunks are XOR-swizzled on the way in (the global
-// address of each lane's chunk is free to choose) so that LDS reads are bank-conflict free.
+// A wave has its SIMD to itself, so every instruction that is not an MFMA takes an issue slot that
+// only the gaps between MFMAs can hide (three per gap), and what moves data costs more than its slot:
+// a 16-byte-per-lane LDS write holds the issue back for as long as its kilobyte takes to leave the
+// registers.  Hence
+//  * a K-major operand ([k][rows], as it lies in memory: B of "NN", both of "TN") goes global -> LDS
+//    directly (buffer loads that write to LDS, one per run of 8 MFMAs, NS - 2 slots ahead of its use)
+//    and its fragments come out of transposing LDS reads, so dgrad and wgrad need no re-layout pass;
+//  * a K-contiguous operand ([row][k]: A of "NT" and "NN", B of "NT") goes global -> registers -> LDS in
+//    whole 128-byte rows, two slots at a time (straight to LDS it would fetch every cache line twice),
+//    each vector written to LDS one K step after it was requested, so no wait ever meets a load in
+//    flight; a fragment is one 16-byte LDS read;
+//  * the descriptor arithmetic of the next slot is a dozen scalar instructions dealt over the gaps of
+//    one run (left to the compiler it was some 35 instructions with 64-bit vector compares in one
+//    place, 5 % of the loop).
+// The hardware range check of the buffer descriptor turns every access past the end of an operand into
+// zeros: whole rows beyond M / N of a K-contiguous operand, the ragged token tail of K and slots past
+// the last.  (Columns beyond M / N of a K-major operand wrap into its next row instead; they only
+// feed outputs beyond M / N, which are never stored.)  16-byte chunks are XOR-swizzled on the way in
+// (the global address of each lane's chunk is free to choose) so that LDS reads are bank-conflict free.
 // The weight-side rows are the MFMA's first operand, so a lane's accumulators are runs of four
 // consecutive output columns; the epilogue transposes them through LDS into full-row stores.
 #include <algorithm>
@@ -38,8 +45,10 @@ namespace {
 
 #define OB_LDS __attribute__((address_space(3)))
 
-constexpr int BK = 64;           // k per LDS stage: 8 chunks of 16 bytes = 128 bytes per row
+constexpr int BK = 32;           // k per ring slot: 4 chunks of 16 bytes = 64 bytes per row of a K-contiguous operand
 constexpr int ROW_BYTES = BK * 2;
+constexpr int NS = 4;            // ring slots
+constexpr int KSTEP = 64;        // k per "K step", the unit the host's plan counts and slices in (two slots)
 
 // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous range of the `count`
 // work items that the workgroups [first, first + count) of a launch stand for (first % 8 == 0).
@@ -79,37 +88,46 @@ template <int BM, int BN, int WM, int WN>
 struct Cfg {
     static constexpr int NW = WM * WN;
     static constexpr int T = BM / WM / 16;        // 16x16 MFMA tiles per wave, each way
-    static constexpr int A_LD = BM / 8 / NW, B_LD = BN / 8 / NW;
-    static constexpr int G = A_LD + B_LD;         // copy groups of one wave per K step
-    static constexpr int STAGE = (BM + BN) * ROW_BYTES;
+    static constexpr int SLOT = (BM + BN) * ROW_BYTES;
     static_assert(BM / WM == BN / WN, "square wave tiles");
-    static_assert(G == 2 * T, "one copy group per run of T MFMAs");
+    static_assert(BM == BN && BM / 16 / NW * 2 == T, "T / 2 pieces of 1 KB per wave, operand and slot");
 };
 
-// One operand's tile in LDS, in one of two layouts; a fragment of the 16x16x32 MFMA is 16 x-values by
-// 32 k, lane l holding x = l % 16, k = 8 (l / 16) .. +7.
+// One operand's part of the ring; a fragment of the 16x16x32 MFMA is 16 x-values by 32 k, lane l
+// holding x = l % 16, k = 8 (l / 16) .. +7.
 //
-// KMAJOR = false: the source is [X, K] with k contiguous.  LDS holds [x][8 chunks of 16 B], chunks
-//   swizzled by row (see row_swizzle).  A fragment is one 16-byte read per lane.
-// KMAJOR = true: the source is [K, X] with x contiguous.  LDS holds [k][X / 8 chunks of 16 B]
-//   (8 x-values per chunk); the chunk at physical position p of row k is logical chunk
-//   p ^ 4 (k & 3) ^ 2 ((k >> 3 ^ k >> 4) & 1).  A fragment is two transposing 8-byte reads
-//   (ds_read_b64_tr_b16): inside a group of 16 lanes, lane 4 k' + c addresses the 4 x-values
-//   [4c, 4c + 4) of row k' of a 4 x 16 block, and lane p receives column p, i.e. 4 consecutive k of
-//   one x.  The four groups of a read sit at k, k + 8, k + 16, k + 24 over the same x; the second
-//   swizzle term puts any two of them that could be served together 32 bytes apart.
+// KMAJOR = true: the source is [K, X] with x contiguous.  A slot holds [32 k][X / 8 chunks of 16 B]
+//   (8 x-values per chunk) and is filled by buffer loads that write straight to LDS: the 64 lanes
+//   of one load deliver 16 bytes each to 1 KB of consecutive LDS addresses (lane i at 16 i), and which
+//   16 bytes of global memory a lane asks for is free to choose: the chunk at physical position p
+//   of row k is logical chunk p ^ 4 (k & 3) ^ 2 ((k >> 3 ^ k >> 4) & 1).  A fragment is two
+//   transposing 8-byte reads (ds_read_b64_tr_b16): inside a group of 16 lanes, lane 4 k' + c
+//   addresses the 4 x-values [4c, 4c + 4) of row k' of a 4 x 16 block, and lane p receives column p,
+//   i.e. 4 consecutive k of one x.  The four groups of a read sit at k, k + 8, k + 16, k + 24 over
+//   the same x; the second swizzle term puts any two of them that could be served together 32 bytes
+//   apart.
+// KMAJOR = false: the source is [X, K] with k contiguous.  Straight to LDS, a load could fill 16 rows of
+//   one slot, 64 bytes of each: half a cache line, whose other half the load for the next slot
+//   would fetch again once the line has left the first-level cache (measured: a quarter slower than
+//   whole lines).  So this operand's slots come in pairs, [x][8 chunks of 16 B] (64 k), the chunk c of
+//   row x at position c ^ row_swizzle(x), and go global -> registers -> LDS a pair at a time: one load
+//   takes 8 rows of 128 bytes, and one K step later each lane writes its 16 bytes, lane-linear inside
+//   the 1 KB piece (the swizzle was applied by the choice of each lane's global address).  A fragment
+//   is one 16-byte read per lane, from the chunks 0-3 (even slot) or 4-7 (odd slot).
 template <int X, int NW, int T, bool KMAJOR>
 struct Operand {
-    static constexpr int LD = X / 8 / NW;
+    static constexpr int LD = KMAJOR ? X / 16 / NW : X / 8 / NW;   // loads per wave: per slot / per two slots
     static constexpr int ROWB = X * 2;
-    const unsigned char *base;
-    long left;                                   // bytes from `base` to the end of the source
-    uint32_t step;                               // bytes per K step
+    uint64_t base;                               // (uniform) address of the slot / pair of slots to describe next
+    long left;                                   // bytes from there to the end of the source (may be negative)
+    uint32_t step;                               // bytes from one to the next
+    uint32_t num;                                // checked range of the one at hand
     uint32_t voff[LD];
-    int rd[KMAJOR ? T : BK / 32];                // LDS read offsets: per tile i (k-major) / per k-step u
+    int rd[KMAJOR ? T : 2];                      // LDS read offsets (from the ring's start): per tile i (k-major) / per slot of the pair
+    int wr;                                      // k-contiguous: LDS write offset of this lane in piece 0 of pair 0
+    u32x4 v[KMAJOR ? 1 : LD];                    // k-contiguous: the loads on their way
 
-    // k-contiguous layout: the chunk at physical position p of row x is logical chunk
-    // p ^ row_swizzle(x).  The LDS serves a 16-byte read 16 lanes at a time (measured with a probe
+    // k-contiguous layout.  The LDS serves a 16-byte read 16 lanes at a time (measured with a probe
     // of lane pairs): within each half of the wavefront, first the lanes whose index bits 2, 3, 4 have
     // even parity, then the others.  For these fragments such a group is all 16 rows, the rows with
     // bit 2 ^ bit 3 = 0 at chunk c and the others at c ^ 1 (or the other way round); rows alternate
@@ -118,27 +136,25 @@ struct Operand {
     static __device__ __forceinline__ int row_swizzle(int x) { return (x >> 1) & 7; }
 
     // ld = source leading dimension (elements); x0 = first tile row; total_bytes = size of the
-    // source; wave_x0 = first x-value of this wave's part of the tile
+    // source; wave_x0 = first x-value of this wave's part of the tile; region = where in the ring this
+    // operand's slots start (part of every per-lane offset, so that what is added per slot, tile and
+    // piece fits an instruction's 16-bit offset field)
     __device__ __forceinline__ void init(const __bf16 *src, int ld, int x0, long total_bytes, int wave,
-                                         int lane, int wave_x0) {
+                                         int lane, int wave_x0, int region) {
         if (!KMAJOR) {
-            base = (const unsigned char *)(src + (size_t)x0 * ld);
-            left = total_bytes - (long)x0 * ld * 2;
-            step = ROW_BYTES;
+            set((const unsigned char *)(src + (size_t)x0 * ld), total_bytes - (long)x0 * ld * 2, 2 * ROW_BYTES, 0);
 #pragma unroll
             for (int p = 0; p < LD; ++p) {
-                const int blk = wave * LD + p, row = blk * 8 + (lane >> 3);
+                const int row = (wave * LD + p) * 8 + (lane >> 3);
                 const int ch = (lane & 7) ^ row_swizzle(row);
                 voff[p] = ((uint32_t)row * (uint32_t)ld + ch * 8) * 2u;
             }
             const int lx = lane & 15, lq = lane >> 4;
-            const int f = row_swizzle(lx);
 #pragma unroll
-            for (int u = 0; u < BK / 32; ++u) rd[u] = (wave_x0 + lx) * ROW_BYTES + (((4 * u + lq) ^ f) * 16);
+            for (int h = 0; h < 2; ++h) rd[h] = region + (wave_x0 + lx) * 2 * ROW_BYTES + (((4 * h + lq) ^ row_swizzle(lx)) * 16);
+            wr = region + wave * LD * 1024 + lane * 16;
         } else {
-            base = (const unsigned char *)(src + x0);
-            left = total_bytes - (long)x0 * 2;
-            step = (uint32_t)BK * (uint32_t)ld * 2u;
+            set((const unsigned char *)(src + x0), total_bytes - (long)x0 * 2, (uint32_t)BK * (uint32_t)ld * 2u, 0);
             constexpr int KPB = 1024 / ROWB, CPR = ROWB / 16;
 #pragma unroll
             for (int p = 0; p < LD; ++p) {
@@ -152,55 +168,69 @@ struct Operand {
 #pragma unroll
             for (int i = 0; i < T; ++i) {
                 const int chunk = (wave_x0 + 16 * i) / 8 + (c >> 1);
-                rd[i] = (8 * b + kq) * ROWB + ((chunk ^ (4 * kq) ^ (2 * ((b ^ (b >> 1)) & 1))) * 16) + (c & 1) * 8;
+                rd[i] = region + (8 * b + kq) * ROWB + ((chunk ^ (4 * kq) ^ (2 * ((b ^ (b >> 1)) & 1))) * 16) + (c & 1) * 8;
             }
+            wr = 0;
         }
     }
-    __device__ __forceinline__ void advance() {
+    // the contraction starts `first` steps into the source (all arguments uniform)
+    __device__ __forceinline__ void set(const unsigned char *b, long l, uint32_t step_bytes, int first) {
+        base = (uint64_t)b + (uint64_t)first * step_bytes;
+        left = l - (long)first * step_bytes;
+        step = step_bytes;
+    }
+    // start the contraction `ksteps` K steps (64 k) into the source
+    __device__ __forceinline__ void skip(int ksteps) {
+        set((const unsigned char *)base, left, step, KMAJOR ? 2 * ksteps : ksteps);
+    }
+    // Descriptor of the slot (pair) at hand, then on to the next one, in two parts (to be placed between
+    // different pairs of MFMAs).  The range a descriptor can check is 32 bits wide: a source with more
+    // than 4 GB left is clamped (no access of a slot reaches that far from the base), one past its
+    // end is empty, and so is any slot when k_left < 1 (every load returns zeros without touching
+    // memory).  Written as scalar instructions: the compiler's own 64-bit compares go through the
+    // vector unit, a few dozen instructions per slot that a wave alone on its SIMD cannot hide.
+    __device__ __forceinline__ void next_range(int k_left) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm("s_cmp_eq_u32 %2, 0\n\ts_cselect_b32 %0, %1, -1\n\t"
+            "s_cmp_lt_i32 %2, 0\n\ts_cselect_b32 %0, 0, %0\n\t"
+            "s_cmp_gt_i32 %3, 0\n\ts_cselect_b32 %0, %0, 0"
+            : "=&s"(num)
+            : "s"((uint32_t)left), "s"((int32_t)(left >> 32)), "s"(k_left)
+            : "scc");
+#endif
+    }
+    __device__ __forceinline__ __amdgpu_buffer_rsrc_t next() {
+        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)num, 0x00020000);
         base += step;
         left -= step;
+        return r;
     }
-    // start the contraction `steps` K steps into the source
-    __device__ __forceinline__ void skip(int steps) {
-        base += (long)steps * step;
-        left -= (long)steps * step;
+    // k-major: piece p (1 KB per wave) of this wave's share of the slot behind `rsrc`: global -> LDS,
+    // lane i to byte 16 i of the piece; lanes past the end of the source (rows beyond K) deliver zeros
+    __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char OB_LDS *__restrict__ dst, int wave, int p) const {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void OB_LDS *)(dst + (wave * LD + p) * 1024), 16, voff[p], 0, 0, 0);
     }
-    // descriptor of the current K step; must sit in scalar registers: pin its (uniform) parts explicitly
-    // (live = false: an empty range, every load returns zeros without touching memory)
-    __device__ __forceinline__ __amdgpu_buffer_rsrc_t descriptor(bool live) const {
-        const uint64_t b = (uint64_t)base;
-        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
-        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-        // the range a descriptor can check is 32 bits wide: a source with more than 4 GB left is
-        // clamped (no access of a K step reaches that far from `base`), one past its end is empty
-        const long cl = left < 0 ? 0 : (left > 0xFFFFFFFFl ? 0xFFFFFFFFl : left);
-        return __builtin_amdgcn_make_buffer_rsrc((void *)(((uint64_t)hi << 32) | lo), 0,
-                                                 live ? (int)__builtin_amdgcn_readfirstlane((uint32_t)cl) : 0, 0x00020000);
+    // k-contiguous: piece p (8 rows of 64 k) of this wave's share of the pair of slots behind `rsrc`:
+    // global -> registers (rows beyond M / N deliver zeros), and registers -> the pair at `dst`
+    __device__ __forceinline__ void request(__amdgpu_buffer_rsrc_t rsrc, int p) {
+        v[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[p], 0, 0);
     }
-    // piece p (1 KB per wave) of this wave's share of the K step behind `rsrc`: global -> registers;
-    // loads past the end of the source (rows beyond M / N / K) deliver zeros
-    __device__ __forceinline__ u32x4 load(__amdgpu_buffer_rsrc_t rsrc, int p) const {
-        return __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[p], 0, 0);
+    __device__ __forceinline__ void deliver(unsigned char OB_LDS *__restrict__ ring, int pair_bytes, int p) const {
+        *(u32x4 OB_LDS *)(ring + wr + pair_bytes + p * 1024) = v[p];
     }
-    // registers -> its place in the stage (lane-linear inside the 1 KB piece: the swizzle was applied
-    // by the choice of each lane's global address)
-    __device__ __forceinline__ void store(unsigned char OB_LDS *__restrict__ dst, int wave, int lane, int p, u32x4 v) const {
-        *(u32x4 OB_LDS *)(dst + (wave * LD + p) * 1024 + lane * 16) = v;
-    }
-    // fragment for MFMA tile i (16 x-values) at k-step u (32 k)
-    __device__ __forceinline__ bf16x8 frag(const unsigned char OB_LDS *__restrict__ tile, int i, int u) const {
+    // fragment for MFMA tile i (16 x-values) out of the slot at `tile` (k-contiguous: slot h of the
+    // pair at `tile`)
+    __device__ __forceinline__ bf16x8 frag(const unsigned char OB_LDS *__restrict__ tile, int i, int h) const {
         if (!KMAJOR) {
-            return *(const bf16x8 OB_LDS *)(tile + rd[u] + i * 16 * ROW_BYTES);
+            return *(const bf16x8 OB_LDS *)(tile + rd[h] + i * 16 * 2 * ROW_BYTES);
         } else {
 #if defined(__HIP_DEVICE_COMPILE__)
             typedef __attribute__((ext_vector_type(4))) short s16x4;
             typedef __attribute__((ext_vector_type(8))) short s16x8;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 OB_LDS *)(tile + rd[i] + (32 * u) * ROWB));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (s16x4 OB_LDS *)(tile + rd[i] + (32 * u + 4) * ROWB));
-            const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            return __builtin_bit_cast(bf16x8, v);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 OB_LDS *)(tile + rd[i]));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 OB_LDS *)(tile + rd[i] + 4 * ROWB));
+            const s16x8 v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            return __builtin_bit_cast(bf16x8, v8);
 #else
             return bf16x8{};
 #endif
@@ -215,106 +245,226 @@ __device__ __forceinline__ void mfma(f32x4 &acc, bf16x8 first, bf16x8 second) {
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(first), "v"(second));
 }
 
-// State of one wave in the K loop.  A K step (64 k, one LDS stage) is two k-steps of T runs; run g
-// multiplies A fragment g with all T B fragments, and carries one copy group (deliver the vector
-// requested one K step ago, request the same piece of the K step after) between its MFMAs and two
-// or three fragment reads for the next k-step in front of them: the next B fragments into the
-// other B set, the next A fragment g - 1 into the register run g - 1 has just finished with.
+// The bare barrier instruction: __syncthreads() carries a fence as well, which waits for every load
+// to LDS still in flight, the ones for the slots further ahead included.  What has to be complete at a
+// barrier is said by the s_waitcnt in front of it; the empty statement keeps the compiler from moving
+// LDS accesses across.
+__device__ __forceinline__ void wg_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// s_waitcnt operand: at most `vm` vector-memory operations and `lgkm` LDS operations still pending
+constexpr int waitcnt(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) | 0x70 | (lgkm << 8); }
+
+// State of one wave in the K loop.  The contraction advances one ring slot (32 k) at a time: T runs,
+// run g multiplying A fragment g with all T B fragments.  Between its MFMAs a run carries two or
+// three fragment reads for the slot after (the next B fragment g into the other B set, the next A
+// fragment g - 1 into the register run g - 1 has just finished with) and one step of the refill:
+//  * a k-major operand refills, for NS slots ahead, the slot whose last reader has passed the barrier
+//    behind run 0: its T / 2 loads go straight to LDS, from run 1 on (A first; with both operands k-major
+//    the last load of B falls into run 0 of the slot after);
+//  * a k-contiguous operand refills two slots at a time, T pieces that were requested one K step
+//    before: between the barrier of an odd slot, when both slots of the pair before are free, and the
+//    barrier two slots on, behind which the first of them is read again, there are 2 T runs; a
+//    piece is written to LDS in one of them and requested again, for one K step further on.
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 struct KLoop {
     using C = Cfg<BM, BN, WM, WN>;
     static constexpr int T = C::T;
     Operand<BM, C::NW, T, AK> opa;
     Operand<BN, C::NW, T, BKM> opb;
-    u32x4 v[C::G];
-    __amdgpu_buffer_rsrc_t ra, rb;
-    int k_left;
+    __amdgpu_buffer_rsrc_t ra, rb, ra_n, rb_n;
+    int ka_left, kb_left;                        // slots (k-major) / pairs of slots (k-contiguous) not yet described
     int wave, lane;
     bf16x8 af[T], bfr[2][T];
 
-    __device__ __forceinline__ void next_k() {
-        const bool live = k_left > 0;
-        --k_left;
-        ra = opa.descriptor(live);
-        rb = opb.descriptor(live);
-        opa.advance();
-        opb.advance();
-    }
-    __device__ __forceinline__ void request(int g) {
-        v[g] = g < C::A_LD ? opa.load(ra, g) : opb.load(rb, g - C::A_LD);
-    }
-    __device__ __forceinline__ void deliver(unsigned char OB_LDS *__restrict__ dst, int g) const {
-        if (g < C::A_LD) opa.store(dst, wave, lane, g, v[g]);
-        else opb.store(dst + BM * ROW_BYTES, wave, lane, g - C::A_LD, v[g]);
-    }
-    __device__ __forceinline__ bf16x8 a_frag(const unsigned char OB_LDS *__restrict__ stage, int i, int u) const {
-        return opa.frag(stage, i, u);
-    }
-    __device__ __forceinline__ bf16x8 b_frag(const unsigned char OB_LDS *__restrict__ stage, int j, int u) const {
-        return opb.frag(stage + BM * ROW_BYTES, j, u);
-    }
-    // The fragment reads that run g carries.  KIND 0: none.  1: first k-step, reading the second
-    // one of the same stage.  2: run 0 of the second k-step (its own last A fragment; the barrier
-    // follows).  3: second k-step, reading the first one of the next stage (one B read more in run 1,
-    // which makes up for run 0).
-    template <int KIND>
-    __device__ __forceinline__ void read_b(const unsigned char OB_LDS *__restrict__ src, int g) {
-        if (KIND == 1) bfr[1][g] = b_frag(src, g, 1);
-        if (KIND == 3) bfr[0][g] = b_frag(src, g, 0);
-    }
-    template <int KIND>
-    __device__ __forceinline__ void read_a(const unsigned char OB_LDS *__restrict__ src, int g) {
-        if (KIND == 1) {
-            if (g == 0) af[T - 1] = a_frag(src, T - 1, 0);
-            else af[g - 1] = a_frag(src, g - 1, 1);
+    // the descriptors of the next slot (pair), in four parts; ra_n, rb_n take over at commit()
+    template <int PART>
+    __device__ __forceinline__ void next_part() {
+        if (PART == 0) opa.next_range(ka_left);
+        if (PART == 1) {
+            ra_n = opa.next();
+            --ka_left;
         }
-        if (KIND == 2) af[T - 1] = a_frag(src, T - 1, 1);
-        if (KIND == 3) af[g - 1] = a_frag(src, g - 1, 0);
+        if (PART == 2) opb.next_range(kb_left);
+        if (PART == 3) {
+            rb_n = opb.next();
+            --kb_left;
+        }
     }
-    template <int KIND>
-    __device__ __forceinline__ void read_extra(const unsigned char OB_LDS *__restrict__ src, int g) {
-        if (KIND == 3 && g == 1) bfr[0][0] = b_frag(src, 0, 0);
+    __device__ __forceinline__ void next_a() {
+        next_part<0>();
+        next_part<1>();
+        ra = ra_n;
     }
-    // Run g: the T MFMAs of A fragment g with B set `set`, and between them, never more than one
-    // memory instruction between two MFMAs (a 16x16x32 MFMA keeps the pipe busy for four issue slots
-    // of a lone wave, and whatever sits between two of them beyond three slots is lost): the run's
-    // fragment reads, then the delivery of copy group `grp` to `fill` (well behind the reads: an LDS
-    // write right after LDS reads stalls), then its next request (COPY = false: no copy group).
-    template <int KIND, bool COPY>
-    __device__ __forceinline__ void run(f32x4 (&acc)[T][T], int g, int set, const unsigned char OB_LDS *__restrict__ src,
-                                        unsigned char OB_LDS *__restrict__ fill, int grp) {
+    __device__ __forceinline__ void next_b() {
+        next_part<2>();
+        next_part<3>();
+        rb = rb_n;
+    }
+    // The ring holds A's NS slots, then B's: a k-major operand's one after the other, a k-contiguous
+    // one's in pairs.  Fragment i of operand A (j of B) out of the slot in ring position S:
+    static constexpr int A_SLOT = BM * ROW_BYTES, B_SLOT = BN * ROW_BYTES, B_RING = NS * A_SLOT;
+    __device__ __forceinline__ bf16x8 a_frag(const unsigned char OB_LDS *__restrict__ ring, int S, int i) const {
+        return opa.frag(ring + (AK ? S : S & ~1) * A_SLOT, i, S & 1);       // (the operand's offsets start at its region)
+    }
+    __device__ __forceinline__ bf16x8 b_frag(const unsigned char OB_LDS *__restrict__ ring, int S, int j) const {
+        return opb.frag(ring + (BKM ? S : S & ~1) * B_SLOT, j, S & 1);
+    }
+    // Position of run g of slot S among the 2 T runs between the barrier of an odd slot and the barrier
+    // two slots on: the odd slot's runs 1 .. T-1, the even slot's runs, run 0 of the next odd slot.
+    static constexpr int position(int S, int g) { return (S & 1) ? (g == 0 ? 2 * T - 1 : g - 1) : T - 1 + g; }
+    // the piece of a k-contiguous operand that the run at position q carries (-1: none): with both
+    // operands k-contiguous A takes the even positions and B the odd ones; next to a k-major operand,
+    // whose loads sit in runs 1 .. T/2 of every slot, the other runs
+    static constexpr int piece_a(int q) {
+        if (AK) return -1;
+        if (!BKM) return (q & 1) ? -1 : q / 2;
+        return q >= T / 2 && q < T ? q - T / 2 : (q >= T + T / 2 ? q - T : -1);
+    }
+    static constexpr int piece_b(int q) {
+        if (BKM) return -1;
+        return (q & 1) ? q / 2 : -1;             // (A is k-contiguous as well: there is no layout with A alone k-major)
+    }
+    // the pair of slots (0: slots 0 and 1; 1: slots 2 and 3) that the runs of slot S refill
+    static constexpr int pair_of(int S, int g) { return (S & 1) ? (g == 0 ? ((S + 1) / 2) & 1 : (S - 1) / 2) : ((S / 2) + 1) & 1; }
+
+    // Run g of the slot in ring position S: its T MFMAs and between them, never more than one memory
+    // instruction between two MFMAs (a 16x16x32 MFMA keeps the pipe busy for four issue slots of a
+    // lone wave, and whatever sits between two of them beyond three slots is lost: scalar
+    // instructions count).  Run 0 reads its slot's own last A fragment (the register was busy until
+    // now) and moves the descriptors on; the others read ahead in the slot after (run 1 one B fragment
+    // more, which makes up for run 0).
+    template <int S, int g>
+    __device__ __forceinline__ void run(f32x4 (&acc)[T][T], unsigned char OB_LDS *__restrict__ ring) {
         constexpr int AT_RB = 0, AT_RA = 1, AT_RX = T >= 8 ? 2 : 1, AT_DL = T / 2, AT_RQ = T >= 8 ? T / 2 + 2 : T - 1;
+        constexpr int set = S & 1, q = position(S, g), pa = piece_a(q), pb = piece_b(q);
+        constexpr int N = (S + 1) % NS, P = (S + NS - 1) % NS, pair = pair_of(S, g);
 #pragma unroll
         for (int j = 0; j < T; ++j) {
             mfma(acc[g][j], bfr[set][j], af[g]);
             __builtin_amdgcn_sched_barrier(0);
-            if (j == AT_RB) read_b<KIND>(src, g);
-            if (j == AT_RA) read_a<KIND>(src, g);
-            if (j == AT_RX) read_extra<KIND>(src, g);
-            if (COPY && j == AT_DL) deliver(fill, grp);
-            if (COPY && j == AT_RQ) request(grp);
+            if (g == 0) {
+                if (j == AT_RA) af[T - 1] = a_frag(ring, S, T - 1);
+                // the last load of the slot before, when both operands go straight to LDS
+                if (AK && BKM && j == 2) opb.load(rb, ring + B_RING + P * B_SLOT, wave, T / 2 - 1);
+                // descriptors: a k-major operand moves on every slot, a k-contiguous one every other
+                if (AK || (S & 1)) {
+                    if (j == (AK && BKM ? 0 : 2)) next_part<0>();
+                    if (j == (T >= 8 ? 3 : 2)) next_part<1>();
+                }
+                if (BKM || (S & 1)) {
+                    if (j == (T >= 8 ? 5 : 3)) next_part<2>();
+                    if (j == T - 1) next_part<3>();
+                }
+            } else {
+                if (j == AT_RB) bfr[set ^ 1][g] = b_frag(ring, N, g);
+                if (j == AT_RA) af[g - 1] = a_frag(ring, N, g - 1);
+                if (j == AT_RX && g == 1) bfr[set ^ 1][0] = b_frag(ring, N, 0);
+                if (j == AT_RQ) {
+                    if (AK && g - 1 < T / 2) opa.load(ra, ring + S * A_SLOT, wave, g - 1);
+                    if (BKM && !AK && g - 1 < T / 2) opb.load(rb, ring + B_RING + S * B_SLOT, wave, g - 1);
+                    if (BKM && AK && g - 1 >= T / 2) opb.load(rb, ring + B_RING + S * B_SLOT, wave, g - 1 - T / 2);
+                }
+            }
+            // (in run 0 the write goes first: the barrier behind the run waits for it)
+            if (pa >= 0) {
+                if (j == (g == 0 ? 0 : AT_DL)) opa.deliver(ring, pair * 2 * A_SLOT, pa);
+                if (j == AT_RQ) opa.request(ra, pa);
+            }
+            if (pb >= 0) {
+                if (j == (g == 0 ? 0 : AT_DL)) opb.deliver(ring, pair * 2 * B_SLOT, pb);
+                if (j == AT_RQ) opb.request(rb, pb);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (g == 0) {
+            if (AK || (S & 1)) ra = ra_n;
+            if (BKM || (S & 1)) rb = rb_n;
+        }
     }
-    // One K step out of stage `cur`.  On entry bfr[0] and af[0 .. T-2] hold the fragments of its
-    // first k-step.  NEXT: stage `nxt` holds (after the barrier) the K step behind, and on return
-    // the registers hold that one's first fragments; the copy groups in front of the barrier go
-    // to `nxt`, those behind it to `cur`, which by then nobody reads.
-    template <bool NEXT>
-    __device__ __forceinline__ void stage(f32x4 (&acc)[T][T], unsigned char OB_LDS *__restrict__ cur,
-                                          unsigned char OB_LDS *__restrict__ nxt) {
+    template <int S, int g>
+    __device__ __forceinline__ void runs_from(f32x4 (&acc)[T][T], unsigned char OB_LDS *__restrict__ ring) {
+        if constexpr (g < T) {
+            run<S, g>(acc, ring);
+            runs_from<S, g + 1>(acc, ring);
+        }
+    }
+    // the loads of at most this many slots, the newest, may still be on their way at a barrier
+    static constexpr int VM_PENDING = (AK && BKM) ? T * (NS - 2) : BKM ? T * (NS - 2) + T / 2 : 63;
+    // The slot in ring position S.  On entry bfr[S & 1] and af[0 .. T-2] hold its fragments; on return
+    // those of the slot after.
+    template <int S>
+    __device__ __forceinline__ void slot(f32x4 (&acc)[T][T], unsigned char OB_LDS *__restrict__ ring) {
+        run<S, 0>(acc, ring);
+        // own reads of this slot and own writes to LDS landed, own loads to the slot after in LDS (every
+        // run issues one load; the last one to the slot after went out NS - 2 slots ago, T / 2 runs
+        // more when it was B's last with A k-contiguous), then the barrier: the slot after is complete
+        // and nobody reads this one any more
+        __builtin_amdgcn_s_waitcnt(waitcnt(VM_PENDING, 0));
+        wg_barrier();
+        runs_from<S, 1>(acc, ring);
+    }
+    // Before the first slot: the ring filled as the loop expects to find it.  k-major: the first NS
+    // slots requested, all but what run 0 of the first slot issues.  k-contiguous: the first two pairs
+    // of slots, the second one as far as the runs in front of the loop's first would have written it
+    // (positions 0 .. T-2), and those pieces requested again for the pair after.
+    __device__ __forceinline__ void prologue(unsigned char OB_LDS *__restrict__ ring) {
 #pragma unroll
-        for (int g = 0; g < T; ++g) run<1, true>(acc, g, 0, cur, nxt, g);   // k-step 0
-        run<2, true>(acc, 0, 1, cur, nxt, T);
-        if (NEXT) {
-            next_k();                          // scalar work, kept off the path behind the barrier
-            // own LDS traffic done (reads landed, writes in the stage), then the barrier: `nxt` is
-            // complete everywhere and nobody reads `cur` any more; buffer loads stay in flight
-            __builtin_amdgcn_s_waitcnt(0xC07F);
-            __syncthreads();
+        for (int sl = 0; sl < NS; ++sl) {
+            if (AK) {
+                next_a();
+#pragma unroll
+                for (int p = 0; p < T / 2; ++p) opa.load(ra, ring + sl * A_SLOT, wave, p);
+            }
+            if (BKM) {
+                next_b();
+#pragma unroll
+                for (int p = 0; p < T / 2; ++p)
+                    if (!(AK && sl == NS - 1 && p == T / 2 - 1)) opb.load(rb, ring + B_RING + sl * B_SLOT, wave, p);
+            }
+        }
+        if (!AK) {
+            next_a();
+#pragma unroll
+            for (int p = 0; p < T; ++p) opa.request(ra, p);
+        }
+        if (!BKM) {
+            next_b();
+#pragma unroll
+            for (int p = 0; p < T; ++p) opb.request(rb, p);
+        }
+        if (!AK) {
+            next_a();
+#pragma unroll
+            for (int p = 0; p < T; ++p) {
+                opa.deliver(ring, 0, p);
+                opa.request(ra, p);
+            }
+            next_a();
+        }
+        if (!BKM) {
+            next_b();
+#pragma unroll
+            for (int p = 0; p < T; ++p) {
+                opb.deliver(ring, 0, p);
+                opb.request(rb, p);
+            }
+            next_b();
         }
 #pragma unroll
-        for (int g = 1; g < T; ++g) run<NEXT ? 3 : 0, NEXT>(acc, g, 1, nxt, cur, T + g);   // rest of k-step 1
+        for (int q = 0; q < T - 1; ++q) {
+            if (piece_a(q) >= 0) {
+                opa.deliver(ring, 2 * A_SLOT, piece_a(q));
+                opa.request(ra, piece_a(q));
+            }
+            if (piece_b(q) >= 0) {
+                opb.deliver(ring, 2 * B_SLOT, piece_b(q));
+                opb.request(rb, piece_b(q));
+            }
+        }
     }
 };
 
@@ -327,8 +477,7 @@ __device__ __forceinline__ void gemm_tile(
     const __bf16 *R, int ldr, int tile_m, int tile_n, bool sliced, int kz, int tail_tile, const TailSplit &ts) {
     using C = Cfg<BM, BN, WM, WN>;
     constexpr int T = C::T;
-    __shared__ __attribute__((aligned(1024))) unsigned char st0[C::STAGE];
-    __shared__ __attribute__((aligned(1024))) unsigned char st1[C::STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring_mem[NS * C::SLOT];
     const int m0 = __builtin_amdgcn_readfirstlane(tile_m) * BM;
     const int n0 = __builtin_amdgcn_readfirstlane(tile_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -338,8 +487,8 @@ __device__ __forceinline__ void gemm_tile(
     KLoop<BM, BN, WM, WN, AK, BKM> lp;
     lp.wave = wave;
     lp.lane = lane;
-    lp.opa.init(A, lda, m0, (AK ? (long)K : (long)M) * lda * 2, wave, lane, wm * (BM / WM));
-    lp.opb.init(B, ldb, n0, (BKM ? (long)K : (long)N) * ldb * 2, wave, lane, wn * (BN / WN));
+    lp.opa.init(A, lda, m0, (AK ? (long)K : (long)M) * lda * 2, wave, lane, wm * (BM / WM), 0);
+    lp.opb.init(B, ldb, n0, (BKM ? (long)K : (long)N) * ldb * 2, wave, lane, wn * (BN / WN), lp.B_RING);
 
     f32x4 acc[T][T];
 #pragma unroll
@@ -349,65 +498,53 @@ __device__ __forceinline__ void gemm_tile(
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
 
-    unsigned char OB_LDS *s0 = (unsigned char OB_LDS *)st0;
-    unsigned char OB_LDS *s1 = (unsigned char OB_LDS *)st1;
-    // a slice covers K steps [k_first, k_first + nk)
+    unsigned char OB_LDS *ring = (unsigned char OB_LDS *)ring_mem;
+    // a slice covers K steps [k_first, k_first + nk); two ring slots to the K step
     const int k_first = kz * ts.k_chunk;
-    const int nk = sliced ? min(ts.k_chunk, (K + BK - 1) / BK - k_first) : (K + BK - 1) / BK;
+    const int nk = sliced ? min(ts.k_chunk, (K + KSTEP - 1) / KSTEP - k_first) : (K + KSTEP - 1) / KSTEP;
     lp.opa.skip(k_first);
     lp.opb.skip(k_first);
-    lp.k_left = nk;
-    // prologue: K step 0 into stage 0; K step 1 requested, the copy groups that follow a barrier
-    // delivered to stage 1 and re-requested for K step 2: the state behind the barrier of a K step
-    lp.next_k();
+    lp.ka_left = AK ? 2 * nk : nk;
+    lp.kb_left = BKM ? 2 * nk : nk;
+    lp.prologue(ring);
+    __builtin_amdgcn_s_waitcnt(waitcnt(lp.VM_PENDING == 63 ? 63 : T * (NS - 1) - 1, 0));
+    wg_barrier();
 #pragma unroll
-    for (int g = 0; g < C::G; ++g) lp.request(g);
+    for (int j = 0; j < T; ++j) lp.bfr[0][j] = lp.b_frag(ring, 0, j);
 #pragma unroll
-    for (int g = 0; g < C::G; ++g) lp.deliver(s0, g);
-    lp.next_k();
-#pragma unroll
-    for (int g = 0; g < C::G; ++g) lp.request(g);
-    lp.next_k();
-#pragma unroll
-    for (int g = T + 1; g < C::G; ++g) {
-        lp.deliver(s1, g);
-        lp.request(g);
-    }
-    __builtin_amdgcn_s_waitcnt(0xC07F);
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < T; ++j) lp.bfr[0][j] = lp.b_frag(s0, j, 0);
-#pragma unroll
-    for (int i = 0; i < T - 1; ++i) lp.af[i] = lp.a_frag(s0, i, 0);
+    for (int i = 0; i < T - 1; ++i) lp.af[i] = lp.a_frag(ring, 0, i);
 
-    // two K steps per trip: a single straight path with immediate stage addresses.  There is no
+    // once round the ring per trip: a single straight path with immediate LDS addresses.  There is no
     // separate tail (several ways into the epilogue make the register allocator move the
-    // accumulators between homes): the last K step also reads ahead and copies (fragments that
-    // are never used, zeros from past the end of K), and an odd count of K steps is rounded up
-    // with a K step of zeros.
-    for (int kt = 0; kt < nk; kt += 2) {
-        lp.template stage<true>(acc, s0, s1);
-        lp.template stage<true>(acc, s1, s0);
+    // accumulators between homes): the last slots also read ahead and load (fragments that are never
+    // used, zeros from past the end of K), and the count of slots is rounded up to whole trips with
+    // slots of zeros.
+    for (int kt = 0; kt < 2 * nk; kt += NS) {
+        lp.template slot<0>(acc, ring);
+        lp.template slot<1>(acc, ring);
+        lp.template slot<2>(acc, ring);
+        lp.template slot<3>(acc, ring);
     }
+    static_assert(NS == 4, "the trip above names the slots");
 
     // the MFMAs above are opaque to the compiler's hazard handling: let the last ones retire before
     // the accumulators are read
     asm volatile("s_nop 15");
     asm volatile("s_nop 15");
-    // every wave is done reading the last stage and writing the other one; then the stages serve as
-    // transposition slabs.  A lane holds, per MFMA tile, output row m = lane % 16 and columns
+    // every wave is done reading the ring and every load still in flight has landed in it (zeros from
+    // past the end of K); then the ring serves as transposition slabs.  A lane holds, per MFMA tile, output row m = lane % 16 and columns
     // n = 4 (lane / 16) + (0..3): stored directly, every lane of a store would touch a different
     // cache line.  Each wave writes two tile rows (32 output rows) to its slab as fp32 and reads
     // them back so that 16 (or 8) consecutive lanes cover one contiguous row segment; bias and
     // residual are added on the way out, then one rounding to bf16.
-    __builtin_amdgcn_s_waitcnt(0xC07F);
+    __builtin_amdgcn_s_waitcnt(waitcnt(0, 0));
     __syncthreads();
     constexpr int CW = BN / WN;            // columns of the wave's tile
     constexpr int RSTR = CW * 4 + 16;      // fp32 row stride in LDS, padded against bank conflicts
     constexpr int LPR = CW / 8;            // lanes per row on the way out (8 columns each)
     constexpr int RPI = 64 / LPR;          // rows per read instruction
-    static_assert(32 * RSTR <= C::STAGE / (C::NW / 2), "slab does not fit the wave's LDS share");
-    unsigned char OB_LDS *slab = (wave < C::NW / 2 ? s0 : s1) + (wave % (C::NW / 2)) * (C::STAGE / (C::NW / 2));
+    static_assert(32 * RSTR <= NS * C::SLOT / C::NW, "slab does not fit the wave's LDS share");
+    unsigned char OB_LDS *slab = ring + wave * (NS * C::SLOT / C::NW);
     const int lx = lane & 15, lq = lane >> 4;
     const int n_out = n0 + wn * CW + (lane % LPR) * 8;
     float bv[8];
@@ -643,7 +780,7 @@ double estimate_us(bool big, int nk, double n_full, double n_tail, int splits, i
 Plan make_plan(int M, int N, int K, bool can_split) {
     const int big = ((M + 255) / 256) * ((N + 255) / 256);
     const int small = ((M + 127) / 128) * ((N + 127) / 128);
-    const int nk = (K + BK - 1) / BK;
+    const int nk = (K + KSTEP - 1) / KSTEP;
     const double t_big = estimate_us(true, nk, 0, big, 1, 0), t_small = estimate_us(false, nk, 0, small, 1, 0);
     const bool use_big = t_big <= t_small;
     Plan p{use_big, use_big ? big : small, 0, 1, 0};
@@ -692,7 +829,7 @@ void launch_layout(int M, int N, int K, const void *A, int lda, const void *B, i
 // A group of "TN" GEMMs over one K, 256 x 256 tiles: the whole tiles of the full rounds of the combined
 // list, then the slices of its tail (same rule and estimate as for a single GEMM).
 Plan make_group_plan(int total_tiles, int K) {
-    const int nk = (K + BK - 1) / BK, slots = compute_units();
+    const int nk = (K + KSTEP - 1) / KSTEP, slots = compute_units();
     const int n_tail = total_tiles % slots, n_full = total_tiles - n_tail;
     Plan p{true, total_tiles, 0, 1, 0};
     if (n_tail == 0 || nk < 16) return p;
@@ -738,7 +875,7 @@ size_t gemm_tn_group_workspace_bytes(int count, const GemmTN *g, int K) {
 
 int gemm_tn_group(int count, const GemmTN *g, int K, void *ws, size_t ws_bytes, hipStream_t s) {
     if (count < 1 || count > GemmGroup::MAX) return fail(OB_EINVAL, "gemm group: %d members", count);
-    const int nk = (K + BK - 1) / BK;
+    const int nk = (K + KSTEP - 1) / KSTEP;
     GemmGroup grp{};
     grp.n = count;
     double t_single = 0.0, flops = 0.0;
