@@ -16,10 +16,11 @@
 //  * a K-major operand ([k][rows], as it lies in memory: B of "NN", both of "TN") goes global -> LDS
 //    directly (buffer loads that write to LDS, one per run of 8 MFMAs, NS - 2 slots ahead of its use)
 //    and its fragments come out of transposing LDS reads, so dgrad and wgrad need no re-layout pass;
-//  * a K-contiguous operand ([row][k]: A of "NT" and "NN", B of "NT") goes global -> registers -> LDS in
-//    whole 128-byte rows, two slots at a time (straight to LDS it would fetch every cache line twice),
-//    each vector written to LDS one K step after it was requested, so no wait ever meets a load in
-//    flight; a fragment is one 16-byte LDS read;
+//  * a K-contiguous operand ([row][k]: A of "NT" and "NN", B of "NT") moves in whole 128-byte rows, two
+//    slots at a time (a slot at a time it would fetch every cache line twice); a fragment is one
+//    16-byte LDS read.  A goes global -> LDS directly as well, over a ring of three pairs of slots: 160 KB
+//    of LDS hold that and 64 KB for B.  B of "NT" has its two pairs and goes global -> registers -> LDS,
+//    each vector written to LDS one K step after it was requested, so no wait meets a load in flight;
 //  * the descriptor arithmetic of the next slot is a dozen scalar instructions dealt over the gaps of
 //    one run (left to the compiler it was some 35 instructions with 64-bit vector compares in one
 //    place, 5 % of the loop).
@@ -106,14 +107,15 @@ struct Cfg {
 //   i.e. 4 consecutive k of one x.  The four groups of a read sit at k, k + 8, k + 16, k + 24 over
 //   the same x; the second swizzle term puts any two of them that could be served together 32 bytes
 //   apart.
-// KMAJOR = false: the source is [X, K] with k contiguous.  Straight to LDS, a load could fill 16 rows of
-//   one slot, 64 bytes of each: half a cache line, whose other half the load for the next slot
-//   would fetch again once the line has left the first-level cache (measured: a quarter slower than
-//   whole lines).  So this operand's slots come in pairs, [x][8 chunks of 16 B] (64 k), the chunk c of
-//   row x at position c ^ row_swizzle(x), and go global -> registers -> LDS a pair at a time: one load
-//   takes 8 rows of 128 bytes, and one K step later each lane writes its 16 bytes, lane-linear inside
-//   the 1 KB piece (the swizzle was applied by the choice of each lane's global address).  A fragment
-//   is one 16-byte read per lane, from the chunks 0-3 (even slot) or 4-7 (odd slot).
+// KMAJOR = false: the source is [X, K] with k contiguous.  A load that filled 16 rows of one slot would
+//   take 64 bytes of each: half a cache line, whose other half the load for the next slot would
+//   fetch again once the line has left the first-level cache (measured: a quarter slower than whole
+//   lines).  So this operand's slots come in pairs, [x][8 chunks of 16 B] (64 k), the chunk c of row x
+//   at position c ^ row_swizzle(x), filled a pair at a time: one load takes 8 rows of 128 bytes and
+//   lands lane-linear in a 1 KB piece (the swizzle is applied by the choice of each lane's global
+//   address), either straight in LDS or in registers, from where each lane writes its 16 bytes one
+//   K step later.  A fragment is one 16-byte read per lane, from the chunks 0-3 (even slot) or 4-7
+//   (odd slot).
 template <int X, int NW, int T, bool KMAJOR>
 struct Operand {
     static constexpr int LD = KMAJOR ? X / 16 / NW : X / 8 / NW;   // loads per wave: per slot / per two slots
@@ -210,8 +212,12 @@ struct Operand {
     __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, unsigned char OB_LDS *__restrict__ dst, int wave, int p) const {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void OB_LDS *)(dst + (wave * LD + p) * 1024), 16, voff[p], 0, 0, 0);
     }
-    // k-contiguous: piece p (8 rows of 64 k) of this wave's share of the pair of slots behind `rsrc`:
-    // global -> registers (rows beyond M / N deliver zeros), and registers -> the pair at `dst`
+    // k-contiguous: piece p (8 rows of 64 k) of this wave's share of the pair of slots behind `rsrc`
+    // (rows beyond M / N deliver zeros), either global -> the pair at `dst` (this operand's region included)
+    __device__ __forceinline__ void load_pair(__amdgpu_buffer_rsrc_t rsrc, unsigned char OB_LDS *__restrict__ dst, int wave, int p) const {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void OB_LDS *)(dst + (wave * LD + p) * 1024), 16, voff[p], 0, 0, 0);
+    }
+    // or global -> registers, and registers -> the pair `pair_bytes` into the region
     __device__ __forceinline__ void request(__amdgpu_buffer_rsrc_t rsrc, int p) {
         v[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[p], 0, 0);
     }
@@ -265,10 +271,12 @@ constexpr int waitcnt(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) |
 //  * a k-major operand refills, for NS slots ahead, the slot whose last reader has passed the barrier
 //    behind run 0: its T / 2 loads go straight to LDS, from run 1 on (A first; with both operands k-major
 //    the last load of B falls into run 0 of the slot after);
-//  * a k-contiguous operand refills two slots at a time, T pieces that were requested one K step
-//    before: between the barrier of an odd slot, when both slots of the pair before are free, and the
-//    barrier two slots on, behind which the first of them is read again, there are 2 T runs; a
-//    piece is written to LDS in one of them and requested again, for one K step further on.
+//  * a k-contiguous operand refills two slots at a time, T pieces: between the barrier of an odd slot,
+//    when both slots of a pair are free, and the barrier two slots on there are 2 T runs, and each
+//    piece has one of them.  B's piece, requested one K step before, is written to LDS there and
+//    requested again for one K step further on (its pair is the one read next but one).  A's piece is
+//    loaded straight to LDS, into the pair freed last, for three K steps further on: A has a third
+//    pair, so that its loads have two slots to land as well.
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 struct KLoop {
     using C = Cfg<BM, BN, WM, WN>;
@@ -304,14 +312,22 @@ struct KLoop {
         next_part<3>();
         rb = rb_n;
     }
-    // The ring holds A's NS slots, then B's: a k-major operand's one after the other, a k-contiguous
-    // one's in pairs.  Fragment i of operand A (j of B) out of the slot in ring position S:
-    static constexpr int A_SLOT = BM * ROW_BYTES, B_SLOT = BN * ROW_BYTES, B_RING = NS * A_SLOT;
-    __device__ __forceinline__ bf16x8 a_frag(const unsigned char OB_LDS *__restrict__ ring, int S, int i) const {
-        return opa.frag(ring + (AK ? S : S & ~1) * A_SLOT, i, S & 1);       // (the operand's offsets start at its region)
+    // The ring holds A's slots, then B's: a k-major operand's NS one after the other, a k-contiguous
+    // one's in pairs; B's two pairs (filled through registers), A's three (filled straight from memory,
+    // which needs the room of one more pair for the loads on their way; 160 KB of LDS hold one such
+    // ring next to a 64 KB one).  A's pairs are used in turn, which does not go into the four slots of
+    // a trip: where k-contiguous A is read and filled are run-time offsets.
+    static constexpr int A_SLOT = BM * ROW_BYTES, B_SLOT = BN * ROW_BYTES, A_PAIRS = 3;
+    static constexpr int A_BYTES = AK ? NS * A_SLOT : A_PAIRS * 2 * A_SLOT, RING_BYTES = A_BYTES + NS * B_SLOT;
+    static constexpr int A_BASE = AK ? 0 : NS * B_SLOT, B_BASE = AK ? A_BYTES : 0;   // (transposing reads stay in the lower 128 KB)
+    int a_cur, a_nxt, a_fill;                    // k-contiguous A: the pair of the slot at hand, of the one after, the one being filled
+    // fragment i of operand A (j of B) out of the slot in ring position S (`own`: the slot at hand, else the one after it)
+    __device__ __forceinline__ bf16x8 a_frag(const unsigned char OB_LDS *__restrict__ ring, int S, int i, bool own) const {
+        if (AK) return opa.frag(ring + S * A_SLOT, i, 0);
+        return opa.frag(ring + (own || (S & 1) ? a_cur : a_nxt), i, S & 1);
     }
     __device__ __forceinline__ bf16x8 b_frag(const unsigned char OB_LDS *__restrict__ ring, int S, int j) const {
-        return opb.frag(ring + (BKM ? S : S & ~1) * B_SLOT, j, S & 1);
+        return opb.frag(ring + (BKM ? S : S & ~1) * B_SLOT, j, S & 1);       // (the operand's offsets start at its region)
     }
     // Position of run g of slot S among the 2 T runs between the barrier of an odd slot and the barrier
     // two slots on: the odd slot's runs 1 .. T-1, the even slot's runs, run 0 of the next odd slot.
@@ -347,9 +363,9 @@ struct KLoop {
             mfma(acc[g][j], bfr[set][j], af[g]);
             __builtin_amdgcn_sched_barrier(0);
             if (g == 0) {
-                if (j == AT_RA) af[T - 1] = a_frag(ring, S, T - 1);
+                if (j == AT_RA) af[T - 1] = a_frag(ring, S, T - 1, true);
                 // the last load of the slot before, when both operands go straight to LDS
-                if (AK && BKM && j == 2) opb.load(rb, ring + B_RING + P * B_SLOT, wave, T / 2 - 1);
+                if (AK && BKM && j == 2) opb.load(rb, ring + B_BASE + P * B_SLOT, wave, T / 2 - 1);
                 // descriptors: a k-major operand moves on every slot, a k-contiguous one every other
                 if (AK || (S & 1)) {
                     if (j == (AK && BKM ? 0 : 2)) next_part<0>();
@@ -361,19 +377,16 @@ struct KLoop {
                 }
             } else {
                 if (j == AT_RB) bfr[set ^ 1][g] = b_frag(ring, N, g);
-                if (j == AT_RA) af[g - 1] = a_frag(ring, N, g - 1);
+                if (j == AT_RA) af[g - 1] = a_frag(ring, N, g - 1, false);
                 if (j == AT_RX && g == 1) bfr[set ^ 1][0] = b_frag(ring, N, 0);
                 if (j == AT_RQ) {
-                    if (AK && g - 1 < T / 2) opa.load(ra, ring + S * A_SLOT, wave, g - 1);
-                    if (BKM && !AK && g - 1 < T / 2) opb.load(rb, ring + B_RING + S * B_SLOT, wave, g - 1);
-                    if (BKM && AK && g - 1 >= T / 2) opb.load(rb, ring + B_RING + S * B_SLOT, wave, g - 1 - T / 2);
+                    if (AK && g - 1 < T / 2) opa.load(ra, ring + A_BASE + S * A_SLOT, wave, g - 1);
+                    if (BKM && !AK && g - 1 < T / 2) opb.load(rb, ring + B_BASE + S * B_SLOT, wave, g - 1);
+                    if (BKM && AK && g - 1 >= T / 2) opb.load(rb, ring + B_BASE + S * B_SLOT, wave, g - 1 - T / 2);
                 }
             }
+            if (pa >= 0 && j == AT_RQ) opa.load_pair(ra, ring + A_BASE + a_fill, wave, pa);
             // (in run 0 the write goes first: the barrier behind the run waits for it)
-            if (pa >= 0) {
-                if (j == (g == 0 ? 0 : AT_DL)) opa.deliver(ring, pair * 2 * A_SLOT, pa);
-                if (j == AT_RQ) opa.request(ra, pa);
-            }
             if (pb >= 0) {
                 if (j == (g == 0 ? 0 : AT_DL)) opb.deliver(ring, pair * 2 * B_SLOT, pb);
                 if (j == AT_RQ) opb.request(rb, pb);
@@ -383,7 +396,14 @@ struct KLoop {
         if (g == 0) {
             if (AK || (S & 1)) ra = ra_n;
             if (BKM || (S & 1)) rb = rb_n;
+            // behind the barrier of an odd slot its pair is free: the runs from here on fill it, and
+            // read the pair after it
+            if (!AK && (S & 1)) {
+                a_fill = a_cur;
+                a_nxt = a_cur == (A_PAIRS - 1) * 2 * A_SLOT ? 0 : a_cur + 2 * A_SLOT;
+            }
         }
+        if (!AK && (S & 1) && g == T - 1) a_cur = a_nxt;
     }
     template <int S, int g>
     __device__ __forceinline__ void runs_from(f32x4 (&acc)[T][T], unsigned char OB_LDS *__restrict__ ring) {
@@ -393,57 +413,73 @@ struct KLoop {
         }
     }
     // the loads of at most this many slots, the newest, may still be on their way at a barrier
-    static constexpr int VM_PENDING = (AK && BKM) ? T * (NS - 2) : BKM ? T * (NS - 2) + T / 2 : 63;
+    static constexpr int VM_PENDING = T * (NS - 2);
     // The slot in ring position S.  On entry bfr[S & 1] and af[0 .. T-2] hold its fragments; on return
     // those of the slot after.
     template <int S>
     __device__ __forceinline__ void slot(f32x4 (&acc)[T][T], unsigned char OB_LDS *__restrict__ ring) {
         run<S, 0>(acc, ring);
         // own reads of this slot and own writes to LDS landed, own loads to the slot after in LDS (every
-        // run issues one load; the last one to the slot after went out NS - 2 slots ago, T / 2 runs
-        // more when it was B's last with A k-contiguous), then the barrier: the slot after is complete
-        // and nobody reads this one any more
+        // run issues one load, and the last one to the slot after went out NS - 2 slots ago or earlier),
+        // then the barrier: the slot after is complete and nobody reads this one any more
         __builtin_amdgcn_s_waitcnt(waitcnt(VM_PENDING, 0));
         wg_barrier();
         runs_from<S, 1>(acc, ring);
     }
-    // Before the first slot: the ring filled as the loop expects to find it.  k-major: the first NS
-    // slots requested, all but what run 0 of the first slot issues.  k-contiguous: the first two pairs
-    // of slots, the second one as far as the runs in front of the loop's first would have written it
-    // (positions 0 .. T-2), and those pieces requested again for the pair after.
+    // Before the first slot: the ring filled as the loop expects to find it, what the first slot needs
+    // requested first.  k-major: the first NS slots, all but what run 0 of the first slot issues.
+    // k-contiguous A: the first two pairs and of the third what the runs in front of the loop's first
+    // would have asked for (positions 0 .. T-2).  k-contiguous B: the first pair written, the second as
+    // far as those runs would have written it, and these pieces requested again for the pair after.
+    // prologue_later(): the number of loads it issues after the last one that the first slot needs.
+    static constexpr int prologue_later() {
+        int n = 0;
+        for (int q = 0; q < T - 1; ++q) n += (piece_a(q) >= 0 ? 1 : 0) + (piece_b(q) >= 0 ? 1 : 0);
+        n += AK ? (NS - 1) * T / 2 : T;
+        n += BKM ? (NS - 1) * T / 2 - (AK ? 1 : 0) : T;
+        return n;
+    }
     __device__ __forceinline__ void prologue(unsigned char OB_LDS *__restrict__ ring) {
+        next_a();
 #pragma unroll
-        for (int sl = 0; sl < NS; ++sl) {
+        for (int p = 0; p < (AK ? T / 2 : T); ++p) {
+            if (AK) opa.load(ra, ring + A_BASE, wave, p);
+            else opa.load_pair(ra, ring + A_BASE, wave, p);
+        }
+        next_b();
+#pragma unroll
+        for (int p = 0; p < (BKM ? T / 2 : T); ++p) {
+            if (BKM) opb.load(rb, ring + B_BASE, wave, p);
+            else opb.request(rb, p);
+        }
+        // the rest in the order of its use: a barrier of the loop waits for all but a fixed number of
+        // the newest loads
+#pragma unroll
+        for (int sl = 1; sl < NS; ++sl) {
             if (AK) {
                 next_a();
 #pragma unroll
-                for (int p = 0; p < T / 2; ++p) opa.load(ra, ring + sl * A_SLOT, wave, p);
+                for (int p = 0; p < T / 2; ++p) opa.load(ra, ring + A_BASE + sl * A_SLOT, wave, p);
             }
             if (BKM) {
                 next_b();
 #pragma unroll
                 for (int p = 0; p < T / 2; ++p)
-                    if (!(AK && sl == NS - 1 && p == T / 2 - 1)) opb.load(rb, ring + B_RING + sl * B_SLOT, wave, p);
+                    if (!(AK && sl == NS - 1 && p == T / 2 - 1)) opb.load(rb, ring + B_BASE + sl * B_SLOT, wave, p);
             }
-        }
-        if (!AK) {
-            next_a();
+            if (!AK && sl == 1) {
+                next_a();
 #pragma unroll
-            for (int p = 0; p < T; ++p) opa.request(ra, p);
-        }
-        if (!BKM) {
-            next_b();
-#pragma unroll
-            for (int p = 0; p < T; ++p) opb.request(rb, p);
-        }
-        if (!AK) {
-            next_a();
-#pragma unroll
-            for (int p = 0; p < T; ++p) {
-                opa.deliver(ring, 0, p);
-                opa.request(ra, p);
+                for (int p = 0; p < T; ++p) opa.load_pair(ra, ring + A_BASE + 2 * A_SLOT, wave, p);
             }
-            next_a();
+            if (!AK && sl == NS - 1) {
+                next_a();
+#pragma unroll
+                for (int q = 0; q < T - 1; ++q)
+                    if (piece_a(q) >= 0) opa.load_pair(ra, ring + A_BASE + 4 * A_SLOT, wave, piece_a(q));
+                a_cur = a_nxt = 0;
+                a_fill = 4 * A_SLOT;
+            }
         }
         if (!BKM) {
             next_b();
@@ -453,17 +489,12 @@ struct KLoop {
                 opb.request(rb, p);
             }
             next_b();
-        }
 #pragma unroll
-        for (int q = 0; q < T - 1; ++q) {
-            if (piece_a(q) >= 0) {
-                opa.deliver(ring, 2 * A_SLOT, piece_a(q));
-                opa.request(ra, piece_a(q));
-            }
-            if (piece_b(q) >= 0) {
-                opb.deliver(ring, 2 * B_SLOT, piece_b(q));
-                opb.request(rb, piece_b(q));
-            }
+            for (int q = 0; q < T - 1; ++q)
+                if (piece_b(q) >= 0) {
+                    opb.deliver(ring, 2 * B_SLOT, piece_b(q));
+                    opb.request(rb, piece_b(q));
+                }
         }
     }
 };
@@ -477,7 +508,7 @@ __device__ __forceinline__ void gemm_tile(
     const __bf16 *R, int ldr, int tile_m, int tile_n, bool sliced, int kz, int tail_tile, const TailSplit &ts) {
     using C = Cfg<BM, BN, WM, WN>;
     constexpr int T = C::T;
-    __shared__ __attribute__((aligned(1024))) unsigned char ring_mem[NS * C::SLOT];
+    __shared__ __attribute__((aligned(1024))) unsigned char ring_mem[KLoop<BM, BN, WM, WN, AK, BKM>::RING_BYTES];
     const int m0 = __builtin_amdgcn_readfirstlane(tile_m) * BM;
     const int n0 = __builtin_amdgcn_readfirstlane(tile_n) * BN;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -487,8 +518,8 @@ __device__ __forceinline__ void gemm_tile(
     KLoop<BM, BN, WM, WN, AK, BKM> lp;
     lp.wave = wave;
     lp.lane = lane;
-    lp.opa.init(A, lda, m0, (AK ? (long)K : (long)M) * lda * 2, wave, lane, wm * (BM / WM), 0);
-    lp.opb.init(B, ldb, n0, (BKM ? (long)K : (long)N) * ldb * 2, wave, lane, wn * (BN / WN), lp.B_RING);
+    lp.opa.init(A, lda, m0, (AK ? (long)K : (long)M) * lda * 2, wave, lane, wm * (BM / WM), lp.A_BASE);
+    lp.opb.init(B, ldb, n0, (BKM ? (long)K : (long)N) * ldb * 2, wave, lane, wn * (BN / WN), lp.B_BASE);
 
     f32x4 acc[T][T];
 #pragma unroll
@@ -507,12 +538,13 @@ __device__ __forceinline__ void gemm_tile(
     lp.ka_left = AK ? 2 * nk : nk;
     lp.kb_left = BKM ? 2 * nk : nk;
     lp.prologue(ring);
-    __builtin_amdgcn_s_waitcnt(waitcnt(lp.VM_PENDING == 63 ? 63 : T * (NS - 1) - 1, 0));
+    constexpr int later = KLoop<BM, BN, WM, WN, AK, BKM>::prologue_later();
+    __builtin_amdgcn_s_waitcnt(waitcnt(later < 63 ? later : 63, 0));
     wg_barrier();
 #pragma unroll
     for (int j = 0; j < T; ++j) lp.bfr[0][j] = lp.b_frag(ring, 0, j);
 #pragma unroll
-    for (int i = 0; i < T - 1; ++i) lp.af[i] = lp.a_frag(ring, 0, i);
+    for (int i = 0; i < T - 1; ++i) lp.af[i] = lp.a_frag(ring, 0, i, true);
 
     // once round the ring per trip: a single straight path with immediate LDS addresses.  There is no
     // separate tail (several ways into the epilogue make the register allocator move the
