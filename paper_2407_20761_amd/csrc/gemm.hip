@@ -10,17 +10,19 @@
 // 1725-1790 TFLOP/s on random data.
 //
 // A wave has its SIMD to itself, so every instruction that is not an MFMA takes an issue slot that
-// only the gaps between MFMAs can hide (three per gap), and what moves data costs more than its slot:
-// a 16-byte-per-lane LDS write holds the issue back for as long as its kilobyte takes to leave the
-// registers.  Hence
-//  * a K-major operand ([k][rows], as it lies in memory: B of "NN", both of "TN") goes global -> LDS
-//    directly (buffer loads that write to LDS, one per run of 8 MFMAs, NS - 2 slots ahead of its use)
+// only the gaps between MFMAs can hide (three per gap), and what moves data through registers costs
+// more than its slot: a 16-byte-per-lane LDS write holds the issue back for as long as its kilobyte
+// takes to leave the registers (with both operands staged through registers the loop ran 7 - 12 %
+// longer).  Hence
+//  * every tile goes global -> LDS directly (buffer loads that write to LDS), one load per run of
+//    8 MFMAs, issued one to two slots before its use;
+//  * a K-major operand ([k][rows], as it lies in memory: B of "NN", both of "TN") has four slots of 32 k
 //    and its fragments come out of transposing LDS reads, so dgrad and wgrad need no re-layout pass;
 //  * a K-contiguous operand ([row][k]: A of "NT" and "NN", B of "NT") moves in whole 128-byte rows, two
 //    slots at a time (a slot at a time it would fetch every cache line twice); a fragment is one
-//    16-byte LDS read.  A goes global -> LDS directly as well, over a ring of three pairs of slots: 160 KB
-//    of LDS hold that and 64 KB for B.  B of "NT" has its two pairs and goes global -> registers -> LDS,
-//    each vector written to LDS one K step after it was requested, so no wait meets a load in flight;
+//    16-byte LDS read.  A has a ring of three such pairs of slots, so its loads have two slots to land;
+//    B of "NT" has two (160 KB of LDS hold 96 + 64 KB), its loads go out as soon as the barrier has
+//    freed their pair and have a slot and a half;
 //  * the descriptor arithmetic of the next slot is a dozen scalar instructions dealt over the gaps of
 //    one run (left to the compiler it was some 35 instructions with 64-bit vector compares in one
 //    place, 5 % of the loop).
@@ -112,10 +114,9 @@ struct Cfg {
 //   fetch again once the line has left the first-level cache (measured: a quarter slower than whole
 //   lines).  So this operand's slots come in pairs, [x][8 chunks of 16 B] (64 k), the chunk c of row x
 //   at position c ^ row_swizzle(x), filled a pair at a time: one load takes 8 rows of 128 bytes and
-//   lands lane-linear in a 1 KB piece (the swizzle is applied by the choice of each lane's global
-//   address), either straight in LDS or in registers, from where each lane writes its 16 bytes one
-//   K step later.  A fragment is one 16-byte read per lane, from the chunks 0-3 (even slot) or 4-7
-//   (odd slot).
+//   lands lane-linear in a 1 KB piece of LDS (the swizzle is applied by the choice of each lane's
+//   global address).  A fragment is one 16-byte read per lane, from the chunks 0-3 (even slot) or
+//   4-7 (odd slot).
 template <int X, int NW, int T, bool KMAJOR>
 struct Operand {
     static constexpr int LD = KMAJOR ? X / 16 / NW : X / 8 / NW;   // loads per wave: per slot / per two slots
@@ -126,8 +127,6 @@ struct Operand {
     uint32_t num;                                // checked range of the one at hand
     uint32_t voff[LD];
     int rd[KMAJOR ? T : 2];                      // LDS read offsets (from the ring's start): per tile i (k-major) / per slot of the pair
-    int wr;                                      // k-contiguous: LDS write offset of this lane in piece 0 of pair 0
-    u32x4 v[KMAJOR ? 1 : LD];                    // k-contiguous: the loads on their way
 
     // k-contiguous layout.  The LDS serves a 16-byte read 16 lanes at a time (measured with a probe
     // of lane pairs): within each half of the wavefront, first the lanes whose index bits 2, 3, 4 have
@@ -154,7 +153,6 @@ struct Operand {
             const int lx = lane & 15, lq = lane >> 4;
 #pragma unroll
             for (int h = 0; h < 2; ++h) rd[h] = region + (wave_x0 + lx) * 2 * ROW_BYTES + (((4 * h + lq) ^ row_swizzle(lx)) * 16);
-            wr = region + wave * LD * 1024 + lane * 16;
         } else {
             set((const unsigned char *)(src + x0), total_bytes - (long)x0 * 2, (uint32_t)BK * (uint32_t)ld * 2u, 0);
             constexpr int KPB = 1024 / ROWB, CPR = ROWB / 16;
@@ -172,7 +170,6 @@ struct Operand {
                 const int chunk = (wave_x0 + 16 * i) / 8 + (c >> 1);
                 rd[i] = region + (8 * b + kq) * ROWB + ((chunk ^ (4 * kq) ^ (2 * ((b ^ (b >> 1)) & 1))) * 16) + (c & 1) * 8;
             }
-            wr = 0;
         }
     }
     // the contraction starts `first` steps into the source (all arguments uniform)
@@ -213,16 +210,9 @@ struct Operand {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void OB_LDS *)(dst + (wave * LD + p) * 1024), 16, voff[p], 0, 0, 0);
     }
     // k-contiguous: piece p (8 rows of 64 k) of this wave's share of the pair of slots behind `rsrc`
-    // (rows beyond M / N deliver zeros), either global -> the pair at `dst` (this operand's region included)
+    // (rows beyond M / N deliver zeros): global -> the pair at `dst` (this operand's region included)
     __device__ __forceinline__ void load_pair(__amdgpu_buffer_rsrc_t rsrc, unsigned char OB_LDS *__restrict__ dst, int wave, int p) const {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (void OB_LDS *)(dst + (wave * LD + p) * 1024), 16, voff[p], 0, 0, 0);
-    }
-    // or global -> registers, and registers -> the pair `pair_bytes` into the region
-    __device__ __forceinline__ void request(__amdgpu_buffer_rsrc_t rsrc, int p) {
-        v[p] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff[p], 0, 0);
-    }
-    __device__ __forceinline__ void deliver(unsigned char OB_LDS *__restrict__ ring, int pair_bytes, int p) const {
-        *(u32x4 OB_LDS *)(ring + wr + pair_bytes + p * 1024) = v[p];
     }
     // fragment for MFMA tile i (16 x-values) out of the slot at `tile` (k-contiguous: slot h of the
     // pair at `tile`)
@@ -271,12 +261,11 @@ constexpr int waitcnt(int vm, int lgkm) { return (vm & 15) | ((vm >> 4) << 14) |
 //  * a k-major operand refills, for NS slots ahead, the slot whose last reader has passed the barrier
 //    behind run 0: its T / 2 loads go straight to LDS, from run 1 on (A first; with both operands k-major
 //    the last load of B falls into run 0 of the slot after);
-//  * a k-contiguous operand refills two slots at a time, T pieces: between the barrier of an odd slot,
-//    when both slots of a pair are free, and the barrier two slots on there are 2 T runs, and each
-//    piece has one of them.  B's piece, requested one K step before, is written to LDS there and
-//    requested again for one K step further on (its pair is the one read next but one).  A's piece is
-//    loaded straight to LDS, into the pair freed last, for three K steps further on: A has a third
-//    pair, so that its loads have two slots to land as well.
+//  * a k-contiguous operand refills two slots at a time, T loads, straight to LDS as well: between the
+//    barrier of an odd slot, when both slots of a pair are free, and the barrier two slots on there
+//    are 2 T runs.  A has three pairs: the pair freed last is filled for three K steps further on, so
+//    any of those runs will do.  B has two: the pair freed is the one read next but one, so its loads
+//    go out in the odd slot's own runs and the barrier two slots on waits for them.
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
 struct KLoop {
     using C = Cfg<BM, BN, WM, WN>;
@@ -313,10 +302,9 @@ struct KLoop {
         rb = rb_n;
     }
     // The ring holds A's slots, then B's: a k-major operand's NS one after the other, a k-contiguous
-    // one's in pairs; B's two pairs (filled through registers), A's three (filled straight from memory,
-    // which needs the room of one more pair for the loads on their way; 160 KB of LDS hold one such
-    // ring next to a 64 KB one).  A's pairs are used in turn, which does not go into the four slots of
-    // a trip: where k-contiguous A is read and filled are run-time offsets.
+    // one's in pairs: B's two, A's three (160 KB of LDS hold 64 + 96 KB).  A's pairs are used in turn,
+    // which does not go into the four slots of a trip: where k-contiguous A is read and filled are
+    // run-time offsets.
     static constexpr int A_SLOT = BM * ROW_BYTES, B_SLOT = BN * ROW_BYTES, A_PAIRS = 3;
     static constexpr int A_BYTES = AK ? NS * A_SLOT : A_PAIRS * 2 * A_SLOT, RING_BYTES = A_BYTES + NS * B_SLOT;
     static constexpr int A_BASE = AK ? 0 : NS * B_SLOT, B_BASE = AK ? A_BYTES : 0;   // (transposing reads stay in the lower 128 KB)
@@ -332,17 +320,19 @@ struct KLoop {
     // Position of run g of slot S among the 2 T runs between the barrier of an odd slot and the barrier
     // two slots on: the odd slot's runs 1 .. T-1, the even slot's runs, run 0 of the next odd slot.
     static constexpr int position(int S, int g) { return (S & 1) ? (g == 0 ? 2 * T - 1 : g - 1) : T - 1 + g; }
-    // the piece of a k-contiguous operand that the run at position q carries (-1: none): with both
-    // operands k-contiguous A takes the even positions and B the odd ones; next to a k-major operand,
-    // whose loads sit in runs 1 .. T/2 of every slot, the other runs
+    // the piece of k-contiguous A that the run at position q loads (-1: none): next to k-contiguous B
+    // the even slot's runs; next to k-major B, whose loads sit in runs 1 .. T/2 of every slot, the
+    // other runs
     static constexpr int piece_a(int q) {
         if (AK) return -1;
-        if (!BKM) return (q & 1) ? -1 : q / 2;
+        if (!BKM) return q >= T - 1 && q < 2 * T - 1 ? q - (T - 1) : -1;         // the even slot's runs
         return q >= T / 2 && q < T ? q - T / 2 : (q >= T + T / 2 ? q - T : -1);
     }
+    // (B k-contiguous: A is as well, there is no layout with A alone k-major.)  B's pieces go out in the
+    // odd slot's runs 1 .. T-1, as early as its pair is free, the last one as a second load of run 1
     static constexpr int piece_b(int q) {
         if (BKM) return -1;
-        return (q & 1) ? q / 2 : -1;             // (A is k-contiguous as well: there is no layout with A alone k-major)
+        return q < T - 1 ? q : -1;
     }
     // the pair of slots (0: slots 0 and 1; 1: slots 2 and 3) that the runs of slot S refill
     static constexpr int pair_of(int S, int g) { return (S & 1) ? (g == 0 ? ((S + 1) / 2) & 1 : (S - 1) / 2) : ((S / 2) + 1) & 1; }
@@ -386,11 +376,8 @@ struct KLoop {
                 }
             }
             if (pa >= 0 && j == AT_RQ) opa.load_pair(ra, ring + A_BASE + a_fill, wave, pa);
-            // (in run 0 the write goes first: the barrier behind the run waits for it)
-            if (pb >= 0) {
-                if (j == (g == 0 ? 0 : AT_DL)) opb.deliver(ring, pair * 2 * B_SLOT, pb);
-                if (j == AT_RQ) opb.request(rb, pb);
-            }
+            if (pb >= 0 && j == AT_RQ) opb.load_pair(rb, ring + B_BASE + pair * 2 * B_SLOT, wave, pb);
+            if (pb == 0 && j == AT_DL + 1) opb.load_pair(rb, ring + B_BASE + pair * 2 * B_SLOT, wave, T - 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (g == 0) {
@@ -413,7 +400,9 @@ struct KLoop {
         }
     }
     // the loads of at most this many slots, the newest, may still be on their way at a barrier
-    static constexpr int VM_PENDING = T * (NS - 2);
+    // (both operands k-contiguous: at the barrier of an odd slot, behind which B's pair filled two slots
+    // before is read, the T loads of A since; at that of an even slot nothing new is read)
+    static constexpr int vm_pending(int S) { return AK || BKM ? T * (NS - 2) : (S & 1) ? T : 63; }
     // The slot in ring position S.  On entry bfr[S & 1] and af[0 .. T-2] hold its fragments; on return
     // those of the slot after.
     template <int S>
@@ -422,21 +411,21 @@ struct KLoop {
         // own reads of this slot and own writes to LDS landed, own loads to the slot after in LDS (every
         // run issues one load, and the last one to the slot after went out NS - 2 slots ago or earlier),
         // then the barrier: the slot after is complete and nobody reads this one any more
-        __builtin_amdgcn_s_waitcnt(waitcnt(VM_PENDING, 0));
+        __builtin_amdgcn_s_waitcnt(waitcnt(vm_pending(S), 0));
         wg_barrier();
         runs_from<S, 1>(acc, ring);
     }
     // Before the first slot: the ring filled as the loop expects to find it, what the first slot needs
     // requested first.  k-major: the first NS slots, all but what run 0 of the first slot issues.
-    // k-contiguous A: the first two pairs and of the third what the runs in front of the loop's first
-    // would have asked for (positions 0 .. T-2).  k-contiguous B: the first pair written, the second as
-    // far as those runs would have written it, and these pieces requested again for the pair after.
+    // k-contiguous B: its two pairs.  k-contiguous A: the first two pairs and of the third what the runs
+    // in front of the loop's first would have asked for (positions 0 .. T-2).
     // prologue_later(): the number of loads it issues after the last one that the first slot needs.
     static constexpr int prologue_later() {
+        if (!AK && !BKM) return 2 * T;
         int n = 0;
-        for (int q = 0; q < T - 1; ++q) n += (piece_a(q) >= 0 ? 1 : 0) + (piece_b(q) >= 0 ? 1 : 0);
+        for (int q = 0; q < T - 1; ++q) n += piece_a(q) >= 0 ? 1 : 0;
         n += AK ? (NS - 1) * T / 2 : T;
-        n += BKM ? (NS - 1) * T / 2 - (AK ? 1 : 0) : T;
+        n += (NS - 1) * T / 2 - (AK ? 1 : 0);
         return n;
     }
     __device__ __forceinline__ void prologue(unsigned char OB_LDS *__restrict__ ring) {
@@ -450,7 +439,7 @@ struct KLoop {
 #pragma unroll
         for (int p = 0; p < (BKM ? T / 2 : T); ++p) {
             if (BKM) opb.load(rb, ring + B_BASE, wave, p);
-            else opb.request(rb, p);
+            else opb.load_pair(rb, ring + B_BASE, wave, p);
         }
         // the rest in the order of its use: a barrier of the loop waits for all but a fixed number of
         // the newest loads
@@ -467,6 +456,11 @@ struct KLoop {
                 for (int p = 0; p < T / 2; ++p)
                     if (!(AK && sl == NS - 1 && p == T / 2 - 1)) opb.load(rb, ring + B_BASE + sl * B_SLOT, wave, p);
             }
+            if (!BKM && sl == 1) {
+                next_b();
+#pragma unroll
+                for (int p = 0; p < T; ++p) opb.load_pair(rb, ring + B_BASE + 2 * B_SLOT, wave, p);
+            }
             if (!AK && sl == 1) {
                 next_a();
 #pragma unroll
@@ -480,21 +474,6 @@ struct KLoop {
                 a_cur = a_nxt = 0;
                 a_fill = 4 * A_SLOT;
             }
-        }
-        if (!BKM) {
-            next_b();
-#pragma unroll
-            for (int p = 0; p < T; ++p) {
-                opb.deliver(ring, 0, p);
-                opb.request(rb, p);
-            }
-            next_b();
-#pragma unroll
-            for (int q = 0; q < T - 1; ++q)
-                if (piece_b(q) >= 0) {
-                    opb.deliver(ring, 2 * B_SLOT, piece_b(q));
-                    opb.request(rb, piece_b(q));
-                }
         }
     }
 };
