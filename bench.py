@@ -582,8 +582,9 @@ def bench_config(config, steps, warmup, seed, spread_batches, full, cpu_baseline
                 "achieved": g_ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": g_ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(config, "gemm"),
                 "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, copy-calibrated)",
-                "traffic_source": "profiles/hbm_traffic.txt, last changed at commit " +
-                                  str(git_describe("profiles/hbm_traffic.txt")),
+                "traffic_source": "profiles/hbm_traffic.txt: the committed summary of an earlier rocprofv3 counter run, "
+                                  "not measured by this run" +
+                                  (lambda c: f" (last changed at commit {c})" if c else "")(git_describe("profiles/hbm_traffic.txt")),
                 # the 12 GEMMs of a block go out as 12 launches, or fewer when weight gradients are grouped
                 "algorithmic_bytes_per_launch": alg_bytes / (gcnt / (steps * L)),
                 "launches_per_block": gcnt / (steps * L),
