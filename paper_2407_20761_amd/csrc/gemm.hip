@@ -274,7 +274,7 @@ struct KLoop {
     Operand<BN, C::NW, T, BKM> opb;
     __amdgpu_buffer_rsrc_t ra, rb, ra_n, rb_n;
     int ka_left, kb_left;                        // slots (k-major) / pairs of slots (k-contiguous) not yet described
-    int wave, lane;
+    int wave;
     bf16x8 af[T], bfr[2][T];
 
     // the descriptors of the next slot (pair), in four parts; ra_n, rb_n take over at commit()
@@ -496,7 +496,6 @@ __device__ __forceinline__ void gemm_tile(
 
     KLoop<BM, BN, WM, WN, AK, BKM> lp;
     lp.wave = wave;
-    lp.lane = lane;
     lp.opa.init(A, lda, m0, (AK ? (long)K : (long)M) * lda * 2, wave, lane, wm * (BM / WM), lp.A_BASE);
     lp.opb.init(B, ldb, n0, (BKM ? (long)K : (long)N) * ldb * 2, wave, lane, wn * (BN / WN), lp.B_BASE);
 
