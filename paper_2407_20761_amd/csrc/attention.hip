@@ -94,9 +94,17 @@ struct Tile {
         const uint64_t b = (uint64_t)base;
         const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
         const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
-        const long cl = bytes_left < 0 ? 0 : (bytes_left > 0xFFFFFFFFl ? 0xFFFFFFFFl : bytes_left);
+        // the checked range: bytes_left clamped to [0, 2^32 - 1], in scalar instructions (the compiler's own
+        // 64-bit compares go through the vector unit)
+        uint32_t num = 0;
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm("s_cmp_eq_u32 %2, 0\n\ts_cselect_b32 %0, %1, -1\n\ts_cmp_lt_i32 %2, 0\n\ts_cselect_b32 %0, 0, %0"
+            : "=&s"(num)
+            : "s"((uint32_t)bytes_left), "s"((int32_t)(bytes_left >> 32))
+            : "scc");
+#endif
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (void *)(((uint64_t)hi << 32) | lo), 0, (int)__builtin_amdgcn_readfirstlane((uint32_t)cl), 0x00020000);
+            (void *)(((uint64_t)hi << 32) | lo), 0, (int)num, 0x00020000);
 #pragma unroll
         for (int p = 0; p < LD; ++p)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst + (wave * LD + p) * 1024, 16, voff[p], 0, 0, 0);
