@@ -182,27 +182,28 @@ struct Operand {
     __device__ __forceinline__ void skip(int ksteps) {
         set((const unsigned char *)base, left, step, KMAJOR ? 2 * ksteps : ksteps);
     }
-    // Descriptor of the slot (pair) at hand, then on to the next one, in two parts (to be placed between
-    // different pairs of MFMAs).  The range a descriptor can check is 32 bits wide: a source with more
-    // than 4 GB left is clamped (no access of a slot reaches that far from the base), one past its
-    // end is empty, and so is any slot when k_left < 1 (every load returns zeros without touching
-    // memory).  Written as scalar instructions: the compiler's own 64-bit compares go through the
-    // vector unit, a few dozen instructions per slot that a wave alone on its SIMD cannot hide.
-    __device__ __forceinline__ void next_range(int k_left) {
+    // Descriptor of the slot (pair) at hand, then on to the next one, in five steps of two to four scalar
+    // instructions (to be placed between different pairs of MFMAs).  The range a descriptor can check is
+    // 32 bits wide: a source with more than 4 GB left is clamped (no access of a slot reaches that far
+    // from the base), one past its end is empty, and so is any slot when k_left < 1 (every load
+    // returns zeros without touching memory).  Written as scalar instructions: the compiler's own
+    // 64-bit compares go through the vector unit, a few dozen instructions per slot that a wave alone
+    // on its SIMD cannot hide.
+    template <int STEP>
+    __device__ __forceinline__ void next_step(int k_left, __amdgpu_buffer_rsrc_t &r) {
 #if defined(__HIP_DEVICE_COMPILE__)
-        asm("s_cmp_eq_u32 %2, 0\n\ts_cselect_b32 %0, %1, -1\n\t"
-            "s_cmp_lt_i32 %2, 0\n\ts_cselect_b32 %0, 0, %0\n\t"
-            "s_cmp_gt_i32 %3, 0\n\ts_cselect_b32 %0, %0, 0"
-            : "=&s"(num)
-            : "s"((uint32_t)left), "s"((int32_t)(left >> 32)), "s"(k_left)
-            : "scc");
+        if (STEP == 0)
+            asm("s_cmp_eq_u32 %2, 0\n\ts_cselect_b32 %0, %1, -1"
+                : "=s"(num) : "s"((uint32_t)left), "s"((int32_t)(left >> 32)) : "scc");
+        if (STEP == 1)
+            asm("s_cmp_lt_i32 %1, 0\n\ts_cselect_b32 %0, 0, %0" : "+s"(num) : "s"((int32_t)(left >> 32)) : "scc");
+        if (STEP == 2) asm("s_cmp_gt_i32 %1, 0\n\ts_cselect_b32 %0, %0, 0" : "+s"(num) : "s"(k_left) : "scc");
 #endif
-    }
-    __device__ __forceinline__ __amdgpu_buffer_rsrc_t next() {
-        const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)num, 0x00020000);
-        base += step;
-        left -= step;
-        return r;
+        if (STEP == 3) r = __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)num, 0x00020000);
+        if (STEP == 4) {
+            base += step;
+            left -= step;
+        }
     }
     // k-major: piece p (1 KB per wave) of this wave's share of the slot behind `rsrc`: global -> LDS,
     // lane i to byte 16 i of the piece; lanes past the end of the source (rows beyond K) deliver zeros
@@ -277,28 +278,35 @@ struct KLoop {
     int wave;
     bf16x8 af[T], bfr[2][T];
 
-    // the descriptors of the next slot (pair), in four parts; ra_n, rb_n take over at commit()
-    template <int PART>
-    __device__ __forceinline__ void next_part() {
-        if (PART == 0) opa.next_range(ka_left);
-        if (PART == 1) {
-            ra_n = opa.next();
-            --ka_left;
-        }
-        if (PART == 2) opb.next_range(kb_left);
-        if (PART == 3) {
-            rb_n = opb.next();
-            --kb_left;
-        }
+    // The descriptors of the next slot (pair), ten steps (five per operand, see Operand::next_step); ra_n
+    // and rb_n take over behind run 0 of the slot they are for.
+    template <int STEP>
+    __device__ __forceinline__ void next_step() {
+        if (STEP < 5) opa.template next_step<STEP>(ka_left, ra_n);
+        else opb.template next_step<STEP - 5>(kb_left, rb_n);
+        if (STEP == 4) --ka_left;
+        if (STEP == 9) --kb_left;
+    }
+    __device__ __forceinline__ void prepare_a() {
+        next_step<0>();
+        next_step<1>();
+        next_step<2>();
+        next_step<3>();
+        next_step<4>();
+    }
+    __device__ __forceinline__ void prepare_b() {
+        next_step<5>();
+        next_step<6>();
+        next_step<7>();
+        next_step<8>();
+        next_step<9>();
     }
     __device__ __forceinline__ void next_a() {
-        next_part<0>();
-        next_part<1>();
+        prepare_a();
         ra = ra_n;
     }
     __device__ __forceinline__ void next_b() {
-        next_part<2>();
-        next_part<3>();
+        prepare_b();
         rb = rb_n;
     }
     // The ring holds A's slots, then B's: a k-major operand's NS one after the other, a k-contiguous
@@ -356,15 +364,9 @@ struct KLoop {
                 if (j == AT_RA) af[T - 1] = a_frag(ring, S, T - 1, true);
                 // the last load of the slot before, when both operands go straight to LDS
                 if (AK && BKM && j == 2) opb.load(rb, ring + B_BASE + P * B_SLOT, wave, T / 2 - 1);
-                // descriptors: a k-major operand moves on every slot, a k-contiguous one every other
-                if (AK || (S & 1)) {
-                    if (j == (AK && BKM ? 0 : 2)) next_part<0>();
-                    if (j == (T >= 8 ? 3 : 2)) next_part<1>();
-                }
-                if (BKM || (S & 1)) {
-                    if (j == (T >= 8 ? 5 : 3)) next_part<2>();
-                    if (j == T - 1) next_part<3>();
-                }
+                // (small tiles: the descriptors of this slot's loads are worked out here, see below)
+                if (T < 8 && (AK || (S & 1)) && j == 0) prepare_a();
+                if (T < 8 && (BKM || (S & 1)) && j == 2) prepare_b();
             } else {
                 if (j == AT_RB) bfr[set ^ 1][g] = b_frag(ring, N, g);
                 if (j == AT_RA) af[g - 1] = a_frag(ring, N, g - 1, false);
@@ -373,6 +375,27 @@ struct KLoop {
                     if (AK && g - 1 < T / 2) opa.load(ra, ring + A_BASE + S * A_SLOT, wave, g - 1);
                     if (BKM && !AK && g - 1 < T / 2) opb.load(rb, ring + B_BASE + S * B_SLOT, wave, g - 1);
                     if (BKM && AK && g - 1 >= T / 2) opb.load(rb, ring + B_BASE + S * B_SLOT, wave, g - 1 - T / 2);
+                }
+            }
+            // Descriptors: a k-major operand moves on every slot, a k-contiguous one every other, behind run 0.
+            // The ten steps of working the next ones out are dealt over the gaps of runs 2 - 4 of the slot
+            // before that no memory instruction uses (a wave alone on its SIMD has three issue slots per gap).
+            if (T >= 8 && g >= 2 && g <= 4 && (j == 3 || j == 4 || j == 5 || j == 7)) {
+                constexpr int first = (g - 2) * 4;
+                const int step_no = first + (j == 7 ? 3 : j - 3);
+                if (AK || !(S & 1)) {
+                    if (step_no == 0) next_step<0>();
+                    if (step_no == 1) next_step<1>();
+                    if (step_no == 2) next_step<2>();
+                    if (step_no == 3) next_step<3>();
+                    if (step_no == 4) next_step<4>();
+                }
+                if (BKM || !(S & 1)) {
+                    if (step_no == 5) next_step<5>();
+                    if (step_no == 6) next_step<6>();
+                    if (step_no == 7) next_step<7>();
+                    if (step_no == 8) next_step<8>();
+                    if (step_no == 9) next_step<9>();
                 }
             }
             if (pa >= 0 && j == AT_RQ) opa.load_pair(ra, ring + A_BASE + a_fill, wave, pa);
@@ -475,6 +498,10 @@ struct KLoop {
                 a_fill = 4 * A_SLOT;
             }
         }
+        // what runs 2 - 4 of the slot before the first would have left: the descriptors that take over
+        // behind run 0 of the first slot
+        if (T >= 8 && AK) prepare_a();
+        if (T >= 8 && BKM) prepare_b();
     }
 };
 
