@@ -393,36 +393,36 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
 }
 
 // out[c] = (accumulate ? out[c] : 0) + sum_p partial[p * stride + c]; fixed summation order.
-// A workgroup owns 32 columns; its 8 groups of 32 lanes each sum every 8th partial (four
-// independent chains per lane to keep loads in flight), then the 8 sums are combined in LDS.
+// A workgroup owns 32 columns; its RG groups of 32 lanes each sum every RG-th partial (eight
+// independent chains per lane to keep loads in flight: the kernel is a chain of dependent memory
+// latencies, a few hundred partials deep), then the RG sums are combined in LDS.
+constexpr int REDUCE_THREADS = 512, RG = REDUCE_THREADS / 32;
 __device__ __forceinline__ void reduce_columns(const float *__restrict__ partial, int n_part, int stride,
                                                __bf16 *__restrict__ out, int C, int accumulate) {
-    __shared__ float red[8][32];
+    __shared__ float red[RG][32];
     const int col = threadIdx.x & 31, pl = threadIdx.x >> 5;
     const int c = blockIdx.x * 32 + col;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (c < C) {
         int p = pl;
-        for (; p + 24 < n_part; p += 32) {
-            s0 += partial[(size_t)p * stride + c];
-            s1 += partial[(size_t)(p + 8) * stride + c];
-            s2 += partial[(size_t)(p + 16) * stride + c];
-            s3 += partial[(size_t)(p + 24) * stride + c];
+        for (; p + 7 * RG < n_part; p += 8 * RG) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s[u] += partial[(size_t)(p + u * RG) * stride + c];
         }
-        for (; p < n_part; p += 8) s0 += partial[(size_t)p * stride + c];
+        for (; p < n_part; p += RG) s[0] += partial[(size_t)p * stride + c];
     }
-    red[pl][col] = (s0 + s1) + (s2 + s3);
+    red[pl][col] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
     __syncthreads();
     if (pl == 0 && c < C) {
-        float s = 0.f;
+        float t = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s += red[i][col];
-        if (accumulate) s += (float)out[c];
-        out[c] = (__bf16)s;
+        for (int i = 0; i < RG; ++i) t += red[i][col];
+        if (accumulate) t += (float)out[c];
+        out[c] = (__bf16)t;
     }
 }
 
-__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial,
+__global__ __launch_bounds__(REDUCE_THREADS) void reduce_partials_kernel(const float *__restrict__ partial,
                                                               int n_part, int stride,
                                                               __bf16 *__restrict__ out, int C,
                                                               int accumulate) {
@@ -430,7 +430,7 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
 }
 
 // the reductions of one block's backward pass in one launch: blockIdx.y picks the job
-__global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch b, int accumulate) {
+__global__ __launch_bounds__(REDUCE_THREADS) void reduce_batch_kernel(ReduceBatch b, int accumulate) {
     const ReduceJob j = b.job[blockIdx.y];
     if ((int)blockIdx.x * 32 >= j.C) return;
     reduce_columns(j.partial, j.n_part, j.stride, (__bf16 *)j.out, j.C, accumulate);
@@ -665,7 +665,7 @@ void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats
 void launch_reduce_partials(const float *partial, int n_part, int stride, void *out, int C,
                             int accumulate, hipStream_t s) {
     ProfScope prof(K_REDUCE, s, 4.0 * n_part * C);
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C + 31) / 32), dim3(256), 0, s, partial, n_part,
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((C + 31) / 32), dim3(REDUCE_THREADS), 0, s, partial, n_part,
                        stride, (__bf16 *)out, C, accumulate);
 }
 
@@ -679,7 +679,7 @@ int launch_reduce_batch(const ReduceBatch &b, int accumulate, hipStream_t s) {
         if (b.job[i].C > max_c) max_c = b.job[i].C;
     }
     ProfScope prof(K_REDUCE, s, work);
-    hipLaunchKernelGGL(reduce_batch_kernel, dim3((max_c + 31) / 32, b.n), dim3(256), 0, s, b, accumulate);
+    hipLaunchKernelGGL(reduce_batch_kernel, dim3((max_c + 31) / 32, b.n), dim3(REDUCE_THREADS), 0, s, b, accumulate);
     return OB_OK;
 }
 
