@@ -795,8 +795,11 @@ __device__ __forceinline__ void issue_row_stats(const float *base, long floats_l
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst, 4, lane * 4, 0, 0, 0);
 }
 
+// pairs of waves per workgroup of the dK / dV kernel, each owning 32 key rows: with D = 64 a wave needs few
+// enough registers for three on a SIMD, so six pairs (192 key rows) share every streamed tile
+constexpr int dkv_pairs(int d) { return d == 64 ? 6 : 4; }
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
+__global__ __launch_bounds__(128 * dkv_pairs(D)) void attn_bwd_dkv_kernel(
     const __bf16 *__restrict__ d_o, const __bf16 *__restrict__ q, const __bf16 *__restrict__ k,
     const __bf16 *__restrict__ v, const float *__restrict__ lse2_all, const float *__restrict__ delta,
     __bf16 *__restrict__ dk, __bf16 *__restrict__ dv, int ldq, int ldkv, int ldo,
@@ -805,18 +808,19 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
     // three stages of the streamed Q and dO tiles (the dK side works one tile behind the dV side, see
     // below), two buffers for the probabilities on their way from one to the other, row statistics
     __shared__ __attribute__((aligned(1024))) unsigned char tiles_s[6 * Tile<D>::BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char p_s[2 * 4 * 4096];  // [buffer][pair]: 4 x 64 lanes x 16 B
+    constexpr int NP = dkv_pairs(D), KVT = 32 * NP;                              // pairs; key rows of the workgroup
+    __shared__ __attribute__((aligned(1024))) unsigned char p_s[2 * NP * 4096];  // [buffer][pair]: 4 x 64 lanes x 16 B
     __shared__ __attribute__((aligned(256))) float stat_s[6 * ST];              // lse2 x 3 stages, Delta x 3 stages
     __shared__ int sh[8];
     const int rank = blockIdx.x / heads;
-    const TileInfo ti = pick_tile(ord, rank, cu, n_seg, QT, sh);
+    const TileInfo ti = pick_tile(ord, rank, cu, n_seg, KVT, sh);
     if (ti.row0 < 0) return;
     // one workgroup per key/value head: the group's query heads run one after another
     const int kvh = head_of_slot(blockIdx.x - rank * heads, heads);
     const int lane = threadIdx.x & 63, lx = lane & 31, lh = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int pair = wave & 3;
-    const bool role_g = wave >= 4;  // false: S, P, dV;  true: dP, dS, dK
+    const bool role_g = wave >= NP;  // false: S, P, dV;  true: dP, dS, dK
+    const int pair = role_g ? wave - NP : wave;
     const int kv_row = min(ti.row0 + pair * 32 + lx, ti.seg_end - 1);
     const bool kv_live = ti.row0 + pair * 32 + lx < ti.seg_end;
     const int pair_kv_first = ti.row0 + pair * 32;
@@ -860,13 +864,14 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
         const int head_ = kvh * group + (hq_);                                                                \
         const int q0_ = q_begin + (it_) * ST;                                                                 \
         const long off_ = (long)q0_ * own_ld2 + (long)head_ * D * 2;                                          \
-        tl.issue(own_base + off_, own_total - off_, role_g ? OB_DOS(S) : OB_QS(S), pair);                     \
+        /* four waves of each role copy a tile */                                                            \
+        if (pair < 4) tl.issue(own_base + off_, own_total - off_, role_g ? OB_DOS(S) : OB_QS(S), pair);       \
         if (wave == 0) issue_row_stats(lse2_all + (size_t)head_ * T + q0_, (long)T - q0_, OB_LSES(S), lane);  \
-        if (wave == 4) issue_row_stats(delta + (size_t)head_ * T + q0_, (long)T - q0_, OB_DLTS(S), lane);     \
+        if (wave == NP) issue_row_stats(delta + (size_t)head_ * T + q0_, (long)T - q0_, OB_DLTS(S), lane);    \
     } while (0)
-    // causal: only the first two query tiles touch some pair's diagonal; either way only the last
+    // causal: only the first KVT / ST query tiles touch some pair's diagonal; either way only the last
     // tile can be ragged.  The tiles in between need no mask.
-    const int n_head = CAUSAL ? min(2, n_iter) : 0;
+    const int n_head = CAUSAL ? min(KVT / ST, n_iter) : 0;
     const int n_mid_end = max(n_head, n_iter - (((ti.seg_end - q_begin) % ST) ? 1 : 0));
     // Order of work: first the masked tiles of every query head of the group (phase 0), then the
     // mask-free ones of every head (phase 1) in one single-path loop -- the sums do not care, and one
@@ -918,14 +923,14 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
                 dkv_scores<D>(OB_QS(S), tl, kvf, acc_x);                                                    \
                 dkv_probs<CAUSAL, MASKED>(acc_x, OB_LSES(S), q0, ti.seg_end, kv_row, sl2, pk);              \
                 _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                            \
-                    *(bf16x8 OB_LDS *)(p_mine + (gi & 1) * 16384 + i_ * 1024) = pk[i_ >> 1][i_ & 1];        \
+                    *(bf16x8 OB_LDS *)(p_mine + (gi & 1) * (NP * 4096) + i_ * 1024) = pk[i_ >> 1][i_ & 1];        \
                 dkv_outputs<D>(OB_DOS(S), tl, pk, acc_out);                                                 \
             }                                                                                               \
         } else {                                                                                            \
             if (live_prev) {                                                                                \
                 bf16x8 pk[2][2];                                                                            \
                 _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                            \
-                    pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + ((gi - 1) & 1) * 16384 + i_ * 1024); \
+                    pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + ((gi - 1) & 1) * (NP * 4096) + i_ * 1024); \
                 dkv_dscores(dp_keep, OB_DLTS(PREV), pk);                                                    \
                 dkv_outputs<D>(OB_QS(PREV), tl, pk, acc_out);                                               \
             }                                                                                               \
@@ -958,7 +963,7 @@ __global__ __launch_bounds__(512) void attn_bwd_dkv_kernel(
         bf16x8 pk[2][2];
 #pragma unroll
         for (int i_ = 0; i_ < 4; ++i_)
-            pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + ((gi - 1) & 1) * 16384 + i_ * 1024);
+            pk[i_ >> 1][i_ & 1] = *(const bf16x8 OB_LDS *)(p_mine + ((gi - 1) & 1) * (NP * 4096) + i_ * 1024);
         dkv_dscores(dp_keep, OB_DLTS(p_), pk);
         dkv_outputs<D>(OB_QS(p_), tl, pk, acc_out);
     }
@@ -1101,9 +1106,10 @@ void launch_attn_bwd(const void *d_o, const void *q, const void *k, const void *
     }
     ProfScope prof(K_ATTN_BWD_DKV, s, 1.5 * attn_flops(seg, nq, d, causal));  // dV, dP, dK
     TileOrder ord;
-    make_order(seg, QT, causal, true, tiles, ord);
-    const dim3 grid_kv((unsigned)tiles * nkv);
-    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_kv, 512, (const __bf16 *)d_o, (const __bf16 *)q,
+    const int kvt = 32 * dkv_pairs(d), tiles_kv = count_tiles(seg, kvt);
+    make_order(seg, kvt, causal, true, tiles_kv, ord);
+    const dim3 grid_kv((unsigned)tiles_kv * nkv);
+    OB_ATTN_DISPATCH(attn_bwd_dkv_kernel, grid_kv, 4 * kvt, (const __bf16 *)d_o, (const __bf16 *)q,
                      (const __bf16 *)k, (const __bf16 *)v, lse2, delta, (__bf16 *)dk, (__bf16 *)dv, ldq, ldkv,
                      ldo, seg->cu_dev, seg->n_seg, T, group, scale, rot, nkv, ord);
 }
