@@ -527,13 +527,6 @@ __device__ __forceinline__ void gemm_tile(
     lp.opb.init(B, ldb, n0, (BKM ? (long)K : (long)N) * ldb * 2, wave, lane, wn * (BN / WN), lp.B_BASE);
 
     f32x4 acc[T][T];
-#pragma unroll
-    for (int i = 0; i < T; ++i)
-#pragma unroll
-        for (int j = 0; j < T; ++j)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
-
     unsigned char OB_LDS *ring = (unsigned char OB_LDS *)ring_mem;
     // a slice covers K steps [k_first, k_first + nk); two ring slots to the K step
     const int k_first = kz * ts.k_chunk;
@@ -543,6 +536,16 @@ __device__ __forceinline__ void gemm_tile(
     lp.ka_left = AK ? 2 * nk : nk;
     lp.kb_left = BKM ? 2 * nk : nk;
     lp.prologue(ring);
+    // the accumulators are cleared while the first loads are on their way (the empty statement pins the 256
+    // moves here: left alone they sink behind the wait for those loads)
+#pragma unroll
+    for (int i = 0; i < T; ++i)
+#pragma unroll
+        for (int j = 0; j < T; ++j) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+            asm volatile("" : "+a"(acc[i][j]));
+        }
     constexpr int later = KLoop<BM, BN, WM, WN, AK, BKM>::prologue_later();
     __builtin_amdgcn_s_waitcnt(waitcnt(later < 63 ? later : 63, 0));
     wg_barrier();
