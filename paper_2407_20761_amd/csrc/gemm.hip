@@ -35,6 +35,7 @@
 // consecutive output columns; the epilogue transposes them through LDS into full-row stores.
 #include <algorithm>
 #include <cmath>
+#include <type_traits>
 
 #include "ob_internal.h"
 
@@ -595,39 +596,72 @@ __device__ __forceinline__ void gemm_tile(
 #pragma unroll
         for (int e = 0; e < 8; ++e) bv[e] = (float)b8[e];
     }
-#pragma unroll
-    for (int ii = 0; ii < T / 2; ++ii) {
+    auto put = [&](int ii) {   // tile rows 2 ii and 2 ii + 1 of the wave into its slab
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int j = 0; j < T; ++j)
                 *(f32x4 OB_LDS *)(slab + (16 * h + lx) * RSTR + (j * 16 + lq * 4) * 4) = acc[2 * ii + h][j];
+    };
+    // One straight path per kind of output (MODE 0: bf16; 1: bf16 with the residual added; 2: the fp32 sums
+    // of a slice, the whole tile: sums beyond M and N are never read by tail_sum_kernel) and per kind of
+    // tile (CHECK: some rows or columns lie past M or N): with the choices inside the loop every row read
+    // was a round trip to LDS of its own.  All reads of a pair of tile rows are issued together; the next
+    // pair is written to the slab behind them (a wave's LDS accesses execute in order) while the rows
+    // just read are rounded and stored.
+    auto out = [&](auto mode, auto check) {
+        constexpr int MODE = decltype(mode)::value;
+        constexpr bool CHECK = decltype(check)::value;
+        constexpr int NR = 32 / RPI;
+        put(0);
 #pragma unroll
-        for (int r = 0; r < 32 / RPI; ++r) {
-            const int row = r * RPI + lane / LPR;
-            const f32x4 lo = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32);
-            const f32x4 hi = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32 + 16);
-            const int m = m0 + wm * (BM / WM) + ii * 32 + row;
-            if (sliced) {   // the whole tile; sums beyond M and N are never read by tail_sum_kernel
-                float *dst = ts.part + ((size_t)(kz * ts.n_tail + tail_tile) * BM + (m - m0)) * BN + (n_out - n0);
-                *(f32x4 *)dst = lo;
-                *(f32x4 *)(dst + 4) = hi;
-            } else if (m < M && n_out < N) {
-                float o8[8];
+        for (int ii = 0; ii < T / 2; ++ii) {
+            f32x4 lo[NR], hi[NR];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) { o8[e] = lo[e] + bv[e]; o8[4 + e] = hi[e] + bv[4 + e]; }
-                if (R) {
-                    const bf16x8 r8 = *(const bf16x8 *)(R + (size_t)m * ldr + n_out);
+            for (int r = 0; r < NR; ++r) {
+                const int row = r * RPI + lane / LPR;
+                lo[r] = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32);
+                hi[r] = *(const f32x4 OB_LDS *)(slab + row * RSTR + (lane % LPR) * 32 + 16);
+            }
+            if (ii + 1 < T / 2) put(ii + 1);
+            const int m_first = m0 + wm * (BM / WM) + ii * 32 + lane / LPR;
+            bf16x8 r8[NR];
+            if (MODE == 1) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) o8[e] += (float)r8[e];
+                for (int r = 0; r < NR; ++r)
+                    if (!CHECK || (m_first + r * RPI < M && n_out < N))
+                        r8[r] = *(const bf16x8 *)(R + (size_t)(m_first + r * RPI) * ldr + n_out);
+            }
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                const int m = m_first + r * RPI;
+                if (MODE == 2) {
+                    float *dst = ts.part + ((size_t)(kz * ts.n_tail + tail_tile) * BM + (m - m0)) * BN + (n_out - n0);
+                    *(f32x4 *)dst = lo[r];
+                    *(f32x4 *)(dst + 4) = hi[r];
+                } else if (!CHECK || (m < M && n_out < N)) {
+                    float o8[8];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { o8[e] = lo[r][e] + bv[e]; o8[4 + e] = hi[r][e] + bv[4 + e]; }
+                    if (MODE == 1) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) o8[e] += (float)r8[r][e];
+                    }
+                    bf16x8 o;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) o[e] = (__bf16)o8[e];
+                    __builtin_nontemporal_store(o, (bf16x8 *)(Cm + (size_t)m * ldc + n_out));
                 }
-                bf16x8 o;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[e] = (__bf16)o8[e];
-                __builtin_nontemporal_store(o, (bf16x8 *)(Cm + (size_t)m * ldc + n_out));
             }
         }
-    }
+    };
+    using std::integral_constant;
+    const bool inside = m0 + BM <= M && n0 + BN <= N;
+    if (sliced) out(integral_constant<int, 2>{}, integral_constant<bool, false>{});
+    else if (inside && R) out(integral_constant<int, 1>{}, integral_constant<bool, false>{});
+    else if (inside) out(integral_constant<int, 0>{}, integral_constant<bool, false>{});
+    else if (R) out(integral_constant<int, 1>{}, integral_constant<bool, true>{});
+    else out(integral_constant<int, 0>{}, integral_constant<bool, true>{});
 }
 
 template <int BM, int BN, int WM, int WN, bool AK, bool BKM>
