@@ -46,6 +46,30 @@ constexpr int WAIT_VM0 = 0x0F70;  // s_waitcnt vmcnt(0) only
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// The value of lane l ^ 32, in one vector instruction (v_permlane32_swap exchanges the upper half of its
+// first register with the lower half of its second; given the same value twice, every lane ends up with
+// its own value in one of the two results and its partner's in the other): __shfl_xor goes through the
+// LDS crossbar, a round trip in the middle of the forward's dependent chain maximum -> exponentials.
+__device__ __forceinline__ void both_halves(float x, float &a, float &b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+#else
+    a = b = x;
+#endif
+}
+__device__ __forceinline__ float max_halves(float x) {
+    float a, b;
+    both_halves(x, a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_halves(float x) {
+    float a, b;
+    both_halves(x, a, b);
+    return a + b;
+}
+
 // XOR applied to the 16-byte chunk index of tile row r.  D = 128 (16 chunks per 256-byte row):
 // 16 consecutive rows get 16 different values (conflict-free fragment reads) and the 4 rows of a
 // transposing read differ in bits 2-3 (they land in different 64-byte groups).  D = 64 (8 chunks
@@ -313,7 +337,7 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, acc_s[mt][r]);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_halves(mx);
     // The reference maximum m_run of a row only has to keep the exponentials in range, it need not be
     // the true maximum: it follows the row maximum when that has outgrown it by more than 2^RESCALE_LOG2
     // in some row of the wave (probabilities then reach at most 2^RESCALE_LOG2, harmless in fp32 sums
@@ -373,8 +397,9 @@ __device__ __forceinline__ void fwd_tile(const unsigned char OB_LDS *__restrict_
     l_run += psum;
 }
 
+// (D = 64: 128 registers, four waves on a SIMD)
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
+__global__ __launch_bounds__(256, D == 64 ? 4 : 2) void attn_fwd_kernel(
     const __bf16 *__restrict__ q, const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
     __bf16 *__restrict__ o, float *__restrict__ lse, int ldq, int ldkv, int ldo,
     const int32_t *__restrict__ cu, int n_seg, int T, int group, float scale, int heads, TileOrder ord) {
@@ -454,7 +479,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(
     while (j < n_tiles) OB_FWD_ANY(true)
 #undef OB_FWD_ANY
 #undef OB_FWD_ITER
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = sum_halves(l_run);
     if (!q_live) return;
     const float inv = 1.0f / l_tot;
 #pragma unroll
@@ -608,7 +633,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) dlt += (float)dof[t][e] * (float)of[e];
     }
-    dlt += __shfl_xor(dlt, 32);
+    dlt = sum_halves(dlt);
     if (q_live && lh == 0) {
         lse2_all[(size_t)head * T + q_row] = lse2;
         delta[(size_t)head * T + q_row] = dlt;
