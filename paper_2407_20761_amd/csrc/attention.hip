@@ -124,7 +124,8 @@ struct Tile {
 #if defined(__HIP_DEVICE_COMPILE__)
         asm("s_cmp_eq_u32 %2, 0\n\ts_cselect_b32 %0, %1, -1\n\ts_cmp_lt_i32 %2, 0\n\ts_cselect_b32 %0, 0, %0"
             : "=&s"(num)
-            : "s"((uint32_t)bytes_left), "s"((int32_t)(bytes_left >> 32))
+            : "s"(__builtin_amdgcn_readfirstlane((uint32_t)bytes_left)),
+              "s"(__builtin_amdgcn_readfirstlane((int32_t)(bytes_left >> 32)))
             : "scc");
 #endif
         const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
