@@ -155,7 +155,7 @@ Work work_layout(const Dims &m) {
     w.delta = L.take((size_t)m.nq * T * 4); w.lse2 = L.take((size_t)m.nq * T * 4);
     // fp32 partial sums of the column reductions, one region each: they are all summed by one
     // launch at the end of the backward pass
-    const size_t ncs = colsum_partials(m.T), nnb = norm_bwd_partials(m.T);
+    const size_t ncs = colsum_partials(m.T), nnb = norm_bwd_partials(m.T, m.H);
     // (b_down and b_o: column sums of dy and dx1, left by the second norm's backward next to its own partials)
     w.p_down = L.take(nnb * 2 * m.H * 4); w.p_up = L.take(ncs * m.upF * 4); w.p_o = 0;
     w.p_qkv = L.take(ncs * m.Dqkv * 4); w.p_n2 = L.take(nnb * 2 * m.H * 4); w.p_n1 = L.take(nnb * 2 * m.H * 4);
@@ -384,7 +384,7 @@ extern "C" int ob_block_bwd(const ob_block_desc *desc, const ob_block_weights *w
     unsigned char *d_o = at(ws, wk.d_o), *dqkv = at(ws, wk.dqkv), *gws = at(ws, wk.gemm);
     float *delta = (float *)at(ws, wk.delta);
     const float scale = 1.0f / sqrtf((float)m.d);
-    const int ncs = colsum_partials(m.T), nnb = norm_bwd_partials(m.T);
+    const int ncs = colsum_partials(m.T), nnb = norm_bwd_partials(m.T, m.H);
     int rc;
     ReduceBatch sums;      // the column reductions' second halves, launched together at the end
     auto bias_grad = [&](const void *src, int C, size_t region, void *out) {

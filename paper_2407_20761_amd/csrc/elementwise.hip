@@ -283,17 +283,20 @@ __global__ __launch_bounds__(NORM_THREADS) void norm_bwd_kernel(
     }
 }
 
-// The same backward with one wavefront per row (H <= 64 * 8 * NV): no workgroup barrier anywhere, the
+// The same backward with one wavefront per row (H <= 64 * 8 * NV): no workgroup barrier in the walk, the
 // row sums are wave reductions, and the next row's loads are in flight while the current row is
-// worked on (one wave per SIMD, 24 KB per wave in flight at H = 4096).  Every wave keeps its own
-// column sums and writes its own partial: partial[(blockIdx.x * 4 + wave)][2][H].
-template <bool LAYERNORM, int NV, bool CSUM>
-__global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
+// worked on (24 KB per wave in flight at H = 4096).  Every wave keeps its own column sums.  W = 4: every
+// wave writes its own partial, partial[(blockIdx.x * 4 + wave)][2][H].  W = 8 (narrow rows, where four
+// waves per CU have too few bytes in flight to fill the memory pipes): the workgroup's eight waves add
+// their column sums in LDS, in wave order, and leave ONE partial, partial[blockIdx.x][2][H]: twice the
+// rows in flight for a quarter of the partial sums written here and read again by the final reduction.
+template <bool LAYERNORM, int NV, bool CSUM, int W>
+__global__ __launch_bounds__(64 * W) void norm_bwd_wave_kernel(
     const __bf16 *__restrict__ dh, const __bf16 *__restrict__ x, const float *__restrict__ stats,
     const __bf16 *__restrict__ gamma, const __bf16 *__restrict__ dres, __bf16 *__restrict__ dx,
     float *__restrict__ partial, float *__restrict__ csum, int T, int H) {
     const int nvec = H / 8, lane = threadIdx.x & 63;
-    const int slot = blockIdx.x * 4 + (threadIdx.x >> 6), n_slots = gridDim.x * 4;
+    const int slot = blockIdx.x * W + (threadIdx.x >> 6), n_slots = gridDim.x * W;
     bf16x8 g[NV];
     float dg[NV][8], db[NV][8];
     float sr[CSUM ? NV : 1][8], sx[CSUM ? NV : 1][8];   // column sums of dres and of dx (see norm_bwd_kernel)
@@ -370,25 +373,55 @@ __global__ __launch_bounds__(256) void norm_bwd_wave_kernel(
             }
         }
     }
-    float *pg = partial + (size_t)slot * 2 * H, *pb = pg + H;
+    if constexpr (W == 4) {
+        float *pg = partial + (size_t)slot * 2 * H, *pb = pg + H;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-        const int c = lane + 64 * i;
-        if (c < nvec) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                pg[c * 8 + e] = dg[i][e];
-                pb[c * 8 + e] = db[i][e];
-            }
-            if (CSUM) {
-                float *pr = csum + (size_t)slot * 2 * H, *px = pr + H;
+        for (int i = 0; i < NV; ++i) {
+            const int c = lane + 64 * i;
+            if (c < nvec) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    pr[c * 8 + e] = sr[i][e];
-                    px[c * 8 + e] = sx[i][e];
+                    pg[c * 8 + e] = dg[i][e];
+                    pb[c * 8 + e] = db[i][e];
+                }
+                if (CSUM) {
+                    float *pr = csum + (size_t)slot * 2 * H, *px = pr + H;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        pr[c * 8 + e] = sr[i][e];
+                        px[c * 8 + e] = sx[i][e];
+                    }
                 }
             }
         }
+    } else {
+        constexpr int HMAX = 64 * 8 * NV;
+        __shared__ float red[W][2][HMAX];
+        const int wave = threadIdx.x >> 6;
+        auto fold = [&](const float (&a)[NV][8], const float (&b)[NV][8], float *__restrict__ out) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int c = lane + 64 * i;
+                if (c < nvec) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        red[wave][0][c * 8 + e] = a[i][e];
+                        red[wave][1][c * 8 + e] = b[i][e];
+                    }
+                }
+            }
+            __syncthreads();
+            for (int c = threadIdx.x; c < 2 * H; c += 64 * W) {
+                const int which = c >= H ? 1 : 0, col = c - which * H;
+                float sum = red[0][which][col];
+#pragma unroll
+                for (int w = 1; w < W; ++w) sum += red[w][which][col];
+                out[c] = sum;   // [2][H]
+            }
+            __syncthreads();
+        };
+        fold(dg, db, partial + (size_t)blockIdx.x * 2 * H);
+        if constexpr (CSUM) fold(sr, sx, csum + (size_t)blockIdx.x * 2 * H);
     }
 }
 
@@ -626,14 +659,16 @@ void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *bet
                            (const __bf16 *)gamma, (const __bf16 *)nullptr, (__bf16 *)h, stats, T, H, eps);
 }
 
-int norm_bwd_partials(int T) { return T < 1024 ? T : 1024; }
+// rows of H <= 1024 elements, enough of them: 256 workgroups of eight row-walking waves, one partial each
+static bool norm_bwd_folds(int T, int H) { return H <= 1024 && T >= 2048; }
+int norm_bwd_partials(int T, int H) { return norm_bwd_folds(T, H) ? 256 : T < 1024 ? T : 1024; }
 
-template <int NV>
+template <int NV, int W>
 static void launch_norm_bwd_wave(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
-                                 const void *dres, void *dx, float *partial, float *csum, int T, int H, int nb,
+                                 const void *dres, void *dx, float *partial, float *csum, int T, int H, int wgs,
                                  hipStream_t s) {
 #define OB_NBW(LN, CS)                                                                                          \
-    hipLaunchKernelGGL((norm_bwd_wave_kernel<LN, NV, CS>), dim3(nb / 4), dim3(256), 0, s, (const __bf16 *)dh,    \
+    hipLaunchKernelGGL((norm_bwd_wave_kernel<LN, NV, CS, W>), dim3(wgs), dim3(64 * W), 0, s, (const __bf16 *)dh, \
                        (const __bf16 *)x, stats, (const __bf16 *)gamma, (const __bf16 *)dres, (__bf16 *)dx,     \
                        partial, csum, T, H)
     if (norm == OB_LAYERNORM) { if (csum) OB_NBW(true, true); else OB_NBW(true, false); }
@@ -641,16 +676,20 @@ static void launch_norm_bwd_wave(int norm, const void *dh, const void *x, const 
 #undef OB_NBW
 }
 
-// csum (may be null): [norm_bwd_partials(T)][2][H] fp32, column sums of dres and of dx per partial
+// csum (may be null): [norm_bwd_partials(T, H)][2][H] fp32, column sums of dres and of dx per partial
 void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
                      const void *dres, void *dx, float *partial, int T, int H, hipStream_t s, float *csum) {
     ProfScope prof(K_NORM_BWD, s, 8.0 * T * H);
-    const int nb = norm_bwd_partials(T);
+    const int nb = norm_bwd_partials(T, H);
+    if (norm_bwd_folds(T, H)) {
+        launch_norm_bwd_wave<2, 8>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb, s);
+        return;
+    }
     // a wave per row while a row fits 8 vectors per lane and there are whole workgroups of rows
     if (H <= 4096 && nb % 4 == 0) {
-        if (H <= 1024) launch_norm_bwd_wave<2>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb, s);
-        else if (H <= 2048) launch_norm_bwd_wave<4>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb, s);
-        else launch_norm_bwd_wave<8>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb, s);
+        if (H <= 1024) launch_norm_bwd_wave<2, 4>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb / 4, s);
+        else if (H <= 2048) launch_norm_bwd_wave<4, 4>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb / 4, s);
+        else launch_norm_bwd_wave<8, 4>(norm, dh, x, stats, gamma, dres, dx, partial, csum, T, H, nb / 4, s);
         return;
     }
 #define OB_NB(LN, CS)                                                                                          \

@@ -54,8 +54,8 @@ int gemm_tn_group(int count, const GemmTN *g, int K, void *ws, size_t ws_bytes, 
 void launch_norm_fwd(int norm, const void *x, const void *gamma, const void *beta, void *h,
                      float *stats, int T, int H, float eps, hipStream_t s);
 // dx = dres + norm_bwd(dh); partial [n_part, 2, H] fp32 sums of dgamma / dbeta
-int norm_bwd_partials(int T);
-// csum (may be null): [norm_bwd_partials(T)][2][H] fp32 column sums of dres and of dx (the bias gradients
+int norm_bwd_partials(int T, int H);
+// csum (may be null): [norm_bwd_partials(T, H)][2][H] fp32 column sums of dres and of dx (the bias gradients
 // of the linears on either side of the norm), formed in the same pass
 void launch_norm_bwd(int norm, const void *dh, const void *x, const float *stats, const void *gamma,
                      const void *dres, void *dx, float *partial, int T, int H, hipStream_t s,
