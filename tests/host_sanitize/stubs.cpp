@@ -22,7 +22,7 @@ int gemm_tn_group(int, const GemmTN *, int, void *, size_t, hipStream_t) { OB_ST
 int gemm_any(int, int, int, int, const void *, const void *, void *, const void *, const void *, void *, size_t,
              hipStream_t) { OB_STUB("gemm_any"); }
 void launch_norm_fwd(int, const void *, const void *, const void *, void *, float *, int, int, float, hipStream_t) { OB_STUB("launch_norm_fwd"); }
-int norm_bwd_partials(int T) { return T < 1024 ? T : 1024; }
+int norm_bwd_partials(int T, int H) { return (H <= 1024 && T >= 2048) ? 256 : T < 1024 ? T : 1024; }
 void launch_norm_bwd(int, const void *, const void *, const float *, const void *, const void *, void *, float *, int,
                      int, hipStream_t, float *) { OB_STUB("launch_norm_bwd"); }
 void launch_reduce_partials(const float *, int, int, void *, int, int, hipStream_t) { OB_STUB("launch_reduce_partials"); }
