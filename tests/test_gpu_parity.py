@@ -301,7 +301,8 @@ def test_block_config1_fwd_bwd():
     _check_block(shape, cu, seed=0)
 
 
-@pytest.mark.parametrize("variant", ["llm-like", "llm-many-segments", "vit-like", "vit-d128-rms"])
+@pytest.mark.parametrize("variant", ["llm-like", "llm-many-segments", "vit-like", "vit-d128-rms", "vit-h768-long",
+                                     "llm-h640-long"])
 def test_block_small_variants(variant):
     if variant == "llm-many-segments":
         # more segments than a wavefront has lanes (the rotary kernel's segment lookup and the attention
@@ -315,6 +316,20 @@ def test_block_small_variants(variant):
                                norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
                                use_rotary=True, has_bias=False, norm_eps=1e-6)
         lens = [300, 1, 140, 259]
+    elif variant == "vit-h768-long":
+        # >= 2048 tokens of <= 1024 elements: the norm backward with eight row-walking waves per workgroup
+        # whose column sums (norm parameters, and two bias gradients beside them) are folded in LDS; 96
+        # 16-byte pieces per row, so the lanes' second piece exists only for half of them; tokens odd
+        shape = si.small_shape(hidden=768, n_q_heads=12, n_kv_heads=12, head_dim=64, mlp_dim=512,
+                               norm=si.NORM_LAYERNORM, mlp=si.MLP_GELU, mask=si.MASK_BIDIR,
+                               use_rotary=False, has_bias=True)
+        lens = [1025, 1025, 13]
+    elif variant == "llm-h640-long":
+        # the same path without biases (no sums beside the norm parameters') and with RMSNorm
+        shape = si.small_shape(hidden=640, n_q_heads=5, n_kv_heads=5, head_dim=128, mlp_dim=384,
+                               norm=si.NORM_RMSNORM, mlp=si.MLP_SWIGLU, mask=si.MASK_CAUSAL,
+                               use_rotary=True, has_bias=False, norm_eps=1e-6)
+        lens = [700, 1, 900, 448]
     elif variant == "vit-like":
         shape = si.small_shape(hidden=192, n_q_heads=3, n_kv_heads=3, head_dim=64, mlp_dim=768,
                                norm=si.NORM_LAYERNORM, mlp=si.MLP_GELU, mask=si.MASK_BIDIR,
